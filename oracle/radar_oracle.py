@@ -1,0 +1,179 @@
+"""ctypes wrapper around radar_oracle.c (host only; test infrastructure).
+
+Every function takes numpy arrays, checks shapes and dtypes, and calls the C
+routine of the same name.  bf16 tensors travel as uint16 bit patterns.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "radar_oracle.c")
+_LIB = os.path.join(_HERE, "libradar_oracle.so")
+_lib = None
+
+
+class OracleError(RuntimeError):
+    pass
+
+
+def build(force=False):
+    """Compile radar_oracle.c with gcc into oracle/libradar_oracle.so."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
+        return _LIB
+    cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+           "-o", _LIB, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.radar_oracle_round_bf16.restype = ctypes.c_uint16
+        _lib.radar_oracle_round_bf16.argtypes = [ctypes.c_double]
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _arr(a, dtype, shape=None, name="array"):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    if shape is not None and tuple(a.shape) != tuple(shape):
+        raise OracleError(f"{name}: expected shape {tuple(shape)}, got {tuple(a.shape)}")
+    return a
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise OracleError(f"{what} failed with status {rc}")
+
+
+def num_threads():
+    return int(_load().radar_oracle_num_threads())
+
+
+def set_threads(n):
+    _load().radar_oracle_set_threads(ctypes.c_int(int(n)))
+
+
+def round_bf16(x):
+    """fp64 -> bf16 bit pattern (round to nearest even)."""
+    return int(_load().radar_oracle_round_bf16(ctypes.c_double(float(x))))
+
+
+def tree_attention(q, k_cache, v_cache, parents, ctx_lens, n_nodes=None, scale=None, want_lse=False):
+    """q uint16[B,T,Hq,D]; k_cache, v_cache uint16[B,Hkv,S,D]; parents int32[B,T];
+    ctx_lens int32[B]; n_nodes int32[B] or None.  Returns out uint16[B,T,Hq,D]
+    (and lse float32[B,T,Hq] when want_lse)."""
+    q = _arr(q, np.uint16, name="q")
+    B, T, Hq, D = q.shape
+    k_cache = _arr(k_cache, np.uint16, name="k_cache")
+    _, Hkv, S, _ = k_cache.shape
+    v_cache = _arr(v_cache, np.uint16, (B, Hkv, S, D), "v_cache")
+    k_cache = _arr(k_cache, np.uint16, (B, Hkv, S, D), "k_cache")
+    parents = _arr(parents, np.int32, (B, T), "parents")
+    ctx_lens = _arr(ctx_lens, np.int32, (B,), "ctx_lens")
+    nn = None if n_nodes is None else _arr(n_nodes, np.int32, (B,), "n_nodes")
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    out = np.zeros((B, T, Hq, D), np.uint16)
+    lse = np.zeros((B, T, Hq), np.float32) if want_lse else None
+    rc = _load().radar_oracle_tree_attention(
+        _p(q), _p(k_cache), _p(v_cache), _p(parents), _p(ctx_lens), _p(nn), _p(out), _p(lse),
+        ctypes.c_int(B), ctypes.c_int(T), ctypes.c_int(Hq), ctypes.c_int(Hkv), ctypes.c_int(D),
+        ctypes.c_int(S), ctypes.c_float(scale))
+    _check(rc, "radar_oracle_tree_attention")
+    return (out, lse) if want_lse else out
+
+
+def draft_expand(logits, parent_scores, parent_pool_idx, k, pool, pool_count):
+    """One expansion step.  ``pool`` is a dict of numpy arrays {tokens int32[cap],
+    scores float32[cap], parents int32[cap]} that is appended to in place at
+    pool_count.  Returns a dict with cand_tokens[F,k], cand_scores[F,k],
+    frontier_pool_idx[k], frontier_tokens[k], frontier_scores[k], frontier_conf[k]."""
+    logits = _arr(logits, np.float32, name="logits")
+    F, V = logits.shape
+    parent_scores = _arr(parent_scores, np.float32, (F,), "parent_scores")
+    parent_pool_idx = _arr(parent_pool_idx, np.int32, (F,), "parent_pool_idx")
+    cap = pool["tokens"].shape[0]
+    for key, dt in (("tokens", np.int32), ("scores", np.float32), ("parents", np.int32)):
+        a = pool[key]
+        if a.dtype != dt or not a.flags["C_CONTIGUOUS"] or a.shape != (cap,):
+            raise OracleError(f"pool[{key}] must be contiguous {dt} of shape ({cap},)")
+    res = dict(
+        cand_tokens=np.zeros((F, k), np.int32), cand_scores=np.zeros((F, k), np.float32),
+        frontier_pool_idx=np.zeros(k, np.int32), frontier_tokens=np.zeros(k, np.int32),
+        frontier_scores=np.zeros(k, np.float32), frontier_conf=np.zeros(k, np.float32))
+    rc = _load().radar_oracle_draft_expand(
+        _p(logits), _p(parent_scores), _p(parent_pool_idx),
+        ctypes.c_int(F), ctypes.c_int(V), ctypes.c_int(k), ctypes.c_int(pool_count), ctypes.c_int(cap),
+        _p(res["cand_tokens"]), _p(res["cand_scores"]), _p(res["frontier_pool_idx"]),
+        _p(res["frontier_tokens"]), _p(res["frontier_scores"]), _p(res["frontier_conf"]),
+        _p(pool["tokens"]), _p(pool["scores"]), _p(pool["parents"]))
+    _check(rc, "radar_oracle_draft_expand")
+    return res
+
+
+def draft_rerank(pool, pool_count, N, root_token):
+    """Keep the best N pool entries; returns dict tokens/parents/scores/depth/pool_idx
+    (each N+1 long) and n_nodes."""
+    res = dict(tokens=np.zeros(N + 1, np.int32), parents=np.zeros(N + 1, np.int32),
+               scores=np.zeros(N + 1, np.float32), depth=np.zeros(N + 1, np.int32),
+               pool_idx=np.zeros(N + 1, np.int32))
+    n_out = ctypes.c_int32(0)
+    rc = _load().radar_oracle_draft_rerank(
+        _p(pool["tokens"]), _p(pool["scores"]), _p(pool["parents"]),
+        ctypes.c_int(pool_count), ctypes.c_int(N), ctypes.c_int32(root_token),
+        _p(res["tokens"]), _p(res["parents"]), _p(res["scores"]), _p(res["depth"]), _p(res["pool_idx"]),
+        ctypes.byref(n_out))
+    _check(rc, "radar_oracle_draft_rerank")
+    res["n_nodes"] = int(n_out.value)
+    return res
+
+
+def verify_accept(target_logits, draft_tokens, parents, n_nodes=None, uniforms=None,
+                  mode=0, temperature=1.0, D_max=None):
+    """target_logits float32[B,T,V]; draft_tokens, parents int32[B,T];
+    uniforms float32[B,T+1] for mode 1.  Returns (accept_len[B], path[B,D_max+1], bonus[B])."""
+    target_logits = _arr(target_logits, np.float32, name="target_logits")
+    B, T, V = target_logits.shape
+    draft_tokens = _arr(draft_tokens, np.int32, (B, T), "draft_tokens")
+    parents = _arr(parents, np.int32, (B, T), "parents")
+    nn = None if n_nodes is None else _arr(n_nodes, np.int32, (B,), "n_nodes")
+    un = None if uniforms is None else _arr(uniforms, np.float32, (B, T + 1), "uniforms")
+    if D_max is None:
+        D_max = T - 1
+    accept_len = np.zeros(B, np.int32)
+    path = np.zeros((B, D_max + 1), np.int32)
+    bonus = np.zeros(B, np.int32)
+    rc = _load().radar_oracle_verify_accept(
+        _p(target_logits), _p(draft_tokens), _p(parents), _p(nn), _p(un),
+        ctypes.c_int(B), ctypes.c_int(T), ctypes.c_int(V), ctypes.c_int(D_max), ctypes.c_int(mode),
+        ctypes.c_float(temperature), _p(accept_len), _p(path), _p(bonus))
+    _check(rc, "radar_oracle_verify_accept")
+    return accept_len, path, bonus
+
+
+def accept_margins(target_logits, draft_tokens, parents, n_nodes, uniforms, temperature=1.0):
+    """Distance of every sampling decision from its threshold: float64[B,2]
+    (accept tests, residual inverse-CDF)."""
+    target_logits = _arr(target_logits, np.float32, name="target_logits")
+    B, T, V = target_logits.shape
+    draft_tokens = _arr(draft_tokens, np.int32, (B, T), "draft_tokens")
+    parents = _arr(parents, np.int32, (B, T), "parents")
+    nn = None if n_nodes is None else _arr(n_nodes, np.int32, (B,), "n_nodes")
+    un = _arr(uniforms, np.float32, (B, T + 1), "uniforms")
+    m = np.zeros((B, 2), np.float64)
+    rc = _load().radar_oracle_accept_margins(
+        _p(target_logits), _p(draft_tokens), _p(parents), _p(nn), _p(un),
+        ctypes.c_int(B), ctypes.c_int(T), ctypes.c_int(V), ctypes.c_float(temperature), _p(m))
+    _check(rc, "radar_oracle_accept_margins")
+    return m
