@@ -1,0 +1,234 @@
+/*
+ * radar.h -- C ABI of the MI355X (gfx950) hot path of RADAR's speculative-
+ * sampling loop (arXiv 2512.14069).
+ *
+ * One decode cycle of the paper's pipeline (Sec. 4.1, App. A.1) runs, on the
+ * device, three data-parallel pieces of work that this library provides:
+ *
+ *   radar_draft_expand   after every draft-model call: vocabulary-wide top-k,
+ *                        cumulative log-probability ("confidence") scoring and
+ *                        choice of the next frontier (App. A.1; Sec. 4.2 Eq. 3)
+ *   radar_draft_rerank   when drafting stops: keep the best N candidates and
+ *                        emit the serialized draft tree (Sec. 1, Sec. 2.3)
+ *   radar_tree_attention inside every target layer: each tree node attends to
+ *                        the prefix KV cache plus its own ancestors (Sec. 1,
+ *                        Sec. 3: one parallel target pass over the tree)
+ *   radar_verify_accept  after the target pass: greedy or rejection-sampling
+ *                        walk down the tree (Sec. 3, Eq. 1-2; Sec. 4.3 Eq. 13)
+ *
+ * Conventions for every call
+ *   - Tensor arguments are DEVICE pointers owned by the caller; descriptors
+ *     are HOST structs read during the call; scalars are passed by value.
+ *   - A call validates what the host can see, enqueues its kernels on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream) and returns
+ *     without synchronising.  Outputs are valid once the stream has reached
+ *     the end of the enqueued work.
+ *   - No call allocates or frees memory.  Scratch memory is a caller-owned
+ *     device workspace whose size the matching *_workspace_bytes query gives.
+ *     A workspace must be passed once through radar_workspace_init before its
+ *     first use (its leading bytes hold arrival counters that the kernels leave
+ *     zeroed again); it may then be reused by any sequence of calls on ONE
+ *     stream.  Calls that share a workspace on different streams race.
+ *   - Return value: RADAR_OK or a negative radar_status.  Nothing is printed,
+ *     thrown or aborted.  On an error no kernel has been launched.
+ *   - Device data is not validated (that would need a synchronisation).  The
+ *     kernels stay in bounds and terminate for any content: a parent index
+ *     that is not smaller than its child simply ends that node's ancestor
+ *     chain; token ids outside [0,V) are not dereferenced.
+ *     radar_debug_validate_tree checks a parent array on request.
+ *
+ * Tree convention (the paper leaves it open): a serialized tree has T_max row
+ * slots per sequence of which the first n_nodes[b] are used; node 0 is the
+ * root, i.e. the token the target produced last ("can" in App. A.1), with
+ * parents[0] = -1; for i > 0, 0 <= parents[i] < i.
+ */
+#ifndef RADAR_H
+#define RADAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t radar_status;
+#define RADAR_OK                    0
+#define RADAR_INVALID_ARG          -1   /* null pointer, non-positive size, inconsistent sizes   */
+#define RADAR_UNSUPPORTED_SHAPE    -2   /* outside the compiled limits listed at each call      */
+#define RADAR_WORKSPACE_TOO_SMALL  -3
+#define RADAR_HIP_ERROR            -4   /* a HIP runtime call failed (launch, attribute query)  */
+
+#define RADAR_T_MAX        64    /* most tree rows per sequence (one 64-bit ancestor word)  */
+#define RADAR_K_MAX        16    /* largest branching factor k                              */
+#define RADAR_F_MAX        64    /* most frontier rows per expand call                      */
+#define RADAR_POOL_MAX   4096    /* most pooled candidates radar_draft_rerank accepts       */
+
+/* Text for a status code; never NULL; static storage. */
+const char *radar_status_string(radar_status status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int radar_version(void);
+
+/* Zero a workspace before its first use.  `bytes` is the full size that was
+ * allocated; at least the first 4096 bytes must exist.  Enqueues one kernel. */
+radar_status radar_workspace_init(void *workspace, size_t bytes, void *stream);
+
+/* --------------------------------------------------------------------------
+ * Tree-verify attention (Sec. 1: the tree "is serialized and verified via
+ * masked attention in a single LLM pass"; Sec. 3).
+ *
+ * For sequence b, node i < n_nodes[b] and query head h:
+ *     out[b,i,h,:] = softmax_j( scale * <q[b,i,h,:], k[b,h/G,j,:]> ) . v[b,h/G,j,:]
+ * over cache rows j in [0, ctx_lens[b])  (the prefix)  and  j = ctx_lens[b] + a
+ * for a = i and every ancestor a of i (cache row ctx_lens[b]+a holds the key /
+ * value of tree node a: the verify pass appends the tree to the cache before
+ * attention).  G = Hq / Hkv.  Rotary embedding, if any, is already applied.
+ * Inputs and output are bf16, scores / softmax / accumulation fp32.
+ * Rows i >= n_nodes[b] of out (and lse) are written as zero.
+ *
+ * Limits: D in {64, 128}; Hq % Hkv == 0; 1 <= T_max <= RADAR_T_MAX;
+ *         ctx_lens[b] + n_nodes[b] <= S_max (caller's contract).
+ * Strides are in elements; the innermost (D) axis is contiguous; a stride of
+ * 0 means "dense" ([B,T_max,Hq,D] for q / out, [B,Hkv,S_max,D] for caches).
+ * All bf16 base pointers and strides must keep rows 16-byte aligned.
+ */
+typedef struct radar_attn_desc {
+    int32_t B, T_max, Hq, Hkv, D, S_max;
+    int64_t q_stride_b, q_stride_t, q_stride_h;
+    int64_t kv_stride_b, kv_stride_h, kv_stride_s;
+    int64_t out_stride_b, out_stride_t, out_stride_h;
+    float   softmax_scale;      /* 0 => 1/sqrt(D) */
+    int32_t keys_per_split;     /* 0 => chosen by the library; else a multiple of 64: cache rows one
+                                   workgroup streams before partial results are merged */
+} radar_attn_desc;
+
+size_t radar_tree_attention_workspace_bytes(const radar_attn_desc *desc);
+
+/* q, out: bf16 [B,T_max,Hq,D]; k_cache, v_cache: bf16 [B,Hkv,S_max,D];
+ * parents: i32 [B,T_max]; ctx_lens: i32 [B]; n_nodes: i32 [B] or NULL (= T_max
+ * everywhere); lse_out: f32 [B,T_max,Hq] or NULL (natural-log sum of exp of the
+ * scaled scores over the allowed set). */
+radar_status radar_tree_attention(const void *q, const void *k_cache, const void *v_cache,
+                                  const int32_t *parents, const int32_t *ctx_lens, const int32_t *n_nodes,
+                                  void *out, float *lse_out, const radar_attn_desc *desc,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+
+/* --------------------------------------------------------------------------
+ * Draft expansion, one call per draft-model call (App. A.1; Sec. 2.3).
+ *
+ * Row f of `logits` is the draft model's output for frontier node f.  For each
+ * row the k best tokens under the order (logit descending, token id ascending)
+ * become candidate children c = f*k + r with
+ *     cand_scores[c] = parent_scores[f] + (logit - logsumexp(row f))
+ * i.e. the log of the path's cumulative draft probability.  The k best of the
+ * F*k candidates under (score descending, c ascending) are the next frontier;
+ * frontier_conf = exp(score) are the k confidences in [0,1] that the paper's
+ * prediction model reads (Sec. 4.2, Eq. 3).  Every candidate is appended to
+ * the pool at index pool_count + c with its parent's pool index, for the final
+ * rerank.  Requires F*k >= k, i.e. always k frontier outputs.
+ *
+ * Limits: 1 <= F <= RADAR_F_MAX; 1 <= k <= min(RADAR_K_MAX, V);
+ *         pool_count + F*k <= pool_capacity.  -inf logits are legal; NaN
+ *         logits and rows that are entirely -inf give unspecified results.
+ */
+typedef struct radar_expand_desc {
+    int32_t F, V, k;
+    int32_t pool_count;      /* candidates already in the pool (host-tracked: grows by F*k per call) */
+    int32_t pool_capacity;   /* length of the three pool arrays */
+} radar_expand_desc;
+
+size_t radar_draft_expand_workspace_bytes(const radar_expand_desc *desc);
+
+/* logits f32 [F,V]; parent_scores f32 [F]; parent_pool_idx i32 [F] (-1 = root);
+ * cand_tokens i32 [F*k]; cand_scores f32 [F*k];
+ * frontier_pool_idx i32 [k]; frontier_tokens i32 [k]; frontier_scores f32 [k];
+ * frontier_conf f32 [k];  pool_tokens i32, pool_scores f32, pool_parents i32
+ * [pool_capacity] (entries [pool_count, pool_count+F*k) are written).
+ * frontier_scores / frontier_pool_idx may be passed as the next call's
+ * parent_scores / parent_pool_idx. */
+radar_status radar_draft_expand(const float *logits, const float *parent_scores, const int32_t *parent_pool_idx,
+                                int32_t *cand_tokens, float *cand_scores,
+                                int32_t *frontier_pool_idx, int32_t *frontier_tokens,
+                                float *frontier_scores, float *frontier_conf,
+                                int32_t *pool_tokens, float *pool_scores, int32_t *pool_parents,
+                                const radar_expand_desc *desc,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/* --------------------------------------------------------------------------
+ * Rerank, once per cycle (Sec. 1 / Sec. 2.3: "reordering and pruning").
+ *
+ * Orders the pool by (score descending, pool index ascending), keeps the first
+ * min(N, pool_count) and emits the tree to verify: node 0 is the root
+ * (root_token, score 0, depth 0, parent -1), the candidate of rank r is node
+ * 1+r, parents are re-indexed to node numbers (pool parent -1 => node 0),
+ * depth = depth(parent) + 1.  Scores never grow from parent to child, so a kept
+ * node's parent is kept and has a smaller node number; should the input break
+ * that, the node's parent is written as -2 and its depth as 0.
+ * Outputs are N+1 long; slots past n_nodes hold token -1, parent -1, score 0,
+ * depth 0, pool_idx -1.  *n_nodes_out (device) = 1 + min(N, pool_count).
+ *
+ * Limits: 0 <= pool_count <= RADAR_POOL_MAX; 0 <= N < RADAR_T_MAX.
+ */
+size_t radar_draft_rerank_workspace_bytes(int32_t pool_count, int32_t N);
+
+radar_status radar_draft_rerank(const int32_t *pool_tokens, const float *pool_scores, const int32_t *pool_parents,
+                                int32_t pool_count, int32_t N, int32_t root_token,
+                                int32_t *tree_tokens, int32_t *tree_parents, float *tree_scores,
+                                int32_t *tree_depth, int32_t *tree_pool_idx, int32_t *n_nodes_out,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/* --------------------------------------------------------------------------
+ * Verification walk (Sec. 3, Eq. 1-2; tree form per Sec. 4.3, Eq. 11-13).
+ *
+ * Row r of target_logits is the target's next-token distribution after the
+ * path ending in node r.  Starting at the root:
+ *   mode RADAR_ACCEPT_GREEDY   descend to the child whose token is the argmax of
+ *       the current row (lowest token id among equal logits, lowest node index
+ *       among equal tokens); stop when none matches; bonus = that argmax.
+ *   mode RADAR_ACCEPT_SAMPLE   p = softmax(row / temperature).  The children
+ *       are fixed tokens (point-mass proposals), so Eq. 1 accepts child c with
+ *       the residual probability of its token: visiting children in ascending
+ *       node index with R = mass of those already rejected, accept iff
+ *       uniforms[b,c] * (1 - R) < p(tok_c), else R += p(tok_c).  If none is
+ *       accepted the bonus token is the inverse CDF, at uniforms[b,T_max] *
+ *       (1 - R), of p with the rejected tokens removed (Eq. 2), scanning token
+ *       ids upwards.  A leaf has R = 0.
+ * accept_len[b] = number of accepted draft nodes (root excluded, <= depth);
+ * accept_path[b,:] = node indices from the root, padded with -1, D_max+1 long;
+ * a walk that would exceed D_max stops there.  bonus_token[b] = the extra token
+ * every cycle emits (Sec. 3: between 1 and t+1 tokens per cycle).
+ *
+ * Limits: 1 <= T_max <= RADAR_T_MAX; 0 <= D_max < RADAR_T_MAX; V >= 1;
+ *         temperature > 0 and uniforms != NULL in sampling mode.
+ */
+#define RADAR_ACCEPT_GREEDY 0
+#define RADAR_ACCEPT_SAMPLE 1
+
+typedef struct radar_accept_desc {
+    int32_t B, T_max, V, D_max;
+    int32_t mode;
+    float   temperature;
+} radar_accept_desc;
+
+size_t radar_verify_accept_workspace_bytes(const radar_accept_desc *desc);
+
+/* target_logits f32 [B,T_max,V]; draft_tokens, parents i32 [B,T_max];
+ * n_nodes i32 [B] or NULL; uniforms f32 [B,T_max+1] or NULL (greedy);
+ * accept_len i32 [B]; accept_path i32 [B,D_max+1]; bonus_token i32 [B]. */
+radar_status radar_verify_accept(const float *target_logits, const int32_t *draft_tokens, const int32_t *parents,
+                                 const int32_t *n_nodes, const float *uniforms,
+                                 int32_t *accept_len, int32_t *accept_path, int32_t *bonus_token,
+                                 const radar_accept_desc *desc,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* Counts, per call, the nodes i < n_nodes[b] whose parent breaks the tree
+ * convention; *bad_count_out (device i32) is overwritten.  parents i32
+ * [B,T_max]; n_nodes i32 [B] or NULL. */
+radar_status radar_debug_validate_tree(const int32_t *parents, const int32_t *n_nodes, int32_t B, int32_t T_max,
+                                       int32_t *bad_count_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RADAR_H */

@@ -1,0 +1,326 @@
+"""ctypes binding of libradar.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/radar.h) and
+takes torch tensors that already live on the GPU; it passes their device
+pointers, a host descriptor and the current HIP stream.  Nothing is computed
+here and there is no fallback: if the library is missing, loading fails.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libradar.so")
+_lib = None
+
+RADAR_OK = 0
+RADAR_ACCEPT_GREEDY = 0
+RADAR_ACCEPT_SAMPLE = 1
+RADAR_T_MAX = 64
+RADAR_K_MAX = 16
+RADAR_F_MAX = 64
+RADAR_POOL_MAX = 4096
+
+
+class RadarError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} ({status})")
+
+
+class AttnDesc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("T_max", ctypes.c_int32), ("Hq", ctypes.c_int32),
+                ("Hkv", ctypes.c_int32), ("D", ctypes.c_int32), ("S_max", ctypes.c_int32),
+                ("q_stride_b", ctypes.c_int64), ("q_stride_t", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
+                ("kv_stride_b", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64), ("kv_stride_s", ctypes.c_int64),
+                ("out_stride_b", ctypes.c_int64), ("out_stride_t", ctypes.c_int64), ("out_stride_h", ctypes.c_int64),
+                ("softmax_scale", ctypes.c_float), ("keys_per_split", ctypes.c_int32)]
+
+
+class ExpandDesc(ctypes.Structure):
+    _fields_ = [("F", ctypes.c_int32), ("V", ctypes.c_int32), ("k", ctypes.c_int32),
+                ("pool_count", ctypes.c_int32), ("pool_capacity", ctypes.c_int32)]
+
+
+class AcceptDesc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("T_max", ctypes.c_int32), ("V", ctypes.c_int32),
+                ("D_max", ctypes.c_int32), ("mode", ctypes.c_int32), ("temperature", ctypes.c_float)]
+
+
+EXPORTS = [
+    "radar_status_string", "radar_version", "radar_workspace_init",
+    "radar_tree_attention_workspace_bytes", "radar_tree_attention",
+    "radar_draft_expand_workspace_bytes", "radar_draft_expand",
+    "radar_draft_rerank_workspace_bytes", "radar_draft_rerank",
+    "radar_verify_accept_workspace_bytes", "radar_verify_accept",
+    "radar_debug_validate_tree",
+]
+
+
+def load():
+    """Load libradar.so (built by paper_2512_14069_amd.build); raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
+                           "(python -m paper_2512_14069_amd.build)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32
+    lib.radar_status_string.restype = ctypes.c_char_p
+    lib.radar_status_string.argtypes = [i32]
+    lib.radar_version.restype = ctypes.c_int
+    lib.radar_workspace_init.restype = i32
+    lib.radar_workspace_init.argtypes = [vp, sz, vp]
+    lib.radar_tree_attention_workspace_bytes.restype = sz
+    lib.radar_tree_attention_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc)]
+    lib.radar_tree_attention.restype = i32
+    lib.radar_tree_attention.argtypes = [vp] * 8 + [ctypes.POINTER(AttnDesc), vp, sz, vp]
+    lib.radar_draft_expand_workspace_bytes.restype = sz
+    lib.radar_draft_expand_workspace_bytes.argtypes = [ctypes.POINTER(ExpandDesc)]
+    lib.radar_draft_expand.restype = i32
+    lib.radar_draft_expand.argtypes = [vp] * 12 + [ctypes.POINTER(ExpandDesc), vp, sz, vp]
+    lib.radar_draft_rerank_workspace_bytes.restype = sz
+    lib.radar_draft_rerank_workspace_bytes.argtypes = [i32, i32]
+    lib.radar_draft_rerank.restype = i32
+    lib.radar_draft_rerank.argtypes = [vp] * 3 + [i32, i32, i32] + [vp] * 6 + [vp, sz, vp]
+    lib.radar_verify_accept_workspace_bytes.restype = sz
+    lib.radar_verify_accept_workspace_bytes.argtypes = [ctypes.POINTER(AcceptDesc)]
+    lib.radar_verify_accept.restype = i32
+    lib.radar_verify_accept.argtypes = [vp] * 8 + [ctypes.POINTER(AcceptDesc), vp, sz, vp]
+    lib.radar_debug_validate_tree.restype = i32
+    lib.radar_debug_validate_tree.argtypes = [vp, vp, i32, i32, vp, vp]
+    _lib = lib
+    return lib
+
+
+def status_string(status):
+    return load().radar_status_string(int(status)).decode()
+
+
+def radar_version():
+    return int(load().radar_version())
+
+
+def _ptr(t, dtype=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a GPU tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _dense(t, name):
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc, what):
+    if rc != RADAR_OK:
+        raise RadarError(rc, what)
+
+
+def _ws_args(ws):
+    if ws is None:
+        return None, 0
+    return ctypes.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size()
+
+
+def new_workspace(nbytes, device="cuda"):
+    """Device workspace of at least nbytes, passed through radar_workspace_init."""
+    nbytes = max(int(nbytes), 4096)
+    ws = torch.empty((nbytes + 255) // 256 * 256, dtype=torch.uint8, device=device)
+    radar_workspace_init(ws)
+    return ws
+
+
+def radar_workspace_init(ws):
+    p, n = _ws_args(ws)
+    _check(load().radar_workspace_init(p, n, _stream()), "radar_workspace_init")
+
+
+# ------------------------------------------------------------ tree attention
+
+def attn_desc(q, k_cache, keys_per_split=0, softmax_scale=0.0):
+    B, T, Hq, D = q.shape
+    Bk, Hkv, S, Dk = k_cache.shape
+    d = AttnDesc()
+    d.B, d.T_max, d.Hq, d.Hkv, d.D, d.S_max = B, T, Hq, Hkv, D, S
+    d.q_stride_b, d.q_stride_t, d.q_stride_h = q.stride(0), q.stride(1), q.stride(2)
+    d.kv_stride_b, d.kv_stride_h, d.kv_stride_s = k_cache.stride(0), k_cache.stride(1), k_cache.stride(2)
+    d.out_stride_b = d.out_stride_t = d.out_stride_h = 0
+    d.softmax_scale = float(softmax_scale)
+    d.keys_per_split = int(keys_per_split)
+    return d
+
+
+def radar_tree_attention_workspace_bytes(desc):
+    return int(load().radar_tree_attention_workspace_bytes(ctypes.byref(desc)))
+
+
+def radar_tree_attention(q, k_cache, v_cache, parents, ctx_lens, n_nodes=None, out=None, lse_out=None,
+                         desc=None, workspace=None, keys_per_split=0, softmax_scale=0.0):
+    """q bf16 [B,T,Hq,D]; k_cache, v_cache bf16 [B,Hkv,S,D] (same strides, D contiguous);
+    parents i32 [B,T]; ctx_lens i32 [B]; n_nodes i32 [B] or None.  Returns out bf16 [B,T,Hq,D]."""
+    if q.stride(-1) != 1 or k_cache.stride(-1) != 1 or v_cache.stride() != k_cache.stride():
+        raise ValueError("innermost axis must be contiguous and k/v caches must share strides")
+    if desc is None:
+        desc = attn_desc(q, k_cache, keys_per_split, softmax_scale)
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.bfloat16, device=q.device)
+    _dense(out, "out")
+    if workspace is None:
+        workspace = new_workspace(radar_tree_attention_workspace_bytes(desc), q.device)
+    wp, wn = _ws_args(workspace)
+    rc = load().radar_tree_attention(
+        _ptr(q, torch.bfloat16, "q"), _ptr(k_cache, torch.bfloat16, "k_cache"),
+        _ptr(v_cache, torch.bfloat16, "v_cache"), _ptr(_dense(parents, "parents"), torch.int32, "parents"),
+        _ptr(_dense(ctx_lens, "ctx_lens"), torch.int32, "ctx_lens"),
+        _ptr(None if n_nodes is None else _dense(n_nodes, "n_nodes"), torch.int32, "n_nodes"),
+        _ptr(out, torch.bfloat16, "out"), _ptr(lse_out, torch.float32, "lse_out"),
+        ctypes.byref(desc), wp, wn, _stream())
+    _check(rc, "radar_tree_attention")
+    return out
+
+
+# ------------------------------------------------------------ draft expansion
+
+class DraftPool:
+    """Caller-owned pool arrays (tokens, scores, parents) and the host-side count."""
+
+    def __init__(self, capacity, device="cuda"):
+        self.capacity = int(capacity)
+        self.tokens = torch.zeros(self.capacity, dtype=torch.int32, device=device)
+        self.scores = torch.zeros(self.capacity, dtype=torch.float32, device=device)
+        self.parents = torch.zeros(self.capacity, dtype=torch.int32, device=device)
+        self.count = 0
+
+
+class ExpandOut:
+    def __init__(self, F, k, device):
+        self.cand_tokens = torch.empty(F * k, dtype=torch.int32, device=device)
+        self.cand_scores = torch.empty(F * k, dtype=torch.float32, device=device)
+        self.frontier_pool_idx = torch.empty(k, dtype=torch.int32, device=device)
+        self.frontier_tokens = torch.empty(k, dtype=torch.int32, device=device)
+        self.frontier_scores = torch.empty(k, dtype=torch.float32, device=device)
+        self.frontier_conf = torch.empty(k, dtype=torch.float32, device=device)
+
+
+def expand_desc(F, V, k, pool_count, pool_capacity):
+    d = ExpandDesc()
+    d.F, d.V, d.k, d.pool_count, d.pool_capacity = F, V, k, pool_count, pool_capacity
+    return d
+
+
+def radar_draft_expand_workspace_bytes(desc):
+    return int(load().radar_draft_expand_workspace_bytes(ctypes.byref(desc)))
+
+
+def radar_draft_expand(logits, parent_scores, parent_pool_idx, k, pool, out=None, workspace=None):
+    """logits f32 [F,V]; parent_scores f32 [F]; parent_pool_idx i32 [F]; pool: DraftPool
+    (appended to; pool.count advances by F*k).  Returns an ExpandOut."""
+    F, V = logits.shape
+    desc = expand_desc(F, V, k, pool.count, pool.capacity)
+    if out is None:
+        out = ExpandOut(F, k, logits.device)
+    if workspace is None:
+        workspace = new_workspace(radar_draft_expand_workspace_bytes(desc), logits.device)
+    wp, wn = _ws_args(workspace)
+    rc = load().radar_draft_expand(
+        _ptr(_dense(logits, "logits"), torch.float32, "logits"),
+        _ptr(_dense(parent_scores, "parent_scores"), torch.float32, "parent_scores"),
+        _ptr(_dense(parent_pool_idx, "parent_pool_idx"), torch.int32, "parent_pool_idx"),
+        _ptr(out.cand_tokens, torch.int32), _ptr(out.cand_scores, torch.float32),
+        _ptr(out.frontier_pool_idx, torch.int32), _ptr(out.frontier_tokens, torch.int32),
+        _ptr(out.frontier_scores, torch.float32), _ptr(out.frontier_conf, torch.float32),
+        _ptr(pool.tokens, torch.int32), _ptr(pool.scores, torch.float32), _ptr(pool.parents, torch.int32),
+        ctypes.byref(desc), wp, wn, _stream())
+    _check(rc, "radar_draft_expand")
+    pool.count += F * k
+    return out
+
+
+class TreeOut:
+    def __init__(self, N, device):
+        self.tokens = torch.empty(N + 1, dtype=torch.int32, device=device)
+        self.parents = torch.empty(N + 1, dtype=torch.int32, device=device)
+        self.scores = torch.empty(N + 1, dtype=torch.float32, device=device)
+        self.depth = torch.empty(N + 1, dtype=torch.int32, device=device)
+        self.pool_idx = torch.empty(N + 1, dtype=torch.int32, device=device)
+        self.n_nodes = torch.empty(1, dtype=torch.int32, device=device)
+
+
+def radar_draft_rerank_workspace_bytes(pool_count, N):
+    return int(load().radar_draft_rerank_workspace_bytes(int(pool_count), int(N)))
+
+
+def radar_draft_rerank(pool, N, root_token, out=None, workspace=None):
+    """Keep the best N pool entries; returns a TreeOut (device tensors)."""
+    if out is None:
+        out = TreeOut(N, pool.tokens.device)
+    wp, wn = _ws_args(workspace)
+    rc = load().radar_draft_rerank(
+        _ptr(pool.tokens, torch.int32), _ptr(pool.scores, torch.float32), _ptr(pool.parents, torch.int32),
+        int(pool.count), int(N), int(root_token),
+        _ptr(out.tokens, torch.int32), _ptr(out.parents, torch.int32), _ptr(out.scores, torch.float32),
+        _ptr(out.depth, torch.int32), _ptr(out.pool_idx, torch.int32), _ptr(out.n_nodes, torch.int32),
+        wp, wn, _stream())
+    _check(rc, "radar_draft_rerank")
+    return out
+
+
+# ------------------------------------------------------------ verification
+
+def accept_desc(B, T, V, D_max, mode, temperature):
+    d = AcceptDesc()
+    d.B, d.T_max, d.V, d.D_max, d.mode, d.temperature = B, T, V, D_max, mode, temperature
+    return d
+
+
+def radar_verify_accept_workspace_bytes(desc):
+    return int(load().radar_verify_accept_workspace_bytes(ctypes.byref(desc)))
+
+
+def radar_verify_accept(target_logits, draft_tokens, parents, n_nodes=None, uniforms=None, mode=RADAR_ACCEPT_GREEDY,
+                        temperature=1.0, D_max=None, out=None, workspace=None):
+    """target_logits f32 [B,T,V]; draft_tokens, parents i32 [B,T]; n_nodes i32 [B] or None;
+    uniforms f32 [B,T+1] (sampling).  Returns (accept_len [B], accept_path [B,D_max+1], bonus_token [B])."""
+    B, T, V = target_logits.shape
+    if D_max is None:
+        D_max = T - 1
+    desc = accept_desc(B, T, V, D_max, mode, temperature)
+    dev = target_logits.device
+    if out is None:
+        out = (torch.empty(B, dtype=torch.int32, device=dev),
+               torch.empty((B, D_max + 1), dtype=torch.int32, device=dev),
+               torch.empty(B, dtype=torch.int32, device=dev))
+    if workspace is None:
+        workspace = new_workspace(radar_verify_accept_workspace_bytes(desc), dev)
+    wp, wn = _ws_args(workspace)
+    rc = load().radar_verify_accept(
+        _ptr(_dense(target_logits, "target_logits"), torch.float32, "target_logits"),
+        _ptr(_dense(draft_tokens, "draft_tokens"), torch.int32, "draft_tokens"),
+        _ptr(_dense(parents, "parents"), torch.int32, "parents"),
+        _ptr(None if n_nodes is None else _dense(n_nodes, "n_nodes"), torch.int32, "n_nodes"),
+        _ptr(None if uniforms is None else _dense(uniforms, "uniforms"), torch.float32, "uniforms"),
+        _ptr(out[0], torch.int32), _ptr(out[1], torch.int32), _ptr(out[2], torch.int32),
+        ctypes.byref(desc), wp, wn, _stream())
+    _check(rc, "radar_verify_accept")
+    return out
+
+
+def radar_debug_validate_tree(parents, n_nodes=None):
+    B, T = parents.shape
+    bad = torch.zeros(1, dtype=torch.int32, device=parents.device)
+    rc = load().radar_debug_validate_tree(
+        _ptr(_dense(parents, "parents"), torch.int32), _ptr(n_nodes, torch.int32), B, T, _ptr(bad), _stream())
+    _check(rc, "radar_debug_validate_tree")
+    return bad

@@ -223,7 +223,8 @@ def config(cid, trial=0):
         B = 16
         ctx = tuple(int(x) for x in rng.integers(512, 8193, size=B))
         dep = tuple(int(x) for x in rng.integers(1, 9, size=B))
-        nn = tuple(int(rng.integers(d + 1, 61)) for d in dep)
+        # a depth-d tree of branching 10 holds at most 1 + 10 + (d-1)*100 nodes
+        nn = tuple(int(rng.integers(d + 1, min(60, 1 + 10 + (d - 1) * 100) + 1)) for d in dep)
         a = AttnShape(B=B, Hq=32, Hkv=8, D=128, T=60, ctx_lens=ctx, n_nodes=nn, depths=dep)
         return Config(4, "c4_ragged", a, vocab=128256, k=10, N=59, expand_steps=8, F=10)
     if cid == 5:

@@ -1,0 +1,188 @@
+"""GPU parity: radar_tree_attention (through the C ABI) against the CPU oracle.
+
+Tolerance (bf16 inputs, fp32 accumulation, bf16 output; probabilities are rounded to
+bf16 before the P.V contraction): max-abs error <= 2e-2 and relative error (L2 norm
+over the compared block) <= 1e-2, the bounds of the baseline description."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_14069_amd import synth
+from gpu_util import bf16_dev, bf16_bits, dev, host
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS = 2e-2
+REL = 1e-2
+
+
+def f64(bits):
+    return synth.bf16_bits_to_f32(bits).astype(np.float64)
+
+
+def check_close(got_bits, ref_bits, what=""):
+    got, ref = f64(got_bits), f64(ref_bits)
+    assert np.all(np.isfinite(got)), what
+    err = np.abs(got - ref)
+    rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
+    assert err.max() <= MAX_ABS, f"{what}: max abs {err.max():.3e}"
+    assert rel <= REL, f"{what}: rel {rel:.3e}"
+    return err.max(), rel
+
+
+def run_gpu(b, x, keys_per_split=0, want_lse=False, scale=0.0):
+    q, kc, vc = bf16_dev(x["q"]), bf16_dev(x["k_cache"]), bf16_dev(x["v_cache"])
+    B, T, Hq, D = q.shape
+    lse = torch.full((B, T, Hq), 7.0, dtype=torch.float32, device="cuda") if want_lse else None
+    out = torch.full(q.shape, 3.0, dtype=torch.bfloat16, device="cuda")
+    b.radar_tree_attention(q, kc, vc, dev(x["parents"]), dev(x["ctx_lens"]), dev(x["n_nodes"]),
+                           out=out, lse_out=lse, keys_per_split=keys_per_split, softmax_scale=scale)
+    torch.cuda.synchronize()
+    return (bf16_bits(out), host(lse)) if want_lse else bf16_bits(out)
+
+
+def shape(B, Hq, Hkv, D, T, ctx, nn, dep, k=4):
+    return synth.AttnShape(B=B, Hq=Hq, Hkv=Hkv, D=D, T=T, ctx_lens=tuple(ctx), n_nodes=tuple(nn), depths=tuple(dep), k=k)
+
+
+CASES = {
+    "c1_smoke": shape(1, 4, 1, 64, 16, [256], [16], [4]),
+    "gqa4_d128_ragged_tail": shape(2, 8, 2, 128, 40, [333, 70], [40, 17], [5, 3]),
+    "mha_d64": shape(1, 3, 3, 64, 33, [129], [33], [6]),
+    "group_of_3": shape(1, 6, 2, 128, 20, [200], [20], [4]),
+    "group_of_8_two_query_blocks": shape(2, 16, 2, 128, 64, [190, 65], [64, 50], [8, 8], k=10),
+    "group_of_6": shape(1, 6, 1, 64, 12, [100], [12], [3]),
+    "empty_prefix": shape(2, 4, 2, 128, 30, [0, 0], [30, 1], [4, 1]),
+    "root_only": shape(1, 4, 4, 64, 8, [77], [1], [1]),
+    "one_slot": shape(1, 2, 1, 128, 1, [50], [1], [1]),
+}
+
+
+@pytest.mark.parametrize("kps", [0, 64, 128])
+@pytest.mark.parametrize("name", list(CASES))
+def test_small_cases_match_oracle(oracle, name, kps):
+    from paper_2512_14069_amd import binding as b
+    a = CASES[name]
+    x = synth.attention_inputs(a, seed=synth.seed_for(1, len(name)), shuffle=True)
+    ref, ref_lse = oracle.tree_attention(x["q"], x["k_cache"], x["v_cache"], x["parents"], x["ctx_lens"],
+                                         x["n_nodes"], want_lse=True)
+    got, lse = run_gpu(b, x, keys_per_split=kps, want_lse=True)
+    for bb in range(a.B):
+        n = a.n_nodes[bb]
+        check_close(got[bb, :n], ref[bb, :n], f"{name} b={bb}")
+        assert np.max(np.abs(lse[bb, :n] - ref_lse[bb, :n])) < 2e-2
+        assert np.all(got[bb, n:] == 0) and np.all(lse[bb, n:] == 0)     # unused rows are zeroed
+
+
+def test_chain_and_star_trees_depth_63(oracle):
+    from paper_2512_14069_amd import binding as b
+    a = shape(2, 4, 1, 128, 64, [100, 31], [64, 64], [8, 8], k=10)
+    x = synth.attention_inputs(a, seed=4)
+    x["parents"][0] = synth.chain_tree(64)
+    x["parents"][1] = synth.star_tree(64)
+    ref = oracle.tree_attention(x["q"], x["k_cache"], x["v_cache"], x["parents"], x["ctx_lens"], x["n_nodes"])
+    for kps in (0, 64):
+        got = run_gpu(b, x, keys_per_split=kps)
+        check_close(got, ref, f"kps={kps}")
+
+
+def test_non_ancestors_and_padding_rows_do_not_leak(oracle):
+    """Changing K/V of cache rows past the tree, of a leaf's non-ancestors, or parents past
+    n_nodes leaves the affected outputs bit-identical on the device."""
+    from paper_2512_14069_amd import binding as b
+    a = shape(1, 8, 2, 128, 24, [150], [20], [4])
+    x = synth.attention_inputs(a, seed=12)
+    base = run_gpu(b, x)
+    rng = np.random.default_rng(0)
+    y = {k: v.copy() for k, v in x.items()}
+    L, n = 150, 20
+    y["k_cache"][0, :, L + n:] = synth.normal_bf16(rng, y["k_cache"][0, :, L + n:].shape)
+    y["v_cache"][0, :, L + n:] = 0x7fc0                     # NaNs past the end must not leak
+    y["parents"][0, n:] = 0
+    victim = n - 1                                            # last node: ancestor of nobody else
+    y["k_cache"][0, :, L + victim] = synth.normal_bf16(rng, (2, 128))
+    y["v_cache"][0, :, L + victim] = synth.normal_bf16(rng, (2, 128))
+    got = run_gpu(b, y)
+    assert np.array_equal(got[0, :victim], base[0, :victim])
+    assert not np.array_equal(got[0, victim], base[0, victim])
+
+
+def test_strided_views_and_scale(oracle):
+    """q taken from a fused [B,T,3*Hq,D] projection buffer and caches with a padded row pitch."""
+    from paper_2512_14069_amd import binding as b
+    a = shape(1, 8, 2, 128, 20, [90], [20], [4])
+    x = synth.attention_inputs(a, seed=3)
+    ref = oracle.tree_attention(x["q"], x["k_cache"], x["v_cache"], x["parents"], x["ctx_lens"], x["n_nodes"],
+                                scale=0.05)
+    fused = torch.zeros((1, 20, 24, 128), dtype=torch.bfloat16, device="cuda")
+    fused[:, :, 8:16] = bf16_dev(x["q"])
+    q = fused[:, :, 8:16]
+    S = x["k_cache"].shape[2]
+    kbuf = torch.zeros((1, 2, S + 9, 128), dtype=torch.bfloat16, device="cuda")
+    vbuf = torch.zeros((1, 2, S + 9, 128), dtype=torch.bfloat16, device="cuda")
+    kbuf[:, :, :S] = bf16_dev(x["k_cache"]); vbuf[:, :, :S] = bf16_dev(x["v_cache"])
+    out = b.radar_tree_attention(q, kbuf[:, :, :S], vbuf[:, :, :S], dev(x["parents"]), dev(x["ctx_lens"]),
+                                 dev(x["n_nodes"]), softmax_scale=0.05)
+    torch.cuda.synchronize()
+    check_close(bf16_bits(out), ref, "strided")
+
+
+def sampled_heads_check(oracle, b, a, seed, pairs, kps=0):
+    """Full-size launch; the oracle recomputes whole (sequence, query head) slices."""
+    x = synth.attention_inputs(a, seed=seed)
+    got = run_gpu(b, x, keys_per_split=kps)
+    G = a.Hq // a.Hkv
+    worst = (0.0, 0.0)
+    for (bb, h) in pairs:
+        sub = oracle.tree_attention(x["q"][bb:bb + 1, :, h:h + 1], x["k_cache"][bb:bb + 1, h // G:h // G + 1],
+                                    x["v_cache"][bb:bb + 1, h // G:h // G + 1], x["parents"][bb:bb + 1],
+                                    x["ctx_lens"][bb:bb + 1], x["n_nodes"][bb:bb + 1])
+        n = a.n_nodes[bb]
+        e = check_close(got[bb, :n, h], sub[0, :n, 0], f"b={bb} h={h}")
+        worst = (max(worst[0], e[0]), max(worst[1], e[1]))
+        assert np.all(got[bb, n:, h] == 0)
+    return worst
+
+
+def test_config2_full(oracle):
+    """Llama-3.1-8B-shaped verify layer, every output compared."""
+    from paper_2512_14069_amd import binding as b
+    a = synth.config(2).attn
+    x = synth.attention_inputs(a, seed=synth.seed_for(2))
+    ref = oracle.tree_attention(x["q"], x["k_cache"], x["v_cache"], x["parents"], x["ctx_lens"], x["n_nodes"])
+    got = run_gpu(b, x)
+    check_close(got, ref, "config 2")
+    again = run_gpu(b, x)
+    assert np.array_equal(got, again)            # bit-reproducible
+
+
+def test_config4_ragged_sampled(oracle):
+    from paper_2512_14069_amd import binding as b
+    a = synth.config(4).attn
+    rng = np.random.default_rng(1)
+    pairs = [(bb, int(rng.integers(0, a.Hq))) for bb in range(a.B)]
+    sampled_heads_check(oracle, b, a, synth.seed_for(4), pairs)
+
+
+def test_config5_sampled(oracle):
+    from paper_2512_14069_amd import binding as b
+    a = synth.config(5).attn
+    rng = np.random.default_rng(2)
+    pairs = [(int(rng.integers(0, a.B)), int(rng.integers(0, a.Hq))) for _ in range(6)]
+    sampled_heads_check(oracle, b, a, synth.seed_for(5), pairs)
+
+
+def test_bad_descriptors_are_rejected():
+    from paper_2512_14069_amd import binding as b
+    q = torch.zeros((1, 8, 4, 96), dtype=torch.bfloat16, device="cuda")
+    kv = torch.zeros((1, 2, 64, 96), dtype=torch.bfloat16, device="cuda")
+    par = torch.zeros((1, 8), dtype=torch.int32, device="cuda")
+    ctx = torch.zeros(1, dtype=torch.int32, device="cuda")
+    with pytest.raises(b.RadarError) as e:
+        b.radar_tree_attention(q, kv, kv, par, ctx, workspace=b.new_workspace(1 << 20))
+    assert e.value.status == -2                                   # head dim 96 is not compiled
+    q = torch.zeros((1, 8, 4, 128), dtype=torch.bfloat16, device="cuda")
+    kv = torch.zeros((1, 3, 64, 128), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(b.RadarError) as e:
+        b.radar_tree_attention(q, kv, kv, par, ctx, workspace=b.new_workspace(1 << 20))
+    assert e.value.status == -1                                   # 4 query heads over 3 KV heads
