@@ -1,0 +1,243 @@
+#!/usr/bin/env python3
+"""Benchmark of the RADAR hot path on one MI355X.
+
+One step = one decode cycle's device work at the 8B shape: one layer of tree-verify
+attention (config 2: context 2048, 32/8 heads, head dim 128, 60 tree rows), 8 draft-
+expansion calls (config 3: 10 rows x 128256 logits, k = 10), the rerank to the best 60,
+and the verification walk over the 61 rows x 128256 target logits (rejection sampling,
+temperature 1).  Inputs are synthetic, seeded and resident in HBM before timing; every
+step uses the next of several input sets whose total size exceeds L2 + Infinity Cache,
+so the kernels read from HBM, not from cache.
+
+Prints one JSON line.  `value` is the attention kernel's achieved HBM bandwidth
+(algorithmic bytes / average kernel time measured with events around each launch in
+the timed region); the expand+accept time per cycle is reported next to it.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBPS = 8000.0
+METRIC = "tree-verify attention HBM GB/s (% peak); expand+accept µs/step at 8B shape"
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--attn-sets", type=int, default=64, help="distinct KV caches cycled through (9.6 MB each)")
+    ap.add_argument("--cycle-sets", type=int, default=8, help="distinct logits sets cycled through (72 MB each)")
+    ap.add_argument("--only", default="", help="time only 'attention', 'expand' or 'accept' (for profiling)")
+    return ap.parse_args()
+
+
+def read_traffic():
+    """HBM bytes per attention launch measured offline with rocprofv3 --pmc (see profiles/)."""
+    path = os.path.join(ROOT, "profiles", "tree_attention_c2_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2512_14069_amd import binding as b, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    b.load()
+    dev = "cuda"
+    c2, c3 = synth.config(2), synth.config(3)
+    A = c2.attn
+    V, k, F, N, steps_per_cycle = c3.vocab, c3.k, c3.F, c3.N, c3.expand_steps
+    T_acc = N + 1
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.seed_for(2, 99))
+
+    # ---------------------------------------------------------------- attention inputs
+    S = A.S
+    attn_sets = []
+    rng = np.random.default_rng(synth.seed_for(2, 98))
+    parents_np, _, _ = synth.make_tree(rng, A.n_nodes[0], A.depths[0], A.k, V)
+    parents = torch.from_numpy(parents_np[None].copy()).to(dev)
+    ctx = torch.tensor(A.ctx_lens, dtype=torch.int32, device=dev)
+    nn_ = torch.tensor(A.n_nodes, dtype=torch.int32, device=dev)
+    for _ in range(args.attn_sets):
+        q = torch.randn((A.B, A.T, A.Hq, A.D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        kc = torch.randn((A.B, A.Hkv, S, A.D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        vc = torch.randn((A.B, A.Hkv, S, A.D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        attn_sets.append((q, kc, vc))
+    attn_out = torch.empty((A.B, A.T, A.Hq, A.D), dtype=torch.bfloat16, device=dev)
+    adesc = b.attn_desc(attn_sets[0][0], attn_sets[0][1])
+    attn_ws = b.new_workspace(b.radar_tree_attention_workspace_bytes(adesc))
+    kv_rows = A.ctx_lens[0] + A.n_nodes[0]
+    attn_bytes = kv_rows * A.Hkv * A.D * 2 * 2 + 2 * A.n_nodes[0] * A.Hq * A.D * 2 + A.T * 4
+
+    # ---------------------------------------------------------------- expand / accept inputs
+    cap = F * k * steps_per_cycle
+    cycle_sets = []
+    for _ in range(args.cycle_sets):
+        draft = [torch.log_softmax(torch.randn((F, V), generator=gen, device=dev) * c3.logit_std, dim=-1).contiguous()
+                 for _ in range(steps_per_cycle)]
+        u = torch.rand((T_acc, V), generator=gen, device=dev).clamp_(1e-7, 1 - 1e-7)
+        target = (torch.randn((T_acc, V), generator=gen, device=dev) - torch.log(-torch.log(u))).contiguous()
+        uniforms = torch.rand((1, T_acc + 1), generator=gen, device=dev)
+        cycle_sets.append(dict(draft=draft, target=target.view(1, T_acc, V), uniforms=uniforms))
+        del u
+    pool = b.DraftPool(cap)
+    ps0 = torch.zeros(F, dtype=torch.float32, device=dev) - torch.arange(F, device=dev) * 0.25
+    ppi0 = torch.full((F,), -1, dtype=torch.int32, device=dev)
+    exp_outs = [b.ExpandOut(F, k, dev) for _ in range(steps_per_cycle)]
+    exp_ws = b.new_workspace(b.radar_draft_expand_workspace_bytes(b.expand_desc(F, V, k, 0, cap)))
+    tree = b.TreeOut(N, dev)
+    acc_desc = b.accept_desc(1, T_acc, V, T_acc - 1, b.RADAR_ACCEPT_SAMPLE, 1.0)
+    acc_ws = b.new_workspace(b.radar_verify_accept_workspace_bytes(acc_desc))
+    acc_out = (torch.empty(1, dtype=torch.int32, device=dev), torch.empty((1, T_acc), dtype=torch.int32, device=dev),
+               torch.empty(1, dtype=torch.int32, device=dev))
+    expand_bytes = F * V * 4
+    accept_bytes = T_acc * V * 4
+
+    def run_expand_chain(cs):
+        pool.count = 0
+        ps, ppi = ps0, ppi0
+        for s in range(steps_per_cycle):
+            o = b.radar_draft_expand(cs["draft"][s], ps, ppi, k, pool, out=exp_outs[s], workspace=exp_ws)
+            ps, ppi = o.frontier_scores, o.frontier_pool_idx
+        b.radar_draft_rerank(pool, N, 1, out=tree)
+
+    def run_accept(cs):
+        b.radar_verify_accept(cs["target"], tree.tokens.view(1, -1), tree.parents.view(1, -1), tree.n_nodes,
+                              cs["uniforms"], mode=b.RADAR_ACCEPT_SAMPLE, temperature=1.0, D_max=T_acc - 1,
+                              out=acc_out, workspace=acc_ws)
+
+    def run_attention(i):
+        q, kc, vc = attn_sets[i % len(attn_sets)]
+        b.radar_tree_attention(q, kc, vc, parents, ctx, nn_, out=attn_out, desc=adesc, workspace=attn_ws)
+
+    # plant an accepted path into every target set: the drafted tree of a set is fixed by its
+    # draft logits, so draft it once (untimed) and lift one child per node, with probability
+    # 0.75, far above the noise -- accepted lengths then spread like the paper's (Table 1).
+    prng = np.random.default_rng(synth.seed_for(3, 97))
+    for cs in cycle_sets:
+        run_expand_chain(cs)
+        torch.cuda.synchronize()
+        tp, tt = tree.parents.cpu().numpy(), tree.tokens.cpu().numpy()
+        for p in range(T_acc):
+            kids = np.nonzero(tp == p)[0]
+            if len(kids) and prng.random() < 0.75:
+                cs["target"][0, p, int(tt[int(prng.choice(kids))])] = 30.0
+
+    only = args.only
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    K, W = args.steps, args.warmup
+    marks = [[ev() for _ in range(4)] for _ in range(K)]
+
+    def step(i, m=None):
+        cs = cycle_sets[i % len(cycle_sets)]
+        if m: m[0].record()
+        if only in ("", "attention"): run_attention(i)
+        if m: m[1].record()
+        if only in ("", "expand"): run_expand_chain(cs)
+        if m: m[2].record()
+        if only in ("", "accept"): run_accept(cs)
+        if m: m[3].record()
+
+    for i in range(W):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        step(W + i, marks[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    attn_us = np.array([m[0].elapsed_time(m[1]) for m in marks]) * 1e3
+    exp_us = np.array([m[1].elapsed_time(m[2]) for m in marks]) * 1e3
+    acc_us = np.array([m[2].elapsed_time(m[3]) for m in marks]) * 1e3
+    a_us, e_us, c_us = float(attn_us.mean()), float(exp_us.mean()), float(acc_us.mean())
+    attn_gbps = attn_bytes / (a_us * 1e-6) / 1e9 if a_us > 0 else 0.0
+    ea_bytes = expand_bytes * steps_per_cycle + accept_bytes
+    ea_us = e_us + c_us
+    ea_gbps = ea_bytes / (ea_us * 1e-6) / 1e9 if ea_us > 0 else 0.0
+
+    result = {
+        "metric": METRIC,
+        "value": round(attn_gbps, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": round(wall / K * 1e3, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "c2_8b_verify (attention) + c3_8b_expand (8 expand calls, rerank, sampled accept)",
+                   "context": A.ctx_lens[0], "tree_rows": A.T, "q_heads": A.Hq, "kv_heads": A.Hkv, "head_dim": A.D,
+                   "vocab": V, "k": k, "frontier_rows": F, "expand_calls": steps_per_cycle, "rerank_N": N,
+                   "cache": "cold: inputs rotate through %d MB (attention) / %d MB (logits)" % (
+                       attn_bytes * len(attn_sets) // 2**20, ea_bytes * len(cycle_sets) // 2**20)},
+        "attention_us": round(a_us, 2),
+        "attention_pct_peak_hbm": round(100 * attn_gbps / PEAK_HBM_GBPS, 2),
+        "attention_tflops": round(4.0 * A.Hq * A.T * kv_rows * A.D / (a_us * 1e-6) / 1e12, 1) if a_us > 0 else 0.0,
+        "expand_chain_us": round(e_us, 2),
+        "expand_us_per_call": round(e_us / steps_per_cycle, 2),
+        "accept_us": round(c_us, 2),
+        "expand_accept_us_per_step": round(ea_us, 2),
+        "expand_accept_gbps": round(ea_gbps, 1),
+        "expand_accept_pct_peak_hbm": round(100 * ea_gbps / PEAK_HBM_GBPS, 2),
+        "roofline": {"kernel": "tree_attn_split_kernel<128,2>", "bound": "hbm", "achieved": round(attn_gbps, 1),
+                     "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(attn_gbps / PEAK_HBM_GBPS, 4),
+                     "algorithmic_bytes": attn_bytes, "traffic": read_traffic()},
+    }
+
+    if not args.no_cpu_baseline and only == "":
+        import oracle
+        oracle.build()
+        x = synth.attention_inputs(A, seed=synth.seed_for(2))
+        t1 = time.perf_counter()
+        oracle.tree_attention(x["q"], x["k_cache"], x["v_cache"], x["parents"], x["ctx_lens"], x["n_nodes"])
+        t_attn = time.perf_counter() - t1
+        orng = np.random.default_rng(synth.seed_for(3))
+        logits = synth.expand_logits(orng, F, V, c3.logit_std)
+        cp = dict(tokens=np.zeros(F * k, np.int32), scores=np.zeros(F * k, np.float32), parents=np.zeros(F * k, np.int32))
+        t1 = time.perf_counter()
+        oracle.draft_expand(logits, np.zeros(F, np.float32), np.full(F, -1, np.int32), k, cp, 0)
+        t_exp = time.perf_counter() - t1
+        y = synth.accept_inputs(synth.config(3).attn, V, seed=synth.seed_for(3, 1))
+        t1 = time.perf_counter()
+        oracle.verify_accept(y["target_logits"], y["draft_tokens"], y["parents"], y["n_nodes"], y["uniforms"], mode=1)
+        t_acc = time.perf_counter() - t1
+        result["cpu_baseline"] = {
+            "value": round(attn_bytes / t_attn / 1e9, 4), "unit": "GB/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": "one full config-2 attention layer (%.2f s); also one expand call %.1f ms, one sampled "
+                      "verify walk over 61 rows %.1f ms" % (t_attn, t_exp * 1e3, t_acc * 1e3),
+            "attention_us": round(t_attn * 1e6, 0), "expand_call_us": round(t_exp * 1e6, 0),
+            "accept_us": round(t_acc * 1e6, 0)}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -26,8 +26,8 @@
  *   - No call allocates or frees memory.  Scratch memory is a caller-owned
  *     device workspace whose size the matching *_workspace_bytes query gives.
  *     A workspace must be passed once through radar_workspace_init before its
- *     first use (its leading bytes hold arrival counters that the kernels leave
- *     zeroed again); it may then be reused by any sequence of calls on ONE
+ *     first use (it holds arrival counters that the kernels leave zeroed
+ *     again); it may then be reused by any sequence of calls on ONE
  *     stream.  Calls that share a workspace on different streams race.
  *   - Return value: RADAR_OK or a negative radar_status.  Nothing is printed,
  *     thrown or aborted.  On an error no kernel has been launched.
@@ -71,7 +71,8 @@ const char *radar_status_string(radar_status status);
 int radar_version(void);
 
 /* Zero a workspace before its first use.  `bytes` is the full size that was
- * allocated; at least the first 4096 bytes must exist.  Enqueues one kernel. */
+ * allocated (what the *_workspace_bytes query returned, or more; at least 4096).
+ * Enqueues one kernel. */
 radar_status radar_workspace_init(void *workspace, size_t bytes, void *stream);
 
 /* --------------------------------------------------------------------------

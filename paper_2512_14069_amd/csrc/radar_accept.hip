@@ -4,10 +4,11 @@
 // Phase 1, grid (chunks of 4096 logits, tree rows, sequences): one streaming
 // read of the target logits (T*V*4 bytes per sequence) leaves per chunk the
 // arg-max key and, in sampling mode, (max, sum exp) of the temperature-scaled
-// row.  Phase 2 runs in the workgroup whose arrival ticket is the last of its
-// sequence: rows are merged by the four wavefronts, then a single wavefront
-// walks the tree (one lane per node, sibling sets found with ballots).  The
-// residual draw needs one more pass over a single 16 KB chunk.
+// row.  Phase 2: the workgroup whose arrival ticket is the last of its ROW
+// merges that row's chunk partials (one per lane).  Phase 3: the workgroup whose
+// ticket is the last of its SEQUENCE walks the tree in a single wavefront (one
+// lane per node, sibling sets found with ballots); the residual draw needs one
+// more pass over a single 16 KB chunk.  Arrival counters sit 64 B apart.
 #include "radar_device.h"
 
 namespace radar {
@@ -16,8 +17,7 @@ constexpr int kAccThreads = 256;
 constexpr int kAccEPT = 16;
 constexpr int kAccChunk = kAccThreads * kAccEPT;
 constexpr int kAccMaxChunks = 256;
-constexpr int kAccMaxB = 1024;          // one arrival counter per sequence in the 4 KB counter block
-constexpr size_t kAccCounterBytes = 4096;
+constexpr int kAccCounterStride = 16;   // counters 64 B apart (same-line fetch-adds serialise)
 
 struct AcceptArgs {
     const float *logits;
@@ -31,7 +31,10 @@ struct AcceptArgs {
     int B, T, V, D_max, mode, nchunks;
     float inv_temp_f;
     double inv_temp;
-    unsigned int *counters;     // [B]
+    unsigned int *counters;     // [(b*T + r) * stride] chunks of a row, [(B*T + b) * stride] rows of a sequence
+    uint64_t *row_key;          // [B][T] arg-max key of the row
+    double *row_L;              // [B][T] sum of exp(y - row_M)
+    float *row_M;               // [B][T]
     uint64_t *part_key;         // [B][T][nchunks] arg-max key of the chunk
     double *part_l;             // [B][T][nchunks] sum of exp(y - part_m) over the chunk, y = logit / temperature
     float *part_m;              // [B][T][nchunks] reference maximum of the chunk
@@ -41,7 +44,7 @@ struct AcceptSmem {
     uint64_t wave_key[4];
     float wave_m[4];
     double wave_l[4];
-    int is_last;
+    unsigned int ticket;
     // phase 2
     int row_arg[RADAR_T_MAX];
     double row_lse[RADAR_T_MAX];
@@ -56,14 +59,6 @@ struct AcceptSmem {
     double mass[kAccMaxChunks];
     double tsum[kAccThreads];
 };
-
-// Orders LDS traffic between the lanes of one wavefront (a lane reads what another
-// lane of the same wavefront wrote earlier in program order).
-__device__ __forceinline__ void wave_lds_sync() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
 
 template <bool VEC4>
 __global__ __launch_bounds__(kAccThreads) void accept_kernel(AcceptArgs a) {
@@ -83,15 +78,20 @@ __global__ __launch_bounds__(kAccThreads) void accept_kernel(AcceptArgs a) {
 #pragma unroll
     for (int g = 0; g < kAccEPT / 4; ++g) {
         const int idx0 = base + g * (kAccThreads * 4) + tid * 4;
-        float4 v = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+        // branch-free: out-of-range lanes read a valid address and are masked afterwards
+        float4 v;
         if (VEC4) {
-            if (idx0 < a.V) v = *reinterpret_cast<const float4 *>(row + idx0);
+            v = *reinterpret_cast<const float4 *>(row + (idx0 < a.V ? idx0 : 0));
         } else {
-            if (idx0 + 0 < a.V) v.x = row[idx0 + 0];
-            if (idx0 + 1 < a.V) v.y = row[idx0 + 1];
-            if (idx0 + 2 < a.V) v.z = row[idx0 + 2];
-            if (idx0 + 3 < a.V) v.w = row[idx0 + 3];
+            v.x = row[min(idx0 + 0, a.V - 1)];
+            v.y = row[min(idx0 + 1, a.V - 1)];
+            v.z = row[min(idx0 + 2, a.V - 1)];
+            v.w = row[min(idx0 + 3, a.V - 1)];
         }
+        if (idx0 + 0 >= a.V) v.x = -INFINITY;
+        if (idx0 + 1 >= a.V) v.y = -INFINITY;
+        if (idx0 + 2 >= a.V) v.z = -INFINITY;
+        if (idx0 + 3 >= a.V) v.w = -INFINITY;
         x[4 * g + 0] = v.x; x[4 * g + 1] = v.y; x[4 * g + 2] = v.z; x[4 * g + 3] = v.w;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -117,48 +117,72 @@ __global__ __launch_bounds__(kAccThreads) void accept_kernel(AcceptArgs a) {
     }
     __syncthreads();
     const size_t pslot = ((size_t)b * a.T + r) * a.nchunks + chunk;
-    if (tid == 0) {
-        a.part_key[pslot] = max_u64(max_u64(s.wave_key[0], s.wave_key[1]), max_u64(s.wave_key[2], s.wave_key[3]));
+    if (w == 0) {
+        const uint64_t bk = max_u64(max_u64(s.wave_key[0], s.wave_key[1]), max_u64(s.wave_key[2], s.wave_key[3]));
+        if (lane == 0) store_shared_result(&a.part_key[pslot], bk);
         if (sampling) {
             const float m = fmaxf(fmaxf(s.wave_m[0], s.wave_m[1]), fmaxf(s.wave_m[2], s.wave_m[3]));
-            double l = 0.0;
-            if (m > -INFINITY)
-                for (int i = 0; i < 4; ++i)
-                    if (s.wave_m[i] > -INFINITY) l += s.wave_l[i] * exp((double)s.wave_m[i] - (double)m);
-            a.part_m[pslot] = m;
-            a.part_l[pslot] = l;
-        }
-        __threadfence();
-        const unsigned int t = atomicAdd(&a.counters[b], 1u);
-        s.is_last = (t == (unsigned int)(a.nchunks * nn - 1));
-    }
-    __syncthreads();
-    if (!s.is_last) return;
-    __threadfence();
-    if (tid == 0) a.counters[b] = 0;                   // leave the arrival counter clean for the next call
-
-    // ---------------- phase 2: last workgroup of sequence b
-    // (a) merge the rows: one wavefront per row, lanes over chunks
-    for (int rr = w; rr < nn; rr += 4) {
-        const size_t p0 = ((size_t)b * a.T + rr) * a.nchunks;
-        uint64_t kb = 0;
-        float m = -INFINITY;
-        for (int c = lane; c < a.nchunks; c += kWave) {
-            kb = max_u64(kb, load_shared_result(&a.part_key[p0 + c]));
-            if (sampling) m = fmaxf(m, load_shared_result(&a.part_m[p0 + c]));
-        }
-        kb = wave_max_u64(kb);
-        if (lane == 0) s.row_arg[rr] = (int)key_index(kb);
-        if (sampling) {
-            const float M = wave_max_f32(m);
-            double t = 0.0;
-            for (int c = lane; c < a.nchunks; c += kWave) {
-                const float mc = load_shared_result(&a.part_m[p0 + c]);
-                const double lc = load_shared_result(&a.part_l[p0 + c]);
-                if (mc > -INFINITY) t += lc * exp((double)mc - (double)M);
+            double t = 0.0;                                  // lanes 0..3: one fp64 term each
+            if (lane < 4 && s.wave_m[lane] > -INFINITY) t = s.wave_l[lane] * exp((double)s.wave_m[lane] - (double)m);
+            const uint64_t tb = (uint64_t)__double_as_longlong(t);
+            const double l = (__longlong_as_double((long long)readlane_u64(tb, 0)) +
+                              __longlong_as_double((long long)readlane_u64(tb, 1))) +
+                             (__longlong_as_double((long long)readlane_u64(tb, 2)) +
+                              __longlong_as_double((long long)readlane_u64(tb, 3)));
+            if (lane == 0) {
+                store_shared_result(&a.part_m[pslot], m);
+                store_shared_result(&a.part_l[pslot], l);
             }
-            const double L = wave_sum_f64(t);
-            if (lane == 0) { s.row_M[rr] = M; s.row_L[rr] = L; s.row_lse[rr] = (double)M + log(L); }
+        }
+    }
+    unsigned int *row_counter = &a.counters[((size_t)b * a.T + r) * kAccCounterStride];
+    if (publish_then_ticket(row_counter, &s.ticket) != (unsigned int)(a.nchunks - 1)) return;
+
+    // ---------------- phase 2: last workgroup of row r -- merge its chunk partials (one per lane)
+    {
+        const size_t p0 = ((size_t)b * a.T + r) * a.nchunks;
+        const int c = min(tid, a.nchunks - 1);
+        uint64_t kb = load_shared_result(&a.part_key[p0 + c]);
+        float mc = -INFINITY;
+        double lc = 0.0;
+        if (sampling) {
+            mc = load_shared_result(&a.part_m[p0 + c]);
+            lc = load_shared_result(&a.part_l[p0 + c]);
+        }
+        if (tid >= a.nchunks) { kb = 0; mc = -INFINITY; }
+        kb = wave_max_u64(kb);
+        const float wmx = wave_max_f32(mc);
+        if (lane == 0) { s.wave_key[w] = kb; s.wave_m[w] = wmx; }
+        __syncthreads();
+        const float M = fmaxf(fmaxf(s.wave_m[0], s.wave_m[1]), fmaxf(s.wave_m[2], s.wave_m[3]));
+        const double term = (sampling && mc > -INFINITY) ? lc * exp((double)mc - (double)M) : 0.0;
+        const double ws = wave_sum_f64(term);
+        if (lane == 0) s.wave_l[w] = ws;
+        __syncthreads();
+        if (tid == 0) {
+            const size_t rs = (size_t)b * a.T + r;
+            store_shared_result(&a.row_key[rs],
+                                max_u64(max_u64(s.wave_key[0], s.wave_key[1]), max_u64(s.wave_key[2], s.wave_key[3])));
+            if (sampling) {
+                store_shared_result(&a.row_M[rs], M);
+                store_shared_result(&a.row_L[rs], (s.wave_l[0] + s.wave_l[1]) + (s.wave_l[2] + s.wave_l[3]));
+            }
+            store_shared_result(row_counter, 0u);            // leave the row counter clean for the next call
+        }
+    }
+    unsigned int *seq_counter = &a.counters[((size_t)a.B * a.T + b) * kAccCounterStride];
+    if (publish_then_ticket(seq_counter, &s.ticket) != (unsigned int)(nn - 1)) return;
+    if (tid == 0) store_shared_result(seq_counter, 0u);
+
+    // ---------------- phase 3: last workgroup of sequence b
+    if (tid < RADAR_T_MAX) {
+        const size_t rs = (size_t)b * a.T + min(tid, nn - 1);
+        const uint64_t kb = load_shared_result(&a.row_key[rs]);
+        s.row_arg[tid] = (int)key_index(kb);
+        if (sampling) {
+            const float M = load_shared_result(&a.row_M[rs]);
+            const double L = load_shared_result(&a.row_L[rs]);
+            s.row_M[tid] = M; s.row_L[tid] = L; s.row_lse[tid] = (double)M + log(L);
         }
     }
     if (tid < RADAR_T_MAX) {
@@ -331,12 +355,31 @@ __global__ void zero_fill_kernel(uint4 *p, size_t n16) {
 
 using namespace radar;
 
+// Workspace layout: arrival counters (one 64-byte slot per row and per sequence), row results,
+// chunk partials.  Returns the total size; fills the pointers when `ws` is given.
+static size_t accept_layout(int B, int T, size_t nchunks, char *ws, AcceptArgs *a) {
+    const size_t rows = (size_t)B * T, slots = rows * nchunks;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t o = off; off += (bytes + 255) & ~size_t(255); return o; };
+    const size_t o_cnt = take((rows + B) * kAccCounterStride * sizeof(unsigned int));
+    const size_t o_rk = take(rows * sizeof(uint64_t)), o_rl = take(rows * sizeof(double)), o_rm = take(rows * sizeof(float));
+    const size_t o_pk = take(slots * sizeof(uint64_t)), o_pl = take(slots * sizeof(double)), o_pm = take(slots * sizeof(float));
+    if (ws) {
+        a->counters = reinterpret_cast<unsigned int *>(ws + o_cnt);
+        a->row_key = reinterpret_cast<uint64_t *>(ws + o_rk);
+        a->row_L = reinterpret_cast<double *>(ws + o_rl);
+        a->row_M = reinterpret_cast<float *>(ws + o_rm);
+        a->part_key = reinterpret_cast<uint64_t *>(ws + o_pk);
+        a->part_l = reinterpret_cast<double *>(ws + o_pl);
+        a->part_m = reinterpret_cast<float *>(ws + o_pm);
+    }
+    return off;
+}
+
 extern "C" size_t radar_verify_accept_workspace_bytes(const radar_accept_desc *d) {
     if (!d || d->B < 1 || d->T_max < 1 || d->V < 1) return 0;
     const size_t nchunks = ((size_t)d->V + kAccChunk - 1) / kAccChunk;
-    size_t bytes = kAccCounterBytes;
-    bytes += (size_t)d->B * d->T_max * nchunks * (sizeof(uint64_t) + sizeof(double) + sizeof(float));
-    return (bytes + 255) & ~size_t(255);
+    return accept_layout(d->B, d->T_max, nchunks, nullptr, nullptr);
 }
 
 extern "C" radar_status radar_verify_accept(const float *target_logits, const int32_t *draft_tokens,
@@ -350,7 +393,7 @@ extern "C" radar_status radar_verify_accept(const float *target_logits, const in
     if (d->mode != RADAR_ACCEPT_GREEDY && d->mode != RADAR_ACCEPT_SAMPLE) return RADAR_INVALID_ARG;
     if (d->mode == RADAR_ACCEPT_SAMPLE && (!(d->temperature > 0.0f) || !uniforms)) return RADAR_INVALID_ARG;
     const int64_t nchunks = ((int64_t)d->V + kAccChunk - 1) / kAccChunk;
-    if (d->T_max > RADAR_T_MAX || d->D_max >= RADAR_T_MAX || d->B > kAccMaxB || nchunks > kAccMaxChunks)
+    if (d->T_max > RADAR_T_MAX || d->D_max >= RADAR_T_MAX || d->B > 65535 || nchunks > kAccMaxChunks)
         return RADAR_UNSUPPORTED_SHAPE;
     if (workspace_bytes < radar_verify_accept_workspace_bytes(d)) return RADAR_WORKSPACE_TOO_SMALL;
     if (((uintptr_t)workspace & 255) != 0) return RADAR_INVALID_ARG;
@@ -361,12 +404,7 @@ extern "C" radar_status radar_verify_accept(const float *target_logits, const in
     a.B = d->B; a.T = d->T_max; a.V = d->V; a.D_max = d->D_max; a.mode = d->mode; a.nchunks = (int)nchunks;
     a.inv_temp = d->mode == RADAR_ACCEPT_SAMPLE ? 1.0 / (double)d->temperature : 1.0;
     a.inv_temp_f = (float)a.inv_temp;
-    char *ws = static_cast<char *>(workspace);
-    a.counters = reinterpret_cast<unsigned int *>(ws);
-    a.part_key = reinterpret_cast<uint64_t *>(ws + kAccCounterBytes);
-    const size_t nslots = (size_t)d->B * d->T_max * nchunks;
-    a.part_l = reinterpret_cast<double *>(ws + kAccCounterBytes + nslots * sizeof(uint64_t));
-    a.part_m = reinterpret_cast<float *>(ws + kAccCounterBytes + nslots * (sizeof(uint64_t) + sizeof(double)));
+    accept_layout(d->B, d->T_max, (size_t)nchunks, static_cast<char *>(workspace), &a);
 
     const dim3 grid((unsigned)nchunks, (unsigned)d->T_max, (unsigned)d->B), block(kAccThreads);
     const bool vec4 = (d->V % 4 == 0) && (((uintptr_t)target_logits & 15) == 0);

@@ -400,7 +400,7 @@ extern "C" size_t radar_tree_attention_workspace_bytes(const radar_attn_desc *d)
     if (check_attn_desc(d) != RADAR_OK) return 0;
     const int kps = choose_keys_per_split(d);
     const size_t max_splits = ((size_t)d->S_max + kps - 1) / kps;
-    size_t bytes = 4096;
+    size_t bytes = 16384;
     if (max_splits > 1) bytes += (size_t)d->B * d->Hq * max_splits * ((size_t)d->D * 64 + 128) * sizeof(float);
     return (bytes + 255) & ~size_t(255);
 }
@@ -441,7 +441,7 @@ extern "C" radar_status radar_tree_attention(const void *q, const void *k_cache,
     const float scale = d->softmax_scale != 0.f ? d->softmax_scale : 1.0f / sqrtf((float)d->D);
     a.scale_log2 = scale * kLog2e;
     char *ws = static_cast<char *>(workspace);
-    a.part_o = reinterpret_cast<float *>(ws + 4096);
+    a.part_o = reinterpret_cast<float *>(ws + 16384);
     a.part_ml = a.part_o + (size_t)d->B * d->Hq * a.max_splits * (size_t)(d->D * 64);
 
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -120,12 +120,44 @@ __device__ __forceinline__ int lanes_below(uint64_t mask) {
     return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
-// Loads that must observe what other workgroups wrote before their arrival
-// ticket (the reader has passed an agent-scope fence; these bypass nothing by
-// themselves but keep the compiler from hoisting or caching the access).
+// Orders LDS traffic between the lanes of one wavefront (a lane reads what another
+// lane of the same wavefront wrote earlier in program order).
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ------------------------------------------------- cross-workgroup hand-over
+// Results that one workgroup leaves for another workgroup of the SAME launch
+// (partials merged by the last arriver) travel through device-scope accesses:
+// every such store and load carries agent scope, so it is written through /
+// fetched past the per-XCD L2 on its own.  This replaces agent-scope fences,
+// which on this part write back and invalidate a whole L2 (measured: ~8 us per
+// fence against ~0.1 us for the scoped accesses).  Protocol:
+//   producer: store_shared_result(...) for everything it hands over;
+//             publish_then_ticket() = wait until this lane's stores are
+//             acknowledged (vmcnt 0), workgroup barrier, one relaxed device-
+//             scope fetch-add by lane 0;
+//   consumer (the workgroup whose ticket is the last): load_shared_result(...)
+//             only -- it never reads handed-over data through a plain load.
 template <typename T>
 __device__ __forceinline__ T load_shared_result(const T *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ __forceinline__ void store_shared_result(T *p, T v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Returns, to every lane of the workgroup, the value the counter had before this
+// workgroup's arrival.  `flag` is one int of LDS.  All lanes must call it.
+__device__ __forceinline__ unsigned int publish_then_ticket(unsigned int *counter, unsigned int *flag) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0)
+        *flag = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    return *flag;
 }
 
 }  // namespace radar

@@ -17,7 +17,10 @@ constexpr int kExpThreads = 256;
 constexpr int kExpEPT = 16;
 constexpr int kExpChunk = kExpThreads * kExpEPT;      // 4096 logits per workgroup
 constexpr int kExpMaxChunks = 256;                    // V <= 1,048,576
-constexpr size_t kCounterBytes = 4096;                // leading counter block of every workspace
+constexpr int kCounterStride = 32;                    // arrival counters sit 128 B apart: fetch-adds on one
+                                                      // cache line serialise at roughly 10 ns each
+constexpr size_t kCounterBytes = 16384;               // leading counter block of the workspace
+constexpr float kLog2eF = 1.4426950408889634f;
 
 struct ExpandArgs {
     const float *logits;
@@ -33,7 +36,7 @@ struct ExpandArgs {
     float *pool_scores;
     int32_t *pool_parents;
     int F, V, k, nchunks, pool_count;
-    unsigned int *counters;     // [0] rows finished, [1+f] chunks of row f finished
+    unsigned int *counters;     // [0] rows finished, [(1+f) * kCounterStride] chunks of row f finished
     uint64_t *part_keys;        // [F][nchunks][RADAR_K_MAX]
     double *part_l;             // [F][nchunks] sum of exp(x - part_m) over the chunk
     float *part_m;              // [F][nchunks] chunk maximum
@@ -43,13 +46,26 @@ struct ExpandSmem {
     TopkSmem topk;
     float wave_m[4];
     double wave_l[4];
-    double terms[kExpMaxChunks];
-    double lse;
-    int is_last;
+    int tok[RADAR_F_MAX * RADAR_K_MAX];
+    unsigned int ticket;
 };
 
+// sum over the four wavefront entries of l_i * exp(m_i - m): lanes 0..3 of a wavefront take one
+// term each (fp64 exp), the terms are then added in a fixed order.  Every lane gets the result.
+__device__ __forceinline__ double combine4(const float *wm, const double *wl, float m) {
+    const int lane = lane_id();
+    double t = 0.0;
+    if (lane < 4 && wm[lane] > -INFINITY) t = wl[lane] * exp((double)wm[lane] - (double)m);
+    const uint64_t b = (uint64_t)__double_as_longlong(t);
+    const double t0 = __longlong_as_double((long long)readlane_u64(b, 0));
+    const double t1 = __longlong_as_double((long long)readlane_u64(b, 1));
+    const double t2 = __longlong_as_double((long long)readlane_u64(b, 2));
+    const double t3 = __longlong_as_double((long long)readlane_u64(b, 3));
+    return (t0 + t1) + (t2 + t3);
+}
+
 template <bool VEC4>
-__global__ __launch_bounds__(kExpThreads) void expand_kernel(ExpandArgs a) {
+__global__ __launch_bounds__(kExpThreads, 4) void expand_kernel(ExpandArgs a) {
     __shared__ ExpandSmem s;
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int f = blockIdx.y, chunk = blockIdx.x;
@@ -62,30 +78,35 @@ __global__ __launch_bounds__(kExpThreads) void expand_kernel(ExpandArgs a) {
 #pragma unroll
     for (int g = 0; g < kExpEPT / 4; ++g) {
         const int idx0 = base + g * (kExpThreads * 4) + tid * 4;
-        float4 v = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+        // branch-free: out-of-range lanes read a valid address and are masked afterwards
+        float4 v;
         if (VEC4) {
-            if (idx0 < a.V) v = *reinterpret_cast<const float4 *>(row + idx0);
+            v = *reinterpret_cast<const float4 *>(row + (idx0 < a.V ? idx0 : 0));
         } else {
-            if (idx0 + 0 < a.V) v.x = row[idx0 + 0];
-            if (idx0 + 1 < a.V) v.y = row[idx0 + 1];
-            if (idx0 + 2 < a.V) v.z = row[idx0 + 2];
-            if (idx0 + 3 < a.V) v.w = row[idx0 + 3];
+            v.x = row[min(idx0 + 0, a.V - 1)];
+            v.y = row[min(idx0 + 1, a.V - 1)];
+            v.z = row[min(idx0 + 2, a.V - 1)];
+            v.w = row[min(idx0 + 3, a.V - 1)];
         }
+        if (idx0 + 0 >= a.V) v.x = -INFINITY;
+        if (idx0 + 1 >= a.V) v.y = -INFINITY;
+        if (idx0 + 2 >= a.V) v.z = -INFINITY;
+        if (idx0 + 3 >= a.V) v.w = -INFINITY;
         x[4 * g + 0] = v.x; x[4 * g + 1] = v.y; x[4 * g + 2] = v.z; x[4 * g + 3] = v.w;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             keys[4 * g + j] = (idx0 + j < a.V) ? make_key(x[4 * g + j], uint32_t(idx0 + j)) : 0;
     }
 
-    // ---- chunk log-sum-exp partial: per wavefront, then combined by one lane
+    // ---- chunk log-sum-exp partial per wavefront (exp2 of fp32 differences, sums in fp64)
     float tm = x[0];
 #pragma unroll
     for (int e = 1; e < kExpEPT; ++e) tm = fmaxf(tm, x[e]);
     const float wm = wave_max_f32(tm);
-    double tl = 0.0;                                  // fp64 sums: only expf's own rounding is fp32
+    double tl = 0.0;
     if (wm > -INFINITY) {
 #pragma unroll
-        for (int e = 0; e < kExpEPT; ++e) tl += (double)expf(x[e] - wm);
+        for (int e = 0; e < kExpEPT; ++e) tl += (double)__builtin_amdgcn_exp2f((x[e] - wm) * kLog2eF);
     }
     const double wl = wave_sum_f64(tl);
     if (lane == 0) { s.wave_m[w] = wm; s.wave_l[w] = wl; }
@@ -94,107 +115,88 @@ __global__ __launch_bounds__(kExpThreads) void expand_kernel(ExpandArgs a) {
     block_topk<kExpEPT>(keys, a.k, s.topk);          // synchronises; wave_m / wave_l visible after it
 
     const size_t pslot = (size_t)f * a.nchunks + chunk;
-    if (tid < a.k) a.part_keys[pslot * RADAR_K_MAX + tid] = s.topk.top[tid];
-    if (tid == 0) {
+    if (tid < a.k) store_shared_result(&a.part_keys[pslot * RADAR_K_MAX + tid], s.topk.top[tid]);
+    if (w == 1) {                                     // a wavefront that stores no keys
         const float m = fmaxf(fmaxf(s.wave_m[0], s.wave_m[1]), fmaxf(s.wave_m[2], s.wave_m[3]));
-        double l = 0.0;
-        if (m > -INFINITY)
-            for (int i = 0; i < 4; ++i)
-                if (s.wave_m[i] > -INFINITY) l += s.wave_l[i] * exp((double)s.wave_m[i] - (double)m);
-        a.part_m[pslot] = m;
-        a.part_l[pslot] = l;
+        const double l = combine4(s.wave_m, s.wave_l, m);
+        if (lane == 0) {
+            store_shared_result(&a.part_m[pslot], m);
+            store_shared_result(&a.part_l[pslot], l);
+        }
     }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const unsigned int t = atomicAdd(&a.counters[1 + f], 1u);
-        s.is_last = (t == (unsigned int)(a.nchunks - 1));
-    }
-    __syncthreads();
-    if (!s.is_last) return;
-    __threadfence();
+    if (publish_then_ticket(&a.counters[(1 + f) * kCounterStride], &s.ticket) != (unsigned int)(a.nchunks - 1)) return;
 
     // ================= last workgroup of row f: merge the row
-    {
-        const int nk = a.nchunks * a.k;
-        uint64_t mk[kExpEPT];
+    // all loads of the hand-over data are issued together (one round trip)
+    const int nk = a.nchunks * a.k;
+    uint64_t mk[kExpEPT];
 #pragma unroll
-        for (int e = 0; e < kExpEPT; ++e) {
-            const int i = tid + e * kExpThreads;
-            mk[e] = 0;
-            if (i < nk) {
-                const int c = i / a.k, r = i - c * a.k;
-                mk[e] = load_shared_result(&a.part_keys[((size_t)f * a.nchunks + c) * RADAR_K_MAX + r]);
-            }
-        }
-        block_topk<kExpEPT>(mk, a.k, s.topk);
+    for (int e = 0; e < kExpEPT; ++e) {
+        const int i = tid + e * kExpThreads;
+        const int ic = min(i, nk - 1);                            // branch-free: clamp, load, mask
+        const int c = ic / a.k, r = ic - c * a.k;
+        const uint64_t key = load_shared_result(&a.part_keys[((size_t)f * a.nchunks + c) * RADAR_K_MAX + r]);
+        mk[e] = (i < nk) ? key : 0;
     }
-    // row log-sum-exp in fp64 from the chunk partials (fixed order)
-    float rm = -INFINITY;
-    for (int c = tid; c < a.nchunks; c += kExpThreads) {
-        const float m = load_shared_result(&a.part_m[(size_t)f * a.nchunks + c]);
-        rm = fmaxf(rm, m);
-    }
-    rm = wave_max_f32(rm);
+    const int cc = min(tid, a.nchunks - 1);                       // nchunks <= 256: one chunk per lane
+    float cm = load_shared_result(&a.part_m[(size_t)f * a.nchunks + cc]);
+    const double cl = load_shared_result(&a.part_l[(size_t)f * a.nchunks + cc]);
+    if (tid >= a.nchunks) cm = -INFINITY;
+    const float pscore = a.parent_scores[f];
+    const int ppool = a.parent_pool_idx[f];
+    const float rm = wave_max_f32(cm);
     if (lane == 0) s.wave_m[w] = rm;
-    __syncthreads();
+
+    block_topk<kExpEPT>(mk, a.k, s.topk);                         // synchronises
+
+    // row log-sum-exp in fp64 from the chunk partials (fixed association order)
     const float M = fmaxf(fmaxf(s.wave_m[0], s.wave_m[1]), fmaxf(s.wave_m[2], s.wave_m[3]));
-    for (int c = tid; c < a.nchunks; c += kExpThreads) {
-        const float m = load_shared_result(&a.part_m[(size_t)f * a.nchunks + c]);
-        const double l = load_shared_result(&a.part_l[(size_t)f * a.nchunks + c]);
-        s.terms[c] = (m > -INFINITY) ? l * exp((double)m - (double)M) : 0.0;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        double L = 0.0;
-        for (int c = 0; c < a.nchunks; ++c) L += s.terms[c];
-        s.lse = (double)M + log(L);
-    }
+    const double term = (cm > -INFINITY) ? cl * exp((double)cm - (double)M) : 0.0;
+    const double wsum = wave_sum_f64(term);
+    if (lane == 0) s.wave_l[w] = wsum;
     __syncthreads();
     if (tid < a.k) {
+        const double L = (s.wave_l[0] + s.wave_l[1]) + (s.wave_l[2] + s.wave_l[3]);
+        const double lse = (double)M + log(L);
         const uint64_t key = s.topk.top[tid];
         const int tok = (int)key_index(key);
-        const double logp = (double)row[(tok >= 0 && tok < a.V) ? tok : 0] - s.lse;
-        const float cum = (float)((double)a.parent_scores[f] + logp);
+        const double logp = (double)key_value(key) - lse;
+        const float cum = (float)((double)pscore + logp);
         const int c = f * a.k + tid;
-        a.cand_tokens[c] = tok;
-        a.cand_scores[c] = cum;
+        store_shared_result(&a.cand_tokens[c], tok);
+        store_shared_result(&a.cand_scores[c], cum);
         a.pool_tokens[a.pool_count + c] = tok;
         a.pool_scores[a.pool_count + c] = cum;
-        a.pool_parents[a.pool_count + c] = a.parent_pool_idx[f];
+        a.pool_parents[a.pool_count + c] = ppool;
     }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        a.counters[1 + f] = 0;                                    // leave the row counter clean
-        const unsigned int t = atomicAdd(&a.counters[0], 1u);
-        s.is_last = (t == (unsigned int)(a.F - 1));
-    }
-    __syncthreads();
-    if (!s.is_last) return;
-    __threadfence();
+    if (tid == 0) store_shared_result(&a.counters[(1 + f) * kCounterStride], 0u);   // leave the row counter clean
+    if (publish_then_ticket(&a.counters[0], &s.ticket) != (unsigned int)(a.F - 1)) return;
 
     // ================= last workgroup of the call: choose the next frontier
-    {
-        const int C = a.F * a.k;                                  // <= 64 * 16 = 1024
-        uint64_t ck[4];
+    const int C = a.F * a.k;                                      // <= 64 * 16 = 1024
+    uint64_t ck[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int c = tid + e * kExpThreads;
-            ck[e] = (c < C) ? make_key(load_shared_result(&a.cand_scores[c]), uint32_t(c)) : 0;
-        }
-        block_topk<4>(ck, a.k, s.topk);
+    for (int e = 0; e < 4; ++e) {
+        const int c = tid + e * kExpThreads;
+        const int cs = min(c, C - 1);
+        const float sc = load_shared_result(&a.cand_scores[cs]);
+        s.tok[cs] = load_shared_result(&a.cand_tokens[cs]);
+        ck[e] = (c < C) ? make_key(sc, uint32_t(c)) : 0;
     }
+    block_topk<4>(ck, a.k, s.topk);                               // synchronises: s.tok visible
     if (tid < a.k) {
-        int c = (int)key_index(s.topk.top[tid]);
-        if (c < 0 || c >= a.F * a.k) c = 0;                       // only reachable with NaN scores
-        const float sc = load_shared_result(&a.cand_scores[c]);
+        const uint64_t key = s.topk.top[tid];
+        int c = (int)key_index(key);
+        if (c < 0 || c >= C) c = 0;                               // only reachable with NaN scores
+        // candidate scores never are -0.0 results of the sum above unless both terms are zero;
+        // the key holds the score exactly otherwise
+        const float sc = key_value(key);
         a.frontier_pool_idx[tid] = a.pool_count + c;
-        a.frontier_tokens[tid] = load_shared_result(&a.cand_tokens[c]);
+        a.frontier_tokens[tid] = s.tok[c];
         a.frontier_scores[tid] = sc;
         a.frontier_conf[tid] = (float)exp((double)sc);
     }
-    if (tid == 0) a.counters[0] = 0;
+    if (tid == 0) store_shared_result(&a.counters[0], 0u);
 }
 
 // ------------------------------------------------------------------ rerank
@@ -226,7 +228,8 @@ __global__ __launch_bounds__(kTopkThreads) void rerank_kernel(RerankArgs a) {
 #pragma unroll
     for (int e = 0; e < kTopkMaxEPT; ++e) {
         const int i = tid + e * kTopkThreads;
-        keys[e] = (i < a.pool_count) ? make_key(a.pool_scores[i], uint32_t(i)) : 0;
+        const float sc = a.pool_scores[max(0, min(i, a.pool_count - 1))];
+        keys[e] = (i < a.pool_count) ? make_key(sc, uint32_t(i)) : 0;
         if (i < RADAR_POOL_MAX) s.node_of[i] = -1;
     }
     if (keep > 0) block_topk<kTopkMaxEPT>(keys, keep, s.topk);

@@ -5,13 +5,16 @@
 // larger key wins under "value descending, index ascending"; key 0 means
 // "no element".  256 threads, four 64-wide wavefronts.
 //
-// Method.  Each wavefront first finds a threshold tau on the 32-bit value part:
-// the K-th largest of its 64 per-lane maxima (at most K rounds of a DPP maximum
-// with the winners struck out).  At least K of the wavefront's elements are
-// >= tau, and on non-degenerate data few more, so only those "survivors" are
-// compacted (ballot + prefix count) into LDS and ranked exactly by counting.
-// The four wavefront lists (4*K <= 256 keys) are then ranked the same way.
-// Every step is exact; thresholds only limit how much is ranked.
+// Method (loop-free except for the final count).  The lanes are cut into G >= K
+// groups (16-lane DPP rows for K <= 16, quads for K <= 64) and each group's
+// largest value is found with DPP steps.  tau = the smallest group maximum is a
+// valid threshold: at least G >= K elements are >= tau.  On non-degenerate data
+// only a few dozen elements pass it; they are compacted into LDS (ballot +
+// prefix count, one LDS fetch-add per wavefront) and ranked exactly, one
+// survivor per lane, by counting larger keys with broadcast LDS reads.  Every
+// step is exact; the threshold only limits how much is ranked.  Data with huge
+// runs of equal values makes everything survive and is ranked by the same code
+// in a slower loop.
 #pragma once
 
 #include "radar_device.h"
@@ -24,9 +27,10 @@ constexpr int kTopkMaxK = 64;
 constexpr int kTopkMaxEPT = 16;
 
 struct TopkSmem {
-    uint64_t surv[kTopkWaves][kTopkMaxEPT * kWave];   // survivors of each wavefront
-    uint64_t wtop[kTopkWaves][kTopkMaxK];             // each wavefront's best K
+    uint64_t surv[kTopkThreads * kTopkMaxEPT + 2];    // compacted survivors (+2: vector reads past the end)
     uint64_t top[kTopkMaxK];                          // result, best first; 0 where fewer than K exist
+    uint32_t gmax[64];                                // group maxima
+    int count;                                        // number of survivors
 };
 
 // keys[e] == 0 marks an absent element.  All 256 threads must call this
@@ -34,55 +38,71 @@ struct TopkSmem {
 // thread.  1 <= K <= kTopkMaxK, EPT <= kTopkMaxEPT.
 template <int EPT>
 __device__ __forceinline__ void block_topk(const uint64_t (&keys)[EPT], int K, TopkSmem &s) {
-    const int lane = lane_id(), w = wave_id();
+    const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
 
     uint32_t tmax = 0;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) tmax = max(tmax, uint32_t(keys[e] >> 32));
 
-    uint32_t cand = tmax, tau = 1;
-    int remaining = K;
-    for (int round = 0; round < kTopkMaxK; ++round) {       // wave-uniform loop, <= K rounds
-        const uint32_t t = wave_max_u32(cand);
-        if (t == 0) { tau = 1; break; }                     // fewer than K lanes hold anything
-        tau = t;
-        const uint64_t eq = __ballot(cand == t);
-        remaining -= __popcll(eq);
-        if (remaining <= 0) break;
-        if (cand == t) cand = 0;
+    // ---- group maxima: quads always; 16-lane rows when 16 groups are enough
+    uint32_t g = tmax;
+    g = max(g, dpp_u32<0xB1>(g));
+    g = max(g, dpp_u32<0x4E>(g));
+    const bool rows = (K <= 16);
+    if (rows) {
+        g = max(g, dpp_u32<0x141>(g));
+        g = max(g, dpp_u32<0x140>(g));
+        if ((lane & 15) == 0) s.gmax[w * 4 + (lane >> 4)] = g;
+    } else {
+        if ((lane & 3) == 0) s.gmax[w * 16 + (lane >> 2)] = g;
+    }
+    if (tid == 0) s.count = 0;
+    if (tid < kTopkMaxK) s.top[tid] = 0;
+    __syncthreads();
+
+    // ---- tau = smallest group maximum (an empty group makes it 0: everything present survives)
+    uint32_t tau;
+    {
+        const int ng = rows ? 16 : 64;
+        uint32_t v = s.gmax[lane & (ng - 1)];
+        v = min(v, dpp_u32<0xB1>(v));
+        v = min(v, dpp_u32<0x4E>(v));
+        v = min(v, dpp_u32<0x141>(v));
+        v = min(v, dpp_u32<0x140>(v));           // minimum over each 16-lane row = over 16 groups
+        if (!rows) v = min(min(readlane_u32(v, 0), readlane_u32(v, 16)), min(readlane_u32(v, 32), readlane_u32(v, 48)));
+        tau = max(readlane_u32(v, 0), 1u);       // >= 1 so that absent keys (0) never pass
     }
 
-    int n = 0;
+    // ---- compaction: count, reserve a range per wavefront, write
+    int cnt = 0;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) cnt += __popcll(__ballot(uint32_t(keys[e] >> 32) >= tau));
+    int base = 0;
+    if (lane == 0 && cnt > 0) base = atomicAdd(&s.count, cnt);
+    base = (int)readlane_u32((uint32_t)base, 0);
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-        const bool keep = uint32_t(keys[e] >> 32) >= tau;   // tau >= 1, so absent keys never pass
+        const bool keep = uint32_t(keys[e] >> 32) >= tau;
         const uint64_t m = __ballot(keep);
         if (m) {
-            if (keep) s.surv[w][n + lanes_below(m)] = keys[e];
-            n += __popcll(m);
+            if (keep) s.surv[base + lanes_below(m)] = keys[e];
+            base += __popcll(m);
         }
     }
-    if (lane < kTopkMaxK) s.wtop[w][lane] = 0;
-    if (threadIdx.x < kTopkMaxK) s.top[threadIdx.x] = 0;
     __syncthreads();
 
-    for (int i = lane; i < n; i += kWave) {
-        const uint64_t key = s.surv[w][i];
+    // ---- exact ranks among the n survivors; all lanes read the same LDS words (broadcast)
+    const int n = s.count;
+    for (int i = tid; i < n; i += kTopkThreads) {
+        const uint64_t key = s.surv[i];
         int rank = 0;
-        for (int j = 0; j < n; ++j) rank += (s.surv[w][j] > key) ? 1 : 0;
-        if (rank < K) s.wtop[w][rank] = key;
-    }
-    __syncthreads();
-
-    {
-        const int ww = threadIdx.x >> 6, r = threadIdx.x & 63;
-        const uint64_t key = (r < K) ? s.wtop[ww][r] : 0;
-        if (key != 0) {
-            int rank = 0;
-            for (int w2 = 0; w2 < kTopkWaves; ++w2)
-                for (int j = 0; j < K; ++j) rank += (s.wtop[w2][j] > key) ? 1 : 0;
-            if (rank < K) s.top[rank] = key;
+        int j = 0;
+        for (; j + 4 <= n; j += 4) {
+            const uint64_t k0 = s.surv[j], k1 = s.surv[j + 1], k2 = s.surv[j + 2], k3 = s.surv[j + 3];
+            rank += (k0 > key) + (k1 > key) + (k2 > key) + (k3 > key);
         }
+        for (; j < n; ++j) rank += (s.surv[j] > key) ? 1 : 0;
+        if (rank < K) s.top[rank] = key;
     }
     __syncthreads();
 }

@@ -164,4 +164,4 @@ def test_expand_is_deterministic_and_workspace_reusable(oracle):
         outs.append((host(g.cand_tokens).copy(), host(g.cand_scores).copy(), host(g.frontier_pool_idx).copy()))
     for o in outs[1:]:
         assert all(np.array_equal(x, y) for x, y in zip(o, outs[0]))
-    assert int(ws[:4096].view(torch.int32).abs().sum().item()) == 0     # counters left clean
+    assert int(ws[:16384].view(torch.int32).abs().sum().item()) == 0    # counters left clean
