@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--attn-sets", type=int, default=64, help="distinct KV caches cycled through (9.6 MB each)")
     ap.add_argument("--cycle-sets", type=int, default=8, help="distinct logits sets cycled through (72 MB each)")
+    ap.add_argument("--attn-kps", type=int, default=0, help="keys_per_split override for the attention call (0 = library's choice)")
+    ap.add_argument("--attn-variant", type=int, default=0, help="0 auto, 1 key-split, 2 group-share")
     ap.add_argument("--only", default="", help="time only 'attention', 'expand' or 'accept' (for profiling)")
     return ap.parse_args()
 
@@ -88,7 +90,7 @@ def main():
         vc = torch.randn((A.B, A.Hkv, S, A.D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
         attn_sets.append((q, kc, vc))
     attn_out = torch.empty((A.B, A.T, A.Hq, A.D), dtype=torch.bfloat16, device=dev)
-    adesc = b.attn_desc(attn_sets[0][0], attn_sets[0][1])
+    adesc = b.attn_desc(attn_sets[0][0], attn_sets[0][1], keys_per_split=args.attn_kps, variant=args.attn_variant)
     attn_ws = b.new_workspace(b.radar_tree_attention_workspace_bytes(adesc))
     kv_rows = A.ctx_lens[0] + A.n_nodes[0]
     attn_bytes = kv_rows * A.Hkv * A.D * 2 * 2 + 2 * A.n_nodes[0] * A.Hq * A.D * 2 + A.T * 4

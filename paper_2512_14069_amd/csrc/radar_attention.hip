@@ -2,31 +2,45 @@
 // and verified with masked attention in one LLM pass; Sec. 3), hand-written for
 // gfx950: bf16 MFMA 32x32x16, 64-wide wavefronts, KV tiles staged through LDS.
 //
-// Work decomposition.  A workgroup (4 wavefronts) owns one (sequence, KV head,
-// range of cache rows, block of up to 4 grouped query heads); wavefront w holds the
-// T <= 64 tree rows of query head g = 4*block + w.  The cache rows [0, ctx_len +
-// n_nodes) of a sequence are cut into splits of keys_per_split rows so that enough
-// workgroups exist to pull from HBM on every CU; each split leaves an unnormalised
-// partial (running max, sum, output) that a second small kernel merges.  K and V
-// are read from HBM once per (split, query block), 16 bytes per lane, coalesced.
-//
 // Inside a wavefront everything is kept transposed: S^T = K Q^T (keys x queries)
 // and O^T = V^T P^T (head-dim x queries).  With the MFMA accumulator layout a lane
 // then owns ONE query column: its softmax statistics need no cross-lane traffic
 // beyond one exchange with lane^32, the rescaling factor is lane-local, and the
 // exponentiated scores already sit in the register order the next MFMA wants as
 // its B operand (the key order inside a 16-key step is permuted consistently for
-// P^T and V^T, which a contraction does not care about).
+// P^T and V^T, which a contraction does not care about).  A wavefront handles the
+// T <= 64 tree rows of one query head against tiles of 64 cache rows; the running
+// output is rescaled only when some lane's maximum actually moved.
 //
 // The ancestor mask is never materialised in memory: each lane walks parents[]
 // once for its query row and keeps the ancestor set as one 64-bit word; a tile
 // that lies entirely in the prefix skips masking altogether.
+//
+// Two work decompositions share that wavefront routine:
+//
+//  * key-split (small caches, e.g. one 8B-class sequence: the KV of all heads fits
+//    the L2s several times over).  A workgroup owns (sequence, QUERY head, range of
+//    cache rows); its four wavefronts take different 64-row tiles of that range,
+//    each staging its own tiles in a private LDS region (no workgroup barrier in
+//    the main loop), and are merged through LDS.  Cutting the rows four ways
+//    inside a workgroup keeps the number of cross-workgroup partials (the
+//    expensive part: T*D fp32 per split) four times lower for the same number of
+//    busy CUs.  The workgroup whose arrival ticket is the last of its head merges
+//    the splits; there is no second launch.
+//
+//  * group-share (large caches, e.g. long contexts and batches: KV must come from
+//    HBM exactly once).  A workgroup owns (sequence, KV head, range of cache rows,
+//    block of up to 4 grouped query heads); its wavefronts are the query heads and
+//    share every K/V tile through LDS.  Splits are merged by a small second kernel.
 #include "radar_device.h"
 
 namespace radar {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));     // a 16-byte load/store unit kept in registers
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kAttnThreads = 256;
 constexpr int kAttnWaves = 4;
@@ -34,6 +48,7 @@ constexpr int kKT = 64;                    // cache rows per LDS tile
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegBig = -1.0e30f;        // finite stand-in for "no score yet" (log2 units)
+constexpr int kAttnCounterStride = 16;     // arrival counters 64 B apart
 
 struct AttnArgs {
     const __bf16 *q, *k, *v;
@@ -42,17 +57,18 @@ struct AttnArgs {
     float *lse;
     int B, T, Hq, Hkv, G, S, kps, max_splits, n_qblk;
     int64_t q_sb, q_st, q_sh, kv_sb, kv_sh, kv_ss, o_sb, o_st, o_sh;
-    float scale_log2;                      // softmax scale * log2(e)
-    float *part_o;                         // [B][Hq][max_splits][D][64]
-    float *part_ml;                        // [B][Hq][max_splits][2][64]
+    float scale_log2;                      // softmax scale * log2(e), > 0
+    unsigned int *counters;                // key-split: [(b*Hq + h) * kAttnCounterStride]
+    float *part_o;                         // key-split: [B][Hq][max_splits][64][D]; group-share: [..][D][64]
+    float *part_ml;                        // key-split: [B][Hq][max_splits][64][2]; group-share: [..][2][64]
 };
 
-// byte offset of the 16-byte chunk `chunk` of cache row `key` in the K tile
+// byte offset of the 16-byte chunk `chunk` of cache row `key` in a K tile
 template <int D>
 __device__ __forceinline__ int ks_off(int key, int chunk) {
     return key * (D * 2) + ((chunk ^ (key & 7)) << 4);
 }
-// byte offset of element (d, pos) of the transposed V tile; pos = permuted key slot.
+// byte offset of element (d, pos) of a transposed V tile; pos = permuted key slot.
 // 16-byte groups of a row are XOR-swizzled so that both the transposing writes
 // (lanes differ in d/8) and the operand reads (lanes differ in d) spread over banks.
 __device__ __forceinline__ int vt_off(int d, int pos) {
@@ -65,20 +81,423 @@ __device__ __forceinline__ int key_slot(int kappa) {
     return (kappa & ~12) | ((kappa & 4) << 1) | ((kappa & 8) >> 1);
 }
 
+// v = keep ? v : 0 without a branch (a select after a load tempts the compiler into a
+// conditional load, and conditional loads into register arrays wreck register allocation)
+__device__ __forceinline__ void and_mask(u32x4 &v, bool keep) {
+    v &= 0u - (uint32_t)keep;
+}
+
+// Ancestor word of tree row i (bit a set <=> a is i or an ancestor of i).  par[] holds the
+// sequence's parents in LDS.  Terminates and stays in bounds for any content: the chain is
+// followed only while it strictly decreases.
+__device__ __forceinline__ uint64_t ancestor_word(const int *par, int i) {
+    uint64_t m = 1ull << i;
+    int guard = i, p = par[i];
+    while (p >= 0 && p < guard) { m |= 1ull << p; guard = p; p = par[p];}
+    return m;
+}
+
+// Packs four 16-byte V rows (keys 4*kg .. 4*kg+3, elements 8*ch .. 8*ch+7) into the transposed tile.
+__device__ __forceinline__ void store_vt4(unsigned char *Vt, int ch, int kg, const u32x4 (&v)[4]) {
+    const int pos0 = key_slot(kg * 4);
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {
+        // elements 2*e2 (low halves) and 2*e2+1 (high halves) of the four keys
+        u32x2 lo, hi;
+        lo[0] = (v[0][e2] & 0xffffu) | (v[1][e2] << 16);
+        lo[1] = (v[2][e2] & 0xffffu) | (v[3][e2] << 16);
+        hi[0] = (v[0][e2] >> 16) | (v[1][e2] & 0xffff0000u);
+        hi[1] = (v[2][e2] >> 16) | (v[3][e2] & 0xffff0000u);
+        *reinterpret_cast<u32x2 *>(Vt + vt_off(ch * 8 + 2 * e2, pos0)) = lo;
+        *reinterpret_cast<u32x2 *>(Vt + vt_off(ch * 8 + 2 * e2 + 1, pos0)) = hi;
+    }
+}
+
+// One wavefront, one 64-row tile that sits in LDS (Ks row-major swizzled, Vt transposed):
+// scores, masked online softmax, and the update of the transposed output accumulators.
+// The head's query rows also sit in LDS (Qs, 64 x D bf16 in the K tile's swizzled layout)
+// and are fetched as MFMA B operands per 32-query block: holding them in registers for
+// the whole kernel costs 64 VGPRs that the staging of the next tile needs more.
+//   t0        cache row of the tile's first key;  L = prefix length;  kend = end of this range
+//   first     true if the accumulators are still zero (no rescaling needed)
 template <int D, int NQB>
-__global__ __launch_bounds__(kAttnThreads) void tree_attn_split_kernel(AttnArgs a) {
+__device__ __forceinline__ void wave_tile(const unsigned char *Ks, const unsigned char *Vt,
+                                          const unsigned char *Qs, floatx16 (&oacc)[D / 32][NQB],
+                                          float (&m_run)[NQB], float (&l_run)[NQB], const uint64_t (&anc)[NQB],
+                                          int t0, int L, int kend, bool first, float scale_log2) {
+    constexpr int KSTEPS = D / 16, DB = D / 32;
+    const int lane = lane_id();
+    const int j32 = lane & 31, g2 = lane >> 5;
+    const bool need_mask = (t0 + kKT > L) || (t0 + kKT > kend);
+
+    // ---- per 32-query block: S^T = K Q^T for the 64 keys, then the online softmax.  The blocks are
+    // taken one after the other (K operands are read from LDS once per block) so that only one
+    // block's scores are live next to the accumulators.
+    // Register r of sub-tile `sub` is key 32*sub + 8*(r/4) + 4*g2 + r%4.
+    bf16x8 pk[NQB][2][2];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+        bf16x8 qop[KSTEPS];                  // lane (query j32 of the block, half g2): d = 16*st + 8*g2 .. +8
+#pragma unroll
+        for (int st = 0; st < KSTEPS; ++st)
+            qop[st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(Qs + ks_off<D>(32 * qb + j32, 2 * st + g2)));
+        floatx16 sacc[2];
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sacc[sub][r] = 0.f;
+#pragma unroll
+            for (int st = 0; st < KSTEPS; ++st) {
+                const u32x4 raw = *reinterpret_cast<const u32x4 *>(Ks + ks_off<D>(32 * sub + j32, 2 * st + g2));
+                sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), qop[st],
+                                                                    sacc[sub], 0, 0, 0);
+            }
+        }
+        if (need_mask) {                                             // wave-uniform; prefix tiles skip it
+            // bit kappa of `allow`: may this lane's query see key t0 + kappa?  prefix rows, then the
+            // ancestor word shifted to where the tree rows sit in this tile, cut at the range end
+            const int pre = L - t0;                                  // prefix keys in this tile (may be <= 0 or >= 64)
+            uint64_t allow = pre >= 64 ? ~0ull : (pre > 0 ? ((1ull << pre) - 1) : 0ull);
+            if (pre > -64 && pre < 64) allow |= pre >= 0 ? (anc[qb] << pre) : (anc[qb] >> (-pre));
+            const int len = kend - t0;
+            if (len < 64) allow &= len > 0 ? ((1ull << len) - 1) : 0ull;
+            allow >>= 4 * g2;
+            const uint32_t aw[2] = {(uint32_t)allow, (uint32_t)(allow >> 32)};
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    sacc[sub][r] = ((aw[sub] >> (8 * (r >> 2) + (r & 3))) & 1u) ? sacc[sub][r] : -INFINITY;
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[sub][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run[qb], mx * scale_log2);     // scale_log2 > 0; -inf stays -inf
+        if (!first) {
+            const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
+            l_run[qb] *= alpha;
+            if (__any(alpha != 1.0f)) {                              // wave-uniform: most tiles skip this
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
+                    __builtin_amdgcn_sched_barrier(0);        // one 16-register block at a time: keeps the
+                }                                             // accumulator shuffling from exhausting VGPRs
+            }
+        }
+        m_run[qb] = m_new;
+        float rs = 0.f;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[sub][r], scale_log2, -m_new));
+                rs += p;
+                pk[qb][sub][r >> 3][r & 7] = (__bf16)p;
+            }
+        l_run[qb] += rs;
+    }
+
+    // ---- O^T += V^T P^T
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const u32x4 raw = *reinterpret_cast<const u32x4 *>(Vt + vt_off(32 * db + j32, 32 * sub + 16 * s2 + 8 * g2));
+                const bf16x8 va = __builtin_bit_cast(bf16x8, raw);
+#pragma unroll
+                for (int qb = 0; qb < NQB; ++qb)
+                    oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pk[qb][sub][s2], oacc[db][qb], 0, 0, 0);
+            }
+}
+
+// Global -> register staging of one 64-row K/V tile by NT cooperating lanes (lane number t), and
+// the register -> LDS store.  Branch-free: rows past the range re-read the last valid row; V is
+// zeroed afterwards (0 * anything must stay 0), K is masked by the softmax.
+template <int D, int NT>
+struct TileRegs {
+    static constexpr int CH = D / 8;
+    static constexpr int KL = kKT * CH / NT;                               // 16-byte K loads per lane
+    static constexpr int VITEMS = CH * (kKT / 4);                          // (chunk, 4-key group) items
+    static constexpr int VP = (VITEMS + NT - 1) / NT;                      // items per lane
+    u32x4 k[KL];
+    u32x4 v[VP][4];
+};
+
+template <int D, int NT>
+__device__ __forceinline__ void load_tile(TileRegs<D, NT> &r, const __bf16 *kbase, const __bf16 *vbase, int kv_ss,
+                                          int t0, int kend, int t) {
+    constexpr int CH = D / 8;
+#pragma unroll
+    for (int i = 0; i < TileRegs<D, NT>::KL; ++i) {
+        const int c = i * NT + t;
+        const int kpos = min(t0 + c / CH, kend - 1);
+        r.k[i] = *reinterpret_cast<const u32x4 *>(kbase + (uint32_t)(kpos * kv_ss + (c % CH) * 8));
+    }
+#pragma unroll
+    for (int ps = 0; ps < TileRegs<D, NT>::VP; ++ps) {
+        const int item = min(ps * NT + t, TileRegs<D, NT>::VITEMS - 1);
+        const int ch = item % CH, kg = item / CH;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int kpos = t0 + kg * 4 + i;
+            u32x4 v = *reinterpret_cast<const u32x4 *>(vbase + (uint32_t)(min(kpos, kend - 1) * kv_ss + ch * 8));
+            and_mask(v, kpos < kend);
+            r.v[ps][i] = v;
+        }
+    }
+}
+
+template <int D, int NT>
+__device__ __forceinline__ void store_tile(const TileRegs<D, NT> &r, unsigned char *Ks, unsigned char *Vt, int t) {
+    constexpr int CH = D / 8;
+#pragma unroll
+    for (int i = 0; i < TileRegs<D, NT>::KL; ++i) {
+        const int c = i * NT + t;
+        *reinterpret_cast<u32x4 *>(Ks + ks_off<D>(c / CH, c % CH)) = r.k[i];
+    }
+#pragma unroll
+    for (int ps = 0; ps < TileRegs<D, NT>::VP; ++ps) {
+        const int item = ps * NT + t;
+        if (item < TileRegs<D, NT>::VITEMS) store_vt4(Vt, item % CH, item / CH, r.v[ps]);
+    }
+}
+
+// Stages the 64 x D query tile of head h into LDS (swizzled like a K tile); rows >= T are zero.
+// `nthreads` lanes numbered `t` cooperate (a wavefront or the whole workgroup).
+template <int D>
+__device__ __forceinline__ void stage_q(const AttnArgs &a, int b, int h, bool active, unsigned char *Qs, int t, int nthreads) {
+    constexpr int CH = D / 8;
+    const __bf16 *qbase = a.q + (size_t)b * a.q_sb + (size_t)h * a.q_sh;
+    for (int c = t; c < 64 * CH; c += nthreads) {
+        const int row = c / CH, ch = c % CH;
+        u32x4 raw = *reinterpret_cast<const u32x4 *>(qbase + (uint32_t)(min(row, a.T - 1) * (int)a.q_st + ch * 8));
+        and_mask(raw, active && row < a.T);
+        *reinterpret_cast<u32x4 *>(Qs + ks_off<D>(row, ch)) = raw;
+    }
+}
+
+// ===================================================================== key-split kernel
+template <int D>
+struct KsLayout {
+    static constexpr int MROW = D + 4;                           // floats per merge row (padded)
+    static constexpr int WAVE_BYTES = 64 * MROW * 4;             // >= tile bytes (2 * 64 * D * 2)
+    static constexpr int Q_OFF = kAttnWaves * WAVE_BYTES;        // the head's 64 x D query tile (bf16, swizzled)
+    static constexpr int ML_OFF = Q_OFF + 64 * D * 2;            // float [4][2][64]
+    static constexpr int PAR_OFF = ML_OFF + kAttnWaves * 2 * 64 * 4;
+    static constexpr int TICKET_OFF = PAR_OFF + RADAR_T_MAX * 4;
+    static constexpr int BYTES = TICKET_OFF + 16;
+};
+
+template <int D, int NQB>
+__global__ __launch_bounds__(kAttnThreads) void tree_attn_ks_kernel(AttnArgs a) {
+    constexpr int CH = D / 8, DB = D / 32;
+    constexpr int KL = kKT * CH / kWave;                         // 16-byte K loads per lane per tile
+    constexpr int VP = CH * (kKT / 4) / kWave;                   // 4-key V items per lane per tile
+    constexpr int DQ = D / 4;                                    // floats per lane in the merges
+    using Lay = KsLayout<D>;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
+    const int sp = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int hk = h / a.G;
+    const int L = a.ctx_lens[b];
+    int nn = a.n_nodes ? a.n_nodes[b] : a.T;
+    nn = max(1, min(nn, a.T));
+    const int total = min(L + nn, a.S);                          // never read past the cache the caller described
+    const int kbeg = sp * a.kps;
+    if (L < 0 || kbeg >= total) return;
+    const int kend = min(total, kbeg + a.kps);
+    const int nsplit = (total + a.kps - 1) / a.kps;
+    const int j32 = lane & 31, g2 = lane >> 5;
+
+    unsigned char *Ks = smem + w * Lay::WAVE_BYTES;
+    unsigned char *Vt = Ks + kKT * D * 2;
+    float *ml = reinterpret_cast<float *>(smem + Lay::ML_OFF);
+    int *s_par = reinterpret_cast<int *>(smem + Lay::PAR_OFF);
+    unsigned int *s_ticket = reinterpret_cast<unsigned int *>(smem + Lay::TICKET_OFF);
+
+    const __bf16 *kbase = a.k + (size_t)b * a.kv_sb + (size_t)hk * a.kv_sh;
+    const __bf16 *vbase = a.v + (size_t)b * a.kv_sb + (size_t)hk * a.kv_sh;
+    const int kv_ss = (int)a.kv_ss;          // 32-bit offsets inside one head's cache (checked on the host)
+    const int ntiles = (kend - kbeg + kKT - 1) / kKT;
+
+    TileRegs<D, kWave> regs;                                     // staging by ONE wavefront
+
+    // every load this wavefront needs first is issued before anything waits.  The query tile
+    // is the same for the four wavefronts: it is staged once in LDS and read back as MFMA
+    // operands after the K/V staging registers have been released.
+    if (w < ntiles) load_tile<D, kWave>(regs, kbase, vbase, kv_ss, kbeg + w * kKT, kend, lane);
+    stage_q<D>(a, b, h, true, smem + Lay::Q_OFF, tid, kAttnThreads);
+    if (tid < RADAR_T_MAX) s_par[tid] = a.parents[(size_t)b * a.T + min(tid, nn - 1)];
+    __syncthreads();
+    uint64_t anc[NQB];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+        const int i = 32 * qb + j32;
+        anc[qb] = (kend > L && i < nn) ? ancestor_word(s_par, i) : 0ull;
+    }
+
+    floatx16 oacc[DB][NQB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[db][qb][r] = 0.f;
+    float m_run[NQB], l_run[NQB];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) { m_run[qb] = kNegBig; l_run[qb] = 0.f; }
+
+    // ---- this wavefront's tiles: w, w+4, ...  (private LDS region: no workgroup barrier)
+    for (int t = w; t < ntiles; t += kAttnWaves) {
+        const int t0 = kbeg + t * kKT;
+        if (t != w) load_tile<D, kWave>(regs, kbase, vbase, kv_ss, t0, kend, lane);                                // (the first tile's loads were issued up front;
+                                                                  // staging registers are not kept across the compute)
+        wave_lds_sync();                                          // previous tile's LDS reads are done
+        store_tile<D, kWave>(regs, Ks, Vt, lane);
+        wave_lds_sync();
+        wave_tile<D, NQB>(Ks, Vt, smem + Lay::Q_OFF, oacc, m_run, l_run, anc, t0, L, kend, t == w, a.scale_log2);
+    }
+
+    // ---- merge the four wavefronts through LDS (each writes its own region, all read all)
+    wave_lds_sync();
+    {
+        float *mo = reinterpret_cast<float *>(smem + w * Lay::WAVE_BYTES);
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) {
+            const int i = 32 * qb + j32;
+            const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32);
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const float4 v = make_float4(oacc[db][qb][4 * r4], oacc[db][qb][4 * r4 + 1],
+                                                 oacc[db][qb][4 * r4 + 2], oacc[db][qb][4 * r4 + 3]);
+                    *reinterpret_cast<float4 *>(mo + i * Lay::MROW + 32 * db + 8 * r4 + 4 * g2) = v;
+                }
+            if (g2 == 0) { ml[(w * 2 + 0) * 64 + i] = m_run[qb]; ml[(w * 2 + 1) * 64 + i] = l_tot; }
+        }
+        if (NQB == 1 && g2 == 0) { ml[(w * 2 + 0) * 64 + 32 + j32] = kNegBig; ml[(w * 2 + 1) * 64 + 32 + j32] = 0.f; }
+    }
+    __syncthreads();
+
+    const int i = tid >> 2, dq = tid & 3;                         // merge role: query row, quarter of the head dim
+    float acc[DQ];
+    float M = kNegBig, Lsum = 0.f;
+    {
+        float mw[kAttnWaves], wg[kAttnWaves];
+#pragma unroll
+        for (int ww = 0; ww < kAttnWaves; ++ww) { mw[ww] = ml[(ww * 2) * 64 + i]; M = fmaxf(M, mw[ww]); }
+#pragma unroll
+        for (int ww = 0; ww < kAttnWaves; ++ww) {
+            wg[ww] = __builtin_amdgcn_exp2f(mw[ww] - M);
+            Lsum += wg[ww] * ml[(ww * 2 + 1) * 64 + i];
+        }
+#pragma unroll
+        for (int d = 0; d < DQ; ++d) acc[d] = 0.f;
+        if (NQB == 2 || i < 32) {
+#pragma unroll
+            for (int ww = 0; ww < kAttnWaves; ++ww) {
+                const float *mo = reinterpret_cast<const float *>(smem + ww * Lay::WAVE_BYTES) + i * Lay::MROW + dq * DQ;
+#pragma unroll
+                for (int d4 = 0; d4 < DQ / 4; ++d4) {
+                    const float4 v = *reinterpret_cast<const float4 *>(mo + 4 * d4);
+                    acc[4 * d4 + 0] += wg[ww] * v.x; acc[4 * d4 + 1] += wg[ww] * v.y;
+                    acc[4 * d4 + 2] += wg[ww] * v.z; acc[4 * d4 + 3] += wg[ww] * v.w;
+                }
+            }
+        }
+    }
+
+    auto write_out = [&](float Mv, float Lv) {
+        if (i >= a.T) return;
+        __bf16 *orow = a.out + (size_t)b * a.o_sb + (size_t)i * a.o_st + (size_t)h * a.o_sh + dq * DQ;
+        const float inv = (i < nn && Lv > 0.f) ? 1.0f / Lv : 0.f;
+#pragma unroll
+        for (int c = 0; c < DQ / 8; ++c) {
+            bf16x8 o8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o8[e] = (__bf16)(i < nn ? acc[8 * c + e] * inv : 0.f);
+            *reinterpret_cast<bf16x8 *>(orow + 8 * c) = o8;
+        }
+        if (a.lse && dq == 0)
+            a.lse[((size_t)b * a.T + i) * a.Hq + h] = (i < nn) ? (Mv + __builtin_amdgcn_logf(Lv)) * kLn2 : 0.f;
+    };
+
+    if (nsplit == 1) { write_out(M, Lsum); return; }
+
+    // ---- hand the workgroup's partial over (device-scope stores), take a ticket
+    const size_t unit0 = ((size_t)b * a.Hq + h) * a.max_splits;
+    {
+        uint64_t *po = reinterpret_cast<uint64_t *>(a.part_o + ((unit0 + sp) * 64 + i) * D + dq * DQ);
+#pragma unroll
+        for (int e = 0; e < DQ / 2; ++e)
+            store_shared_result(po + e, (uint64_t)__float_as_uint(acc[2 * e]) | ((uint64_t)__float_as_uint(acc[2 * e + 1]) << 32));
+        if (dq == 0)
+            store_shared_result(reinterpret_cast<uint64_t *>(a.part_ml) + (unit0 + sp) * 64 + i,
+                                (uint64_t)__float_as_uint(M) | ((uint64_t)__float_as_uint(Lsum) << 32));
+    }
+    unsigned int *counter = &a.counters[((size_t)b * a.Hq + h) * kAttnCounterStride];
+    if (publish_then_ticket(counter, s_ticket) != (unsigned int)(nsplit - 1)) return;
+    if (tid == 0) store_shared_result(counter, 0u);               // leave the counter clean for the next call
+
+    // ---- last workgroup of this (sequence, head): merge the splits, four at a time so that
+    // all loads of a batch are in flight together
+    M = kNegBig; Lsum = 0.f;
+#pragma unroll
+    for (int d = 0; d < DQ; ++d) acc[d] = 0.f;
+    for (int s0 = 0; s0 < nsplit; s0 += 4) {
+        uint64_t mlv[4];
+        uint64_t ov[4][DQ / 2];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int sc = min(s0 + j, nsplit - 1);
+            mlv[j] = load_shared_result(reinterpret_cast<const uint64_t *>(a.part_ml) + (unit0 + sc) * 64 + i);
+            const uint64_t *po = reinterpret_cast<const uint64_t *>(a.part_o + ((unit0 + sc) * 64 + i) * D + dq * DQ);
+#pragma unroll
+            for (int e = 0; e < DQ / 2; ++e) ov[j][e] = load_shared_result(po + e);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool valid = s0 + j < nsplit;
+            const float ms = valid ? __uint_as_float((uint32_t)mlv[j]) : kNegBig;
+            const float ls = valid ? __uint_as_float((uint32_t)(mlv[j] >> 32)) : 0.f;
+            const float Mn = fmaxf(M, ms);
+            const float aold = __builtin_amdgcn_exp2f(M - Mn);
+            const float wnew = valid ? __builtin_amdgcn_exp2f(ms - Mn) : 0.f;
+            Lsum = Lsum * aold + wnew * ls;
+#pragma unroll
+            for (int e = 0; e < DQ / 2; ++e) {
+                acc[2 * e] = acc[2 * e] * aold + wnew * __uint_as_float((uint32_t)ov[j][e]);
+                acc[2 * e + 1] = acc[2 * e + 1] * aold + wnew * __uint_as_float((uint32_t)(ov[j][e] >> 32));
+            }
+            M = Mn;
+        }
+    }
+    write_out(M, Lsum);
+}
+
+// ===================================================================== group-share kernel
+template <int D, int NQB>
+__global__ __launch_bounds__(kAttnThreads) void tree_attn_gs_kernel(AttnArgs a) {
     constexpr int CH = D / 8;               // 16-byte chunks per cache row
-    constexpr int KSTEPS = D / 16;          // MFMA k-steps of Q K^T
     constexpr int DB = D / 32;              // 32-row blocks of O^T
     constexpr int KLOADS = kKT * CH / kAttnThreads;     // 16-byte K loads per lane per tile
-    constexpr int VKEYS = 4;                              // keys packed per transposed V write
-    constexpr int VITEMS = CH * (kKT / VKEYS);            // (chunk, 4-key group) work items per tile
+    constexpr int VITEMS = CH * (kKT / 4);                // (chunk, 4-key group) work items per tile
     constexpr int VPASSES = (VITEMS + kAttnThreads - 1) / kAttnThreads;
     static_assert(KLOADS >= 1 && kKT * CH % kAttnThreads == 0, "tile too small for 256 lanes");
 
-    __shared__ __attribute__((aligned(16))) unsigned char Ks[kKT * D * 2];
-    __shared__ __attribute__((aligned(16))) unsigned char Vt[D * kKT * 2];
-    __shared__ int s_par[RADAR_T_MAX];
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char *Ks = smem;                                  // [64][D] bf16, swizzled
+    unsigned char *Vt = smem + kKT * D * 2;                    // [D][64] bf16, transposed + swizzled
+    unsigned char *Qs = smem + 2 * kKT * D * 2 + threadIdx.x / kWave * (64 * D * 2);   // this wavefront's head
+    int *s_par = reinterpret_cast<int *>(smem + (2 + kAttnWaves) * kKT * D * 2);
 
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int sp = blockIdx.x;
@@ -98,34 +517,20 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_split_kernel(AttnArgs 
     const int h = hk * a.G + (active ? g : 0);
     const int j32 = lane & 31, g2 = lane >> 5;
 
-    // ---- parents -> LDS, ancestor words (only if this split reaches the tree rows)
-    if (tid < RADAR_T_MAX) s_par[tid] = (tid < nn) ? a.parents[(size_t)b * a.T + tid] : -1;
+    const __bf16 *kbase = a.k + (size_t)b * a.kv_sb + (size_t)hk * a.kv_sh;
+    const __bf16 *vbase = a.v + (size_t)b * a.kv_sb + (size_t)hk * a.kv_sh;
+    const int kv_ss = (int)a.kv_ss;          // 32-bit offsets inside one head's cache (checked on the host)
+
+    TileRegs<D, kAttnThreads> regs;                       // staging by the whole workgroup
+    load_tile<D, kAttnThreads>(regs, kbase, vbase, kv_ss, kbeg, kend, tid);
+    stage_q<D>(a, b, h, active, Qs, lane, kWave);
+    if (tid < RADAR_T_MAX) s_par[tid] = a.parents[(size_t)b * a.T + min(tid, nn - 1)];
     __syncthreads();
     uint64_t anc[NQB];
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
-        anc[qb] = 0;
         const int i = 32 * qb + j32;
-        if (kend > L && i < nn) {
-            uint64_t m = 1ull << i;
-            int guard = i, p = s_par[i];
-            while (p >= 0 && p < guard) { m |= 1ull << p; guard = p; p = s_par[p]; }
-            anc[qb] = m;
-        }
-    }
-
-    // ---- Q as MFMA B operands: lane (query j32 of block qb, half g2) holds d = 16*step + 8*g2 .. +8
-    bf16x8 qreg[KSTEPS][NQB];
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-        const int i = 32 * qb + j32;
-        const __bf16 *qrow = a.q + (size_t)b * a.q_sb + (size_t)i * a.q_st + (size_t)h * a.q_sh;
-#pragma unroll
-        for (int st = 0; st < KSTEPS; ++st) {
-            uint4 raw = make_uint4(0, 0, 0, 0);
-            if (active && i < a.T) raw = *reinterpret_cast<const uint4 *>(qrow + 16 * st + 8 * g2);
-            qreg[st][qb] = __builtin_bit_cast(bf16x8, raw);
-        }
+        anc[qb] = (kend > L && i < nn) ? ancestor_word(s_par, i) : 0ull;
     }
 
     floatx16 oacc[DB][NQB];
@@ -139,140 +544,14 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_split_kernel(AttnArgs 
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) { m_run[qb] = kNegBig; l_run[qb] = 0.f; }
 
-    const __bf16 *kbase = a.k + (size_t)b * a.kv_sb + (size_t)hk * a.kv_sh;
-    const __bf16 *vbase = a.v + (size_t)b * a.kv_sb + (size_t)hk * a.kv_sh;
-
-    // global -> register staging of one tile
-    uint4 kreg[KLOADS];
-    uint4 vreg[VPASSES][VKEYS];
-    auto load_tile = [&](int t0) {
-#pragma unroll
-        for (int i = 0; i < KLOADS; ++i) {
-            const int c = i * kAttnThreads + tid;
-            const int key = c / CH, ch = c % CH;
-            const int kpos = t0 + key;
-            kreg[i] = make_uint4(0, 0, 0, 0);
-            if (kpos < kend) kreg[i] = *reinterpret_cast<const uint4 *>(kbase + (size_t)kpos * a.kv_ss + ch * 8);
-        }
-#pragma unroll
-        for (int ps = 0; ps < VPASSES; ++ps) {
-            const int item = ps * kAttnThreads + tid;
-            const int ch = item % CH, kg = item / CH;
-#pragma unroll
-            for (int i = 0; i < VKEYS; ++i) {
-                const int kpos = t0 + kg * VKEYS + i;
-                vreg[ps][i] = make_uint4(0, 0, 0, 0);
-                if (item < VITEMS && kpos < kend) vreg[ps][i] = *reinterpret_cast<const uint4 *>(vbase + (size_t)kpos * a.kv_ss + ch * 8);
-            }
-        }
-    };
-    auto store_tile = [&]() {
-#pragma unroll
-        for (int i = 0; i < KLOADS; ++i) {
-            const int c = i * kAttnThreads + tid;
-            const int key = c / CH, ch = c % CH;
-            *reinterpret_cast<uint4 *>(Ks + ks_off<D>(key, ch)) = kreg[i];
-        }
-#pragma unroll
-        for (int ps = 0; ps < VPASSES; ++ps) {
-            const int item = ps * kAttnThreads + tid;
-            if (item >= VITEMS) break;
-            const int ch = item % CH, kg = item / CH;
-            const int pos0 = key_slot(kg * VKEYS);
-            const uint32_t w0[4] = {vreg[ps][0].x, vreg[ps][0].y, vreg[ps][0].z, vreg[ps][0].w};
-            const uint32_t w1[4] = {vreg[ps][1].x, vreg[ps][1].y, vreg[ps][1].z, vreg[ps][1].w};
-            const uint32_t w2[4] = {vreg[ps][2].x, vreg[ps][2].y, vreg[ps][2].z, vreg[ps][2].w};
-            const uint32_t w3[4] = {vreg[ps][3].x, vreg[ps][3].y, vreg[ps][3].z, vreg[ps][3].w};
-#pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {
-                // elements 2*e2 (low halves) and 2*e2+1 (high halves) of the four keys
-                uint2 lo, hi;
-                lo.x = (w0[e2] & 0xffffu) | (w1[e2] << 16);
-                lo.y = (w2[e2] & 0xffffu) | (w3[e2] << 16);
-                hi.x = (w0[e2] >> 16) | (w1[e2] & 0xffff0000u);
-                hi.y = (w2[e2] >> 16) | (w3[e2] & 0xffff0000u);
-                *reinterpret_cast<uint2 *>(Vt + vt_off(ch * 8 + 2 * e2, pos0)) = lo;
-                *reinterpret_cast<uint2 *>(Vt + vt_off(ch * 8 + 2 * e2 + 1, pos0)) = hi;
-            }
-        }
-    };
-
     const int ntiles = (kend - kbeg + kKT - 1) / kKT;
-    load_tile(kbeg);
     for (int t = 0; t < ntiles; ++t) {
         const int t0 = kbeg + t * kKT;
         __syncthreads();                      // previous tile fully consumed
-        store_tile();
+        store_tile<D, kAttnThreads>(regs, Ks, Vt, tid);
         __syncthreads();
-        if (t + 1 < ntiles) load_tile(t0 + kKT);   // in flight while this tile is computed
-        if (!active) continue;
-
-        const bool need_mask = (t0 + kKT > L) || (t0 + kKT > kend);
-#pragma unroll
-        for (int sub = 0; sub < kKT / 32; ++sub) {
-            if (t0 + 32 * sub >= kend) break;
-            // ---- S^T = K Q^T for 32 keys x (32*NQB) queries
-            floatx16 sacc[NQB];
-#pragma unroll
-            for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sacc[qb][r] = 0.f;
-#pragma unroll
-            for (int st = 0; st < KSTEPS; ++st) {
-                const uint4 raw = *reinterpret_cast<const uint4 *>(Ks + ks_off<D>(32 * sub + j32, 2 * st + g2));
-                const bf16x8 ka = __builtin_bit_cast(bf16x8, raw);
-#pragma unroll
-                for (int qb = 0; qb < NQB; ++qb)
-                    sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[st][qb], sacc[qb], 0, 0, 0);
-            }
-            // ---- online softmax; register r of a lane is key 8*(r/4) + 4*g2 + r%4 of this sub-tile
-            bf16x8 pk[NQB][2];
-#pragma unroll
-            for (int qb = 0; qb < NQB; ++qb) {
-                float sv[16];
-                float mx = kNegBig;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float sc = sacc[qb][r] * a.scale_log2;
-                    if (need_mask) {
-                        const int kpos = t0 + 32 * sub + 8 * (r >> 2) + 4 * g2 + (r & 3);
-                        const int rel = kpos - L;
-                        const bool ok = (kpos < kend) && (rel < 0 || ((anc[qb] >> (rel & 63)) & 1ull));
-                        sc = ok ? sc : -INFINITY;
-                    }
-                    sv[r] = sc;
-                    mx = fmaxf(mx, sc);
-                }
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m_run[qb], mx);
-                const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
-                m_run[qb] = m_new;
-                float rs = 0.f;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float p = __builtin_amdgcn_exp2f(sv[r] - m_new);
-                    rs += p;
-                    pk[qb][r >> 3][r & 7] = (__bf16)p;
-                }
-                l_run[qb] = l_run[qb] * alpha + rs;
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
-            }
-            // ---- O^T += V^T P^T
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-#pragma unroll
-                for (int s2 = 0; s2 < 2; ++s2) {
-                    const uint4 raw = *reinterpret_cast<const uint4 *>(Vt + vt_off(32 * db + j32, 32 * sub + 16 * s2 + 8 * g2));
-                    const bf16x8 va = __builtin_bit_cast(bf16x8, raw);
-#pragma unroll
-                    for (int qb = 0; qb < NQB; ++qb)
-                        oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pk[qb][s2], oacc[db][qb], 0, 0, 0);
-                }
-            }
-        }
+        if (t + 1 < ntiles) load_tile<D, kAttnThreads>(regs, kbase, vbase, kv_ss, t0 + kKT, kend, tid);   // in flight while this tile is computed
+        if (active) wave_tile<D, NQB>(Ks, Vt, Qs, oacc, m_run, l_run, anc, t0, L, kend, t == 0, a.scale_log2);
     }
     if (!active) return;
 
@@ -289,7 +568,6 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_split_kernel(AttnArgs 
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
-                    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
                     bf16x4 o4;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(i < nn ? oacc[db][qb][4 * r4 + e] * inv : 0.f);
@@ -313,7 +591,8 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_split_kernel(AttnArgs 
     }
 }
 
-// Merges the per-split partials of one (sequence, query head): 64 query rows x D.
+// Merges the group-share kernel's per-split partials of one (sequence, query head): 64 query
+// rows x D.  Splits are taken four at a time so that a batch's loads are in flight together.
 template <int D>
 __global__ __launch_bounds__(kAttnThreads) void tree_attn_merge_kernel(AttnArgs a) {
     const int h = blockIdx.x, b = blockIdx.y;
@@ -329,57 +608,99 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_merge_kernel(AttnArgs 
     const size_t unit0 = ((size_t)b * a.Hq + h) * a.max_splits;
     __bf16 *orow = a.out + (size_t)b * a.o_sb + (size_t)i * a.o_st + (size_t)h * a.o_sh;
     constexpr int DQ = D / 4;
-    typedef __bf16 bf16x8v __attribute__((ext_vector_type(8)));
     if (i >= nn) {
 #pragma unroll
         for (int c = 0; c < DQ / 8; ++c) {
-            bf16x8v z;
+            bf16x8 z;
 #pragma unroll
             for (int e = 0; e < 8; ++e) z[e] = (__bf16)0.f;
-            *reinterpret_cast<bf16x8v *>(orow + part * DQ + 8 * c) = z;
+            *reinterpret_cast<bf16x8 *>(orow + part * DQ + 8 * c) = z;
         }
         if (a.lse && part == 0) a.lse[((size_t)b * a.T + i) * a.Hq + h] = 0.f;
         return;
     }
-    float M = kNegBig;
-    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, a.part_ml[(unit0 + s) * 128 + i]);
+    float M = kNegBig, lsum = 0.f;
     float acc[DQ];
 #pragma unroll
     for (int d = 0; d < DQ; ++d) acc[d] = 0.f;
-    float lsum = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
-        const float ms = a.part_ml[(unit0 + s) * 128 + i];
-        const float ls = a.part_ml[(unit0 + s) * 128 + 64 + i];
-        const float wgt = __builtin_amdgcn_exp2f(ms - M);
-        lsum += wgt * ls;
-        const float *po = a.part_o + (unit0 + s) * (size_t)(D * 64);
+    for (int s0 = 0; s0 < nsplit; s0 += 4) {
+        float ms[4], ls[4], ov[4][DQ];
 #pragma unroll
-        for (int d = 0; d < DQ; ++d) acc[d] += wgt * po[(part * DQ + d) * 64 + i];
+        for (int j = 0; j < 4; ++j) {
+            const int sc = min(s0 + j, nsplit - 1);
+            ms[j] = a.part_ml[(unit0 + sc) * 128 + i];
+            ls[j] = a.part_ml[(unit0 + sc) * 128 + 64 + i];
+            const float *po = a.part_o + (unit0 + sc) * (size_t)(D * 64);
+#pragma unroll
+            for (int d = 0; d < DQ; ++d) ov[j][d] = po[(part * DQ + d) * 64 + i];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool valid = s0 + j < nsplit;
+            const float m = valid ? ms[j] : kNegBig;
+            const float Mn = fmaxf(M, m);
+            const float aold = __builtin_amdgcn_exp2f(M - Mn);
+            const float wnew = valid ? __builtin_amdgcn_exp2f(m - Mn) : 0.f;
+            lsum = lsum * aold + wnew * ls[j];
+#pragma unroll
+            for (int d = 0; d < DQ; ++d) acc[d] = acc[d] * aold + wnew * ov[j][d];
+            M = Mn;
+        }
     }
     const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
 #pragma unroll
     for (int c = 0; c < DQ / 8; ++c) {
-        bf16x8v o8;
+        bf16x8 o8;
 #pragma unroll
         for (int e = 0; e < 8; ++e) o8[e] = (__bf16)(acc[8 * c + e] * inv);
-        *reinterpret_cast<bf16x8v *>(orow + part * DQ + 8 * c) = o8;
+        *reinterpret_cast<bf16x8 *>(orow + part * DQ + 8 * c) = o8;
     }
     if (a.lse && part == 0) a.lse[((size_t)b * a.T + i) * a.Hq + h] = (M + __builtin_amdgcn_logf(lsum)) * kLn2;
 }
 
-static int choose_keys_per_split(const radar_attn_desc *d) {
-    if (d->keys_per_split > 0) return d->keys_per_split;
+// ------------------------------------------------------------------ host-side planning
+struct AttnPlan {
+    bool key_split;
+    int kps, max_splits, n_qblk;
+    size_t off_counters, off_part_o, off_part_ml, bytes;
+};
+
+static AttnPlan plan_attention(const radar_attn_desc *d) {
+    AttnPlan p;
     const int G = d->Hq / d->Hkv;
-    const int n_qblk = (G + kAttnWaves - 1) / kAttnWaves;
-    const long units = (long)d->B * d->Hkv * n_qblk;
-    const long target = 512;                                   // workgroups wanted for 256 CUs
-    long ns = (target + units - 1) / units;
-    if (ns < 1) ns = 1;
-    long kps = ((long)d->S_max + ns - 1) / ns;
-    kps = (kps + kKT - 1) / kKT * kKT;
-    if (kps < 128) kps = 128;
-    if (kps > 2048) kps = 2048;
-    return (int)kps;
+    p.n_qblk = (G + kAttnWaves - 1) / kAttnWaves;
+    // key-split re-reads every KV head G times (from L2): use it while that stays small
+    const double reread_bytes = (double)d->B * d->Hq * d->S_max * d->D * 4.0;
+    p.key_split = d->variant == RADAR_ATTN_KEY_SPLIT || (d->variant == RADAR_ATTN_AUTO && reread_bytes <= 96e6);
+    long kps = d->keys_per_split;
+    if (kps <= 0) {
+        if (p.key_split) {
+            // a multiple of 4 tiles, so that each wavefront gets whole tiles; about 256 workgroups
+            const long units = (long)d->B * d->Hq;
+            long ns = (256 + units - 1) / units;
+            if (ns < 1) ns = 1;
+            kps = ((long)d->S_max + ns - 1) / ns;
+            kps = (kps + 4 * kKT - 1) / (4 * kKT) * (4 * kKT);
+        } else {
+            const long units = (long)d->B * d->Hkv * p.n_qblk;
+            long ns = (512 + units - 1) / units;
+            if (ns < 1) ns = 1;
+            kps = ((long)d->S_max + ns - 1) / ns;
+            kps = (kps + kKT - 1) / kKT * kKT;
+            if (kps < 128) kps = 128;
+            if (kps > 2048) kps = 2048;
+        }
+    }
+    p.kps = (int)kps;
+    p.max_splits = (int)(((long)d->S_max + kps - 1) / kps);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t o = off; off += (bytes + 255) & ~size_t(255); return o; };
+    p.off_counters = take((size_t)d->B * d->Hq * kAttnCounterStride * sizeof(unsigned int));
+    const size_t units = p.max_splits > 1 ? (size_t)d->B * d->Hq * p.max_splits : 0;
+    p.off_part_o = take(units * 64 * d->D * sizeof(float));
+    p.off_part_ml = take(units * 128 * sizeof(float));
+    p.bytes = off;
+    return p;
 }
 
 }  // namespace radar
@@ -391,18 +712,46 @@ static radar_status check_attn_desc(const radar_attn_desc *d) {
     if (d->B < 1 || d->T_max < 1 || d->Hq < 1 || d->Hkv < 1 || d->S_max < 1 || d->Hq % d->Hkv != 0)
         return RADAR_INVALID_ARG;
     if (d->keys_per_split < 0 || d->keys_per_split % kKT != 0) return RADAR_INVALID_ARG;
+    if (d->softmax_scale < 0.f) return RADAR_INVALID_ARG;
+    if (d->variant != RADAR_ATTN_AUTO && d->variant != RADAR_ATTN_KEY_SPLIT && d->variant != RADAR_ATTN_GROUP_SHARE)
+        return RADAR_INVALID_ARG;
     if ((d->D != 64 && d->D != 128) || d->T_max > RADAR_T_MAX) return RADAR_UNSUPPORTED_SHAPE;
-    if (d->B > 65535 || (long)d->Hkv * ((d->Hq / d->Hkv + 3) / 4) > 65535) return RADAR_UNSUPPORTED_SHAPE;
+    if (d->B > 65535 || d->Hq > 65535) return RADAR_UNSUPPORTED_SHAPE;
     return RADAR_OK;
 }
 
 extern "C" size_t radar_tree_attention_workspace_bytes(const radar_attn_desc *d) {
     if (check_attn_desc(d) != RADAR_OK) return 0;
-    const int kps = choose_keys_per_split(d);
-    const size_t max_splits = ((size_t)d->S_max + kps - 1) / kps;
-    size_t bytes = 16384;
-    if (max_splits > 1) bytes += (size_t)d->B * d->Hq * max_splits * ((size_t)d->D * 64 + 128) * sizeof(float);
-    return (bytes + 255) & ~size_t(255);
+    return plan_attention(d).bytes;
+}
+
+template <int D>
+constexpr int gs_smem_bytes() { return (2 + kAttnWaves) * kKT * D * 2 + RADAR_T_MAX * 4; }
+
+template <int D, int NQB>
+static hipError_t launch_gs(const AttnArgs &a, dim3 grid, hipStream_t s) {
+    static bool configured = false;                        // raise the dynamic LDS limit once per instantiation
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_gs_kernel<D, NQB>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, gs_smem_bytes<D>());
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL((tree_attn_gs_kernel<D, NQB>), grid, dim3(kAttnThreads), gs_smem_bytes<D>(), s, a);
+    return hipGetLastError();
+}
+
+template <int D, int NQB>
+static hipError_t launch_ks(const AttnArgs &a, dim3 grid, hipStream_t s) {
+    static bool configured = false;                        // raise the dynamic LDS limit once per instantiation
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_ks_kernel<D, NQB>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, KsLayout<D>::BYTES);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL((tree_attn_ks_kernel<D, NQB>), grid, dim3(kAttnThreads), KsLayout<D>::BYTES, s, a);
+    return hipGetLastError();
 }
 
 extern "C" radar_status radar_tree_attention(const void *q, const void *k_cache, const void *v_cache,
@@ -412,7 +761,8 @@ extern "C" radar_status radar_tree_attention(const void *q, const void *k_cache,
     if (!q || !k_cache || !v_cache || !parents || !ctx_lens || !out || !workspace) return RADAR_INVALID_ARG;
     radar_status st = check_attn_desc(d);
     if (st != RADAR_OK) return st;
-    if (workspace_bytes < radar_tree_attention_workspace_bytes(d)) return RADAR_WORKSPACE_TOO_SMALL;
+    const AttnPlan p = plan_attention(d);
+    if (workspace_bytes < p.bytes) return RADAR_WORKSPACE_TOO_SMALL;
     if (((uintptr_t)workspace & 255) != 0) return RADAR_INVALID_ARG;
 
     AttnArgs a;
@@ -421,9 +771,7 @@ extern "C" radar_status radar_tree_attention(const void *q, const void *k_cache,
     a.parents = parents; a.ctx_lens = ctx_lens; a.n_nodes = n_nodes;
     a.out = static_cast<__bf16 *>(out); a.lse = lse_out;
     a.B = d->B; a.T = d->T_max; a.Hq = d->Hq; a.Hkv = d->Hkv; a.G = d->Hq / d->Hkv; a.S = d->S_max;
-    a.kps = choose_keys_per_split(d);
-    a.max_splits = (d->S_max + a.kps - 1) / a.kps;
-    a.n_qblk = (a.G + kAttnWaves - 1) / kAttnWaves;
+    a.kps = p.kps; a.max_splits = p.max_splits; a.n_qblk = p.n_qblk;
     const int64_t D = d->D;
     a.q_sh = d->q_stride_h ? d->q_stride_h : D;
     a.q_st = d->q_stride_t ? d->q_stride_t : D * d->Hq;
@@ -438,23 +786,35 @@ extern "C" radar_status radar_tree_attention(const void *q, const void *k_cache,
     const uintptr_t al = (uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out;
     const int64_t strides = a.q_sh | a.q_st | a.q_sb | a.kv_ss | a.kv_sh | a.kv_sb | a.o_sh | a.o_st | a.o_sb;
     if ((al & 15) != 0 || (strides & 7) != 0) return RADAR_INVALID_ARG;
+    // the kernels address rows inside one head's cache / one head's queries with 32-bit offsets
+    if (a.kv_ss <= 0 || a.q_st <= 0 || a.kv_ss * (int64_t)d->S_max >= (int64_t(1) << 31) ||
+        a.q_st * (int64_t)d->T_max >= (int64_t(1) << 31))
+        return RADAR_UNSUPPORTED_SHAPE;
     const float scale = d->softmax_scale != 0.f ? d->softmax_scale : 1.0f / sqrtf((float)d->D);
     a.scale_log2 = scale * kLog2e;
     char *ws = static_cast<char *>(workspace);
-    a.part_o = reinterpret_cast<float *>(ws + 16384);
-    a.part_ml = a.part_o + (size_t)d->B * d->Hq * a.max_splits * (size_t)(d->D * 64);
+    a.counters = reinterpret_cast<unsigned int *>(ws + p.off_counters);
+    a.part_o = reinterpret_cast<float *>(ws + p.off_part_o);
+    a.part_ml = reinterpret_cast<float *>(ws + p.off_part_ml);
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const dim3 grid((unsigned)a.max_splits, (unsigned)(a.Hkv * a.n_qblk), (unsigned)a.B), block(kAttnThreads);
+    const dim3 block(kAttnThreads);
     const bool narrow = d->T_max <= 32;
-    if (d->D == 128) {
-        if (narrow) hipLaunchKernelGGL((tree_attn_split_kernel<128, 1>), grid, block, 0, s, a);
-        else        hipLaunchKernelGGL((tree_attn_split_kernel<128, 2>), grid, block, 0, s, a);
-    } else {
-        if (narrow) hipLaunchKernelGGL((tree_attn_split_kernel<64, 1>), grid, block, 0, s, a);
-        else        hipLaunchKernelGGL((tree_attn_split_kernel<64, 2>), grid, block, 0, s, a);
+    if (p.key_split) {
+        const dim3 grid((unsigned)a.max_splits, (unsigned)a.Hq, (unsigned)a.B);
+        hipError_t e;
+        if (d->D == 128) e = narrow ? launch_ks<128, 1>(a, grid, s) : launch_ks<128, 2>(a, grid, s);
+        else             e = narrow ? launch_ks<64, 1>(a, grid, s) : launch_ks<64, 2>(a, grid, s);
+        return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
     }
-    if (hipGetLastError() != hipSuccess) return RADAR_HIP_ERROR;
+    if ((long)a.Hkv * a.n_qblk > 65535) return RADAR_UNSUPPORTED_SHAPE;
+    const dim3 grid((unsigned)a.max_splits, (unsigned)(a.Hkv * a.n_qblk), (unsigned)a.B);
+    {
+        hipError_t e;
+        if (d->D == 128) e = narrow ? launch_gs<128, 1>(a, grid, s) : launch_gs<128, 2>(a, grid, s);
+        else             e = narrow ? launch_gs<64, 1>(a, grid, s) : launch_gs<64, 2>(a, grid, s);
+        if (e != hipSuccess) return RADAR_HIP_ERROR;
+    }
     if (a.max_splits > 1) {
         const dim3 mgrid((unsigned)a.Hq, (unsigned)a.B);
         if (d->D == 128) hipLaunchKernelGGL(tree_attn_merge_kernel<128>, mgrid, block, 0, s, a);
