@@ -130,29 +130,34 @@ __device__ __forceinline__ void wave_tile(const unsigned char *Ks, const unsigne
     const int j32 = lane & 31, g2 = lane >> 5;
     const bool need_mask = (t0 + kKT > L) || (t0 + kKT > kend);
 
-    // ---- per 32-query block: S^T = K Q^T for the 64 keys, then the online softmax.  The blocks are
-    // taken one after the other (K operands are read from LDS once per block) so that only one
-    // block's scores are live next to the accumulators.
+    // Order of work (NQB = 2): scores of block 0, scores of block 1, softmax of block 0, P.V of
+    // block 0, softmax of block 1, P.V of block 1.  Each softmax (vector ALU) is independent of the
+    // MFMAs issued just before it, so the matrix pipe keeps running underneath it; with one
+    // wavefront per SIMD nothing else would hide that time.  K and V operands are read from LDS
+    // once per 32-query block.
     // Register r of sub-tile `sub` is key 32*sub + 8*(r/4) + 4*g2 + r%4.
-    bf16x8 pk[NQB][2][2];
+    floatx16 sacc[NQB][2];
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
         bf16x8 qop[KSTEPS];                  // lane (query j32 of the block, half g2): d = 16*st + 8*g2 .. +8
 #pragma unroll
         for (int st = 0; st < KSTEPS; ++st)
             qop[st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(Qs + ks_off<D>(32 * qb + j32, 2 * st + g2)));
-        floatx16 sacc[2];
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[sub][r] = 0.f;
+            for (int r = 0; r < 16; ++r) sacc[qb][sub][r] = 0.f;
 #pragma unroll
             for (int st = 0; st < KSTEPS; ++st) {
                 const u32x4 raw = *reinterpret_cast<const u32x4 *>(Ks + ks_off<D>(32 * sub + j32, 2 * st + g2));
-                sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), qop[st],
-                                                                    sacc[sub], 0, 0, 0);
+                sacc[qb][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), qop[st],
+                                                                        sacc[qb][sub], 0, 0, 0);
             }
         }
+    }
+
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
         if (need_mask) {                                             // wave-uniform; prefix tiles skip it
             // bit kappa of `allow`: may this lane's query see key t0 + kappa?  prefix rows, then the
             // ancestor word shifted to where the tree rows sit in this tile, cut at the range end
@@ -167,13 +172,13 @@ __device__ __forceinline__ void wave_tile(const unsigned char *Ks, const unsigne
             for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    sacc[sub][r] = ((aw[sub] >> (8 * (r >> 2) + (r & 3))) & 1u) ? sacc[sub][r] : -INFINITY;
+                    sacc[qb][sub][r] = ((aw[sub] >> (8 * (r >> 2) + (r & 3))) & 1u) ? sacc[qb][sub][r] : -INFINITY;
         }
         float mx = -INFINITY;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[sub][r]);
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[qb][sub][r]);
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float m_new = fmaxf(m_run[qb], mx * scale_log2);     // scale_log2 > 0; -inf stays -inf
         if (!first) {
@@ -190,30 +195,29 @@ __device__ __forceinline__ void wave_tile(const unsigned char *Ks, const unsigne
         }
         m_run[qb] = m_new;
         float rs = 0.f;
+        bf16x8 pk[2][2];
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[sub][r], scale_log2, -m_new));
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[qb][sub][r], scale_log2, -m_new));
                 rs += p;
-                pk[qb][sub][r >> 3][r & 7] = (__bf16)p;
+                pk[sub][r >> 3][r & 7] = (__bf16)p;
             }
         l_run[qb] += rs;
-    }
 
-    // ---- O^T += V^T P^T
+        // ---- O^T += V^T P^T for this query block
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
+        for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                const u32x4 raw = *reinterpret_cast<const u32x4 *>(Vt + vt_off(32 * db + j32, 32 * sub + 16 * s2 + 8 * g2));
-                const bf16x8 va = __builtin_bit_cast(bf16x8, raw);
-#pragma unroll
-                for (int qb = 0; qb < NQB; ++qb)
-                    oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pk[qb][sub][s2], oacc[db][qb], 0, 0, 0);
-            }
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    const u32x4 raw = *reinterpret_cast<const u32x4 *>(Vt + vt_off(32 * db + j32, 32 * sub + 16 * s2 + 8 * g2));
+                    oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), pk[sub][s2],
+                                                                           oacc[db][qb], 0, 0, 0);
+                }
+    }
 }
 
 // Global -> register staging of one 64-row K/V tile by NT cooperating lanes (lane number t), and
@@ -270,15 +274,21 @@ __device__ __forceinline__ void store_tile(const TileRegs<D, NT> &r, unsigned ch
 
 // Stages the 64 x D query tile of head h into LDS (swizzled like a K tile); rows >= T are zero.
 // `nthreads` lanes numbered `t` cooperate (a wavefront or the whole workgroup).
-template <int D>
-__device__ __forceinline__ void stage_q(const AttnArgs &a, int b, int h, bool active, unsigned char *Qs, int t, int nthreads) {
-    constexpr int CH = D / 8;
+template <int D, int NT>
+__device__ __forceinline__ void stage_q(const AttnArgs &a, int b, int h, bool active, unsigned char *Qs, int t) {
+    constexpr int CH = D / 8, N = 64 * CH / NT;
     const __bf16 *qbase = a.q + (size_t)b * a.q_sb + (size_t)h * a.q_sh;
-    for (int c = t; c < 64 * CH; c += nthreads) {
-        const int row = c / CH, ch = c % CH;
-        u32x4 raw = *reinterpret_cast<const u32x4 *>(qbase + (uint32_t)(min(row, a.T - 1) * (int)a.q_st + ch * 8));
-        and_mask(raw, active && row < a.T);
-        *reinterpret_cast<u32x4 *>(Qs + ks_off<D>(row, ch)) = raw;
+    u32x4 raw[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {                               // all loads first: one round trip
+        const int c = i * NT + t, row = c / CH, ch = c % CH;
+        raw[i] = *reinterpret_cast<const u32x4 *>(qbase + (uint32_t)(min(row, a.T - 1) * (int)a.q_st + ch * 8));
+        and_mask(raw[i], active && row < a.T);
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const int c = i * NT + t;
+        *reinterpret_cast<u32x4 *>(Qs + ks_off<D>(c / CH, c % CH)) = raw[i];
     }
 }
 
@@ -333,7 +343,7 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_ks_kernel(AttnArgs a) 
     // is the same for the four wavefronts: it is staged once in LDS and read back as MFMA
     // operands after the K/V staging registers have been released.
     if (w < ntiles) load_tile<D, kWave>(regs, kbase, vbase, kv_ss, kbeg + w * kKT, kend, lane);
-    stage_q<D>(a, b, h, true, smem + Lay::Q_OFF, tid, kAttnThreads);
+    stage_q<D, kAttnThreads>(a, b, h, true, smem + Lay::Q_OFF, tid);
     if (tid < RADAR_T_MAX) s_par[tid] = a.parents[(size_t)b * a.T + min(tid, nn - 1)];
     __syncthreads();
     uint64_t anc[NQB];
@@ -523,7 +533,7 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_gs_kernel(AttnArgs a) 
 
     TileRegs<D, kAttnThreads> regs;                       // staging by the whole workgroup
     load_tile<D, kAttnThreads>(regs, kbase, vbase, kv_ss, kbeg, kend, tid);
-    stage_q<D>(a, b, h, active, Qs, lane, kWave);
+    stage_q<D, kWave>(a, b, h, active, Qs, lane);
     if (tid < RADAR_T_MAX) s_par[tid] = a.parents[(size_t)b * a.T + min(tid, nn - 1)];
     __syncthreads();
     uint64_t anc[NQB];
