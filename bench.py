@@ -9,9 +9,13 @@ temperature 1).  Inputs are synthetic, seeded and resident in HBM before timing;
 step uses the next of several input sets whose total size exceeds L2 + Infinity Cache,
 so the kernels read from HBM, not from cache.
 
-Prints one JSON line.  `value` is the attention kernel's achieved HBM bandwidth
-(algorithmic bytes / average kernel time measured with events around each launch in
-the timed region); the expand+accept time per cycle is reported next to it.
+Prints one JSON line.  `value` is the attention call's achieved HBM bandwidth:
+algorithmic bytes / mean time between stream events placed around the call in the
+timed region, less the cost of an empty pair of events.  `roofline` is the same
+bytes over the attention kernel's own mean device duration, taken from HIP events
+that the library attaches to each launch (dispatch begin to end, as in a kernel
+trace); `kernels` lists every kernel of the step that way.  The expand+accept time
+per cycle is reported next to it.
 """
 import argparse
 import json
@@ -153,6 +157,7 @@ def main():
     ev = lambda: torch.cuda.Event(enable_timing=True)
     K, W = args.steps, args.warmup
     marks = [[ev() for _ in range(4)] for _ in range(K)]
+    null_marks = [[ev() for _ in range(2)] for _ in range(K)]
 
     def step(i, m=None):
         cs = cycle_sets[i % len(cycle_sets)]
@@ -167,20 +172,47 @@ def main():
     for i in range(W):
         step(i)
     torch.cuda.synchronize()
+    # per-kernel device durations come from the library's own launch events (dispatch begin/end,
+    # what a kernel trace shows); the phase marks around them add event and launch-gap time
+    b.radar_profile_begin(K * (steps_per_cycle + 8))
     t0 = time.perf_counter()
     for i in range(K):
         step(W + i, marks[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    kern = b.radar_profile_end()
+    for m in null_marks:                       # cost of an empty pair of marks, taken off each phase
+        m[0].record(); m[1].record()
+    torch.cuda.synchronize()
+    null_us = float(np.mean([m[0].elapsed_time(m[1]) for m in null_marks]) * 1e3)
 
     attn_us = np.array([m[0].elapsed_time(m[1]) for m in marks]) * 1e3
     exp_us = np.array([m[1].elapsed_time(m[2]) for m in marks]) * 1e3
     acc_us = np.array([m[2].elapsed_time(m[3]) for m in marks]) * 1e3
-    a_us, e_us, c_us = float(attn_us.mean()), float(exp_us.mean()), float(acc_us.mean())
+    a_us, e_us, c_us = (max(0.0, float(x.mean()) - null_us) for x in (attn_us, exp_us, acc_us))
     attn_gbps = attn_bytes / (a_us * 1e-6) / 1e9 if a_us > 0 else 0.0
     ea_bytes = expand_bytes * steps_per_cycle + accept_bytes
     ea_us = e_us + c_us
     ea_gbps = ea_bytes / (ea_us * 1e-6) / 1e9 if ea_us > 0 else 0.0
+
+    # roofline entries: algorithmic bytes of one launch / that kernel's mean device duration
+    alg_bytes = {"tree_attn_group_share": attn_bytes, "tree_attn_key_split": attn_bytes,
+                 "expand": expand_bytes, "accept": accept_bytes}
+    kernels = []
+    for name, t in sorted(kern.items(), key=lambda kv: -kv[1]["total_us"]):
+        ent = {"kernel": name, "calls_per_step": round(t["calls"] / K, 2), "mean_us": round(t["mean_us"], 2),
+               "min_us": round(t["min_us"], 2), "max_us": round(t["max_us"], 2)}
+        if name in alg_bytes:
+            g = alg_bytes[name] / (t["mean_us"] * 1e-6) / 1e9
+            ent.update(bound="hbm", algorithmic_bytes=alg_bytes[name], achieved=round(g, 1), unit="GB/s",
+                       frac=round(g / PEAK_HBM_GBPS, 4))
+        kernels.append(ent)
+    attn_kernel = next((e for e in kernels if e["kernel"].startswith("tree_attn_") and "achieved" in e), None)
+    roof = {"kernel": None, "bound": "hbm", "achieved": 0.0, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": 0.0,
+            "traffic": None}
+    if attn_kernel:
+        roof.update(kernel=attn_kernel["kernel"], achieved=attn_kernel["achieved"], frac=attn_kernel["frac"],
+                    kernel_us=attn_kernel["mean_us"], algorithmic_bytes=attn_bytes, traffic=read_traffic())
 
     result = {
         "metric": METRIC,
@@ -209,9 +241,9 @@ def main():
         "expand_accept_us_per_step": round(ea_us, 2),
         "expand_accept_gbps": round(ea_gbps, 1),
         "expand_accept_pct_peak_hbm": round(100 * ea_gbps / PEAK_HBM_GBPS, 2),
-        "roofline": {"kernel": "tree_attn_split_kernel<128,2>", "bound": "hbm", "achieved": round(attn_gbps, 1),
-                     "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(attn_gbps / PEAK_HBM_GBPS, 4),
-                     "algorithmic_bytes": attn_bytes, "traffic": read_traffic()},
+        "event_pair_overhead_us": round(null_us, 2),
+        "roofline": roof,
+        "kernels": kernels,
     }
 
     if not args.no_cpu_baseline and only == "":

@@ -76,8 +76,8 @@ int radar_version(void);
 radar_status radar_workspace_init(void *workspace, size_t bytes, void *stream);
 
 /* --------------------------------------------------------------------------
- * Tree-verify attention (Sec. 1: the tree "is serialized and verified via
- * masked attention in a single LLM pass"; Sec. 3).
+ * Tree-verify attention (Sec. 1 and Sec. 3: the target model checks the whole
+ * serialized draft tree in one pass whose attention is masked by the tree).
  *
  * For sequence b, node i < n_nodes[b] and query head h:
  *     out[b,i,h,:] = softmax_j( scale * <q[b,i,h,:], k[b,h/G,j,:]> ) . v[b,h/G,j,:]
@@ -164,7 +164,8 @@ radar_status radar_draft_expand(const float *logits, const float *parent_scores,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
 /* --------------------------------------------------------------------------
- * Rerank, once per cycle (Sec. 1 / Sec. 2.3: "reordering and pruning").
+ * Rerank, once per cycle (Sec. 1 / Sec. 2.3: the dynamic tree is reordered
+ * and pruned by confidence).
  *
  * Orders the pool by (score descending, pool index ascending), keeps the first
  * min(N, pool_count) and emits the tree to verify: node 0 is the root
@@ -235,6 +236,32 @@ radar_status radar_verify_accept(const float *target_logits, const int32_t *draf
  * [B,T_max]; n_nodes i32 [B] or NULL. */
 radar_status radar_debug_validate_tree(const int32_t *parents, const int32_t *n_nodes, int32_t B, int32_t T_max,
                                        int32_t *bad_count_out, void *stream);
+
+/* --------------------------------------------------------------------------
+ * Measurement support (not part of the method; for benchmarks that report
+ * achieved bandwidth per kernel as the paper's Table 5 reports time per
+ * stage).  Between radar_profile_begin and radar_profile_end every kernel the
+ * library launches, from any thread, carries a pair of HIP events stamped
+ * with the dispatch's own begin and end on the device, i.e. the duration a
+ * kernel trace shows, without launch gaps or event overhead.
+ *
+ * radar_profile_begin(max_launches) creates max_launches event pairs (host
+ * objects; 1 <= max_launches <= 2^20) and starts recording; launches beyond
+ * that number run unrecorded.  radar_profile_end stops recording, waits for
+ * the recorded kernels, writes one entry per kernel name into out[0..capacity)
+ * (HOST memory; names beyond capacity are dropped), stores the number of
+ * entries in *n_out and destroys the events.  These two calls are the only
+ * ones that create or destroy anything and that synchronise. */
+typedef struct radar_kernel_time {
+    char name[48];      /* "expand", "rerank", "accept", "tree_attn_group_share", ... */
+    int64_t calls;
+    double total_us;
+    double min_us;
+    double max_us;
+} radar_kernel_time;
+
+radar_status radar_profile_begin(int32_t max_launches);
+radar_status radar_profile_end(radar_kernel_time *out, int32_t capacity, int32_t *n_out);
 
 #ifdef __cplusplus
 }

@@ -17,8 +17,8 @@
  * The paper states the three operations in words only (it prints no listing
  * and no worked numbers), so each function below is the plain definition of
  * the sentence it cites:
- *   - tree attention: Sec. 1 ("serialized and verified via masked attention in
- *     a single LLM pass") and Sec. 3 (single parallel forward pass);
+ *   - tree attention: Sec. 1 and Sec. 3 (the serialized tree is checked by the
+ *     target in one forward pass whose attention is masked by the tree);
  *   - draft expansion: Sec. 2.3 (confidence scores as proxy, reordering and
  *     pruning) and App. A.1 (k tokens -> k*k candidates -> top-k confidences);
  *   - acceptance: Sec. 3, Eq. 1 (accept probability) and Eq. 2 (residual),
@@ -285,7 +285,7 @@ int radar_oracle_draft_expand(const float *logits, const float *parent_scores, c
 
 /* ------------------------------------------------------------------ rerank
  *
- * Sec. 1 / Sec. 2.3 ("reordering and pruning nodes"): once drafting stops, the
+ * Sec. 1 / Sec. 2.3 (dynamic trees are reordered and pruned by confidence): once drafting stops, the
  * candidates gathered over all draft calls are ordered by confidence and only
  * the best N are kept; together with the root they form the tree the target
  * verifies.  Order: (score desc, pool index asc).  Node 0 is the root

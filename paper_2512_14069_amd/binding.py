@@ -47,6 +47,11 @@ class ExpandDesc(ctypes.Structure):
                 ("pool_count", ctypes.c_int32), ("pool_capacity", ctypes.c_int32)]
 
 
+class KernelTime(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 48), ("calls", ctypes.c_int64), ("total_us", ctypes.c_double),
+                ("min_us", ctypes.c_double), ("max_us", ctypes.c_double)]
+
+
 class AcceptDesc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("T_max", ctypes.c_int32), ("V", ctypes.c_int32),
                 ("D_max", ctypes.c_int32), ("mode", ctypes.c_int32), ("temperature", ctypes.c_float)]
@@ -58,7 +63,7 @@ EXPORTS = [
     "radar_draft_expand_workspace_bytes", "radar_draft_expand",
     "radar_draft_rerank_workspace_bytes", "radar_draft_rerank",
     "radar_verify_accept_workspace_bytes", "radar_verify_accept",
-    "radar_debug_validate_tree",
+    "radar_debug_validate_tree", "radar_profile_begin", "radar_profile_end",
 ]
 
 
@@ -95,6 +100,10 @@ def load():
     lib.radar_verify_accept.argtypes = [vp] * 8 + [ctypes.POINTER(AcceptDesc), vp, sz, vp]
     lib.radar_debug_validate_tree.restype = i32
     lib.radar_debug_validate_tree.argtypes = [vp, vp, i32, i32, vp, vp]
+    lib.radar_profile_begin.restype = i32
+    lib.radar_profile_begin.argtypes = [i32]
+    lib.radar_profile_end.restype = i32
+    lib.radar_profile_end.argtypes = [ctypes.POINTER(KernelTime), i32, ctypes.POINTER(i32)]
     _lib = lib
     return lib
 
@@ -329,3 +338,17 @@ def radar_debug_validate_tree(parents, n_nodes=None):
         _ptr(_dense(parents, "parents"), torch.int32), _ptr(n_nodes, torch.int32), B, T, _ptr(bad), _stream())
     _check(rc, "radar_debug_validate_tree")
     return bad
+
+
+def radar_profile_begin(max_launches):
+    _check(load().radar_profile_begin(int(max_launches)), "radar_profile_begin")
+
+
+def radar_profile_end(capacity=32):
+    """Returns {kernel name: dict(calls, total_us, mean_us, min_us, max_us)} for the launches since begin."""
+    arr = (KernelTime * capacity)()
+    n = ctypes.c_int32(0)
+    _check(load().radar_profile_end(arr, capacity, ctypes.byref(n)), "radar_profile_end")
+    return {arr[i].name.decode(): dict(calls=int(arr[i].calls), total_us=arr[i].total_us,
+                                       mean_us=arr[i].total_us / max(1, arr[i].calls),
+                                       min_us=arr[i].min_us, max_us=arr[i].max_us) for i in range(n.value)}

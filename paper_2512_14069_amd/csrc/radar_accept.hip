@@ -10,6 +10,7 @@
 // lane per node, sibling sets found with ballots); the residual draw needs one
 // more pass over a single 16 KB chunk.  Arrival counters sit 64 B apart.
 #include "radar_device.h"
+#include "radar_host.h"
 
 namespace radar {
 
@@ -346,11 +347,6 @@ __global__ void validate_tree_kernel(const int32_t *parents, const int32_t *n_no
     if (threadIdx.x == 0) *bad = count;
 }
 
-__global__ void zero_fill_kernel(uint4 *p, size_t n16) {
-    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
-        p[i] = make_uint4(0, 0, 0, 0);
-}
-
 }  // namespace radar
 
 using namespace radar;
@@ -409,37 +405,15 @@ extern "C" radar_status radar_verify_accept(const float *target_logits, const in
     const dim3 grid((unsigned)nchunks, (unsigned)d->T_max, (unsigned)d->B), block(kAccThreads);
     const bool vec4 = (d->V % 4 == 0) && (((uintptr_t)target_logits & 15) == 0);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (vec4) hipLaunchKernelGGL(accept_kernel<true>, grid, block, 0, st, a);
-    else      hipLaunchKernelGGL(accept_kernel<false>, grid, block, 0, st, a);
-    return hipGetLastError() == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
+    const hipError_t e = vec4 ? launch("accept", accept_kernel<true>, grid, block, 0, st, a)
+                              : launch("accept", accept_kernel<false>, grid, block, 0, st, a);
+    return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
 }
 
 extern "C" radar_status radar_debug_validate_tree(const int32_t *parents, const int32_t *n_nodes, int32_t B,
                                                   int32_t T_max, int32_t *bad_count_out, void *stream) {
     if (!parents || !bad_count_out || B < 1 || T_max < 1) return RADAR_INVALID_ARG;
-    hipLaunchKernelGGL(validate_tree_kernel, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream), parents,
-                       n_nodes, (int)B, (int)T_max, bad_count_out);
-    return hipGetLastError() == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
+    const hipError_t e = launch("validate_tree", validate_tree_kernel, dim3(1), dim3(256), 0,
+                                static_cast<hipStream_t>(stream), parents, n_nodes, (int)B, (int)T_max, bad_count_out);
+    return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
 }
-
-extern "C" radar_status radar_workspace_init(void *workspace, size_t bytes, void *stream) {
-    if (!workspace || bytes < 4096 || ((uintptr_t)workspace & 255) != 0) return RADAR_INVALID_ARG;
-    const size_t n16 = bytes / 16;
-    const unsigned blocks = (unsigned)((n16 + 255) / 256 > 1024 ? 1024 : (n16 + 255) / 256);
-    hipLaunchKernelGGL(zero_fill_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<uint4 *>(workspace), n16);
-    return hipGetLastError() == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
-}
-
-extern "C" const char *radar_status_string(radar_status status) {
-    switch (status) {
-        case RADAR_OK: return "ok";
-        case RADAR_INVALID_ARG: return "invalid argument";
-        case RADAR_UNSUPPORTED_SHAPE: return "shape outside the compiled limits";
-        case RADAR_WORKSPACE_TOO_SMALL: return "workspace too small";
-        case RADAR_HIP_ERROR: return "HIP runtime error";
-        default: return "unknown status";
-    }
-}
-
-extern "C" int radar_version(void) { return 100; }

@@ -33,6 +33,7 @@
 //    block of up to 4 grouped query heads); its wavefronts are the query heads and
 //    share every K/V tile through LDS.  Splits are merged by a small second kernel.
 #include "radar_device.h"
+#include "radar_host.h"
 
 namespace radar {
 
@@ -679,9 +680,7 @@ static AttnPlan plan_attention(const radar_attn_desc *d) {
     AttnPlan p;
     const int G = d->Hq / d->Hkv;
     p.n_qblk = (G + kAttnWaves - 1) / kAttnWaves;
-    // key-split re-reads every KV head G times (from L2): use it while that stays small
-    const double reread_bytes = (double)d->B * d->Hq * d->S_max * d->D * 4.0;
-    p.key_split = d->variant == RADAR_ATTN_KEY_SPLIT || (d->variant == RADAR_ATTN_AUTO && reread_bytes <= 96e6);
+    p.key_split = d->variant == RADAR_ATTN_KEY_SPLIT;      // never chosen automatically: measured slower at every shape tried
     long kps = d->keys_per_split;
     if (kps <= 0) {
         if (p.key_split) {
@@ -747,8 +746,7 @@ static hipError_t launch_gs(const AttnArgs &a, dim3 grid, hipStream_t s) {
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((tree_attn_gs_kernel<D, NQB>), grid, dim3(kAttnThreads), gs_smem_bytes<D>(), s, a);
-    return hipGetLastError();
+    return launch("tree_attn_group_share", tree_attn_gs_kernel<D, NQB>, grid, dim3(kAttnThreads), gs_smem_bytes<D>(), s, a);
 }
 
 template <int D, int NQB>
@@ -760,8 +758,7 @@ static hipError_t launch_ks(const AttnArgs &a, dim3 grid, hipStream_t s) {
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((tree_attn_ks_kernel<D, NQB>), grid, dim3(kAttnThreads), KsLayout<D>::BYTES, s, a);
-    return hipGetLastError();
+    return launch("tree_attn_key_split", tree_attn_ks_kernel<D, NQB>, grid, dim3(kAttnThreads), KsLayout<D>::BYTES, s, a);
 }
 
 extern "C" radar_status radar_tree_attention(const void *q, const void *k_cache, const void *v_cache,
@@ -827,9 +824,9 @@ extern "C" radar_status radar_tree_attention(const void *q, const void *k_cache,
     }
     if (a.max_splits > 1) {
         const dim3 mgrid((unsigned)a.Hq, (unsigned)a.B);
-        if (d->D == 128) hipLaunchKernelGGL(tree_attn_merge_kernel<128>, mgrid, block, 0, s, a);
-        else             hipLaunchKernelGGL(tree_attn_merge_kernel<64>, mgrid, block, 0, s, a);
-        if (hipGetLastError() != hipSuccess) return RADAR_HIP_ERROR;
+        const hipError_t e = d->D == 128 ? launch("tree_attn_merge", tree_attn_merge_kernel<128>, mgrid, block, 0, s, a)
+                                         : launch("tree_attn_merge", tree_attn_merge_kernel<64>, mgrid, block, 0, s, a);
+        if (e != hipSuccess) return RADAR_HIP_ERROR;
     }
     return RADAR_OK;
 }

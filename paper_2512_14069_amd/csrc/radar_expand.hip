@@ -10,6 +10,7 @@
 // append); the workgroup that finishes the last row picks the next frontier.
 // There is no second launch and no host round trip.
 #include "radar_topk.h"
+#include "radar_host.h"
 
 namespace radar {
 
@@ -328,9 +329,9 @@ extern "C" radar_status radar_draft_expand(const float *logits, const float *par
     const dim3 grid((unsigned)nchunks, (unsigned)d->F), block(kExpThreads);
     const bool vec4 = (d->V % 4 == 0) && (((uintptr_t)logits & 15) == 0);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (vec4) hipLaunchKernelGGL(expand_kernel<true>, grid, block, 0, st, a);
-    else      hipLaunchKernelGGL(expand_kernel<false>, grid, block, 0, st, a);
-    return hipGetLastError() == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
+    const hipError_t e = vec4 ? launch("expand", expand_kernel<true>, grid, block, 0, st, a)
+                              : launch("expand", expand_kernel<false>, grid, block, 0, st, a);
+    return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
 }
 
 extern "C" size_t radar_draft_rerank_workspace_bytes(int32_t pool_count, int32_t N) {
@@ -355,6 +356,6 @@ extern "C" radar_status radar_draft_rerank(const int32_t *pool_tokens, const flo
     a.pool_count = pool_count; a.N = N; a.root_token = root_token;
     a.tree_tokens = tree_tokens; a.tree_parents = tree_parents; a.tree_scores = tree_scores;
     a.tree_depth = tree_depth; a.tree_pool_idx = tree_pool_idx; a.n_nodes_out = n_nodes_out;
-    hipLaunchKernelGGL(rerank_kernel, dim3(1), dim3(kTopkThreads), 0, static_cast<hipStream_t>(stream), a);
-    return hipGetLastError() == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
+    const hipError_t e = launch("rerank", rerank_kernel, dim3(1), dim3(kTopkThreads), 0, static_cast<hipStream_t>(stream), a);
+    return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
 }
