@@ -5,18 +5,21 @@
 // workgroup streams its chunk once from HBM with 16-byte loads (the whole
 // step is one read of F*V*4 bytes), keeps its 16 values per lane in registers,
 // and leaves (chunk top-k keys, chunk max, chunk sum of exp) in the workspace.
-// The workgroup whose arrival ticket is the last of its row merges that row
+// Arrival tickets (one counter per row, then one per call) single out the
+// workgroup that finishes last; it merges every row, one wavefront per row
 // (top-k of the chunk lists, log-sum-exp in fp64, cumulative scores, pool
-// append); the workgroup that finishes the last row picks the next frontier.
-// There is no second launch and no host round trip.
+// append), and picks the next frontier.  There is no second launch and no
+// host round trip.
+#include <stdlib.h>
+
 #include "radar_topk.h"
 #include "radar_host.h"
 
 namespace radar {
 
-constexpr int kExpThreads = 256;
-constexpr int kExpEPT = 16;
-constexpr int kExpChunk = kExpThreads * kExpEPT;      // 4096 logits per workgroup
+constexpr int kExpThreads = 512;
+constexpr int kExpWaves = kExpThreads / kWave;
+constexpr int kExpMinEPT = 8;                         // logits per lane: 8, 12 or 16 (chosen per call)
 constexpr int kExpMaxChunks = 256;                    // V <= 1,048,576
 constexpr int kCounterStride = 32;                    // arrival counters sit 128 B apart: fetch-adds on one
                                                       // cache line serialise at roughly 10 ns each
@@ -38,166 +41,272 @@ struct ExpandArgs {
     int32_t *pool_parents;
     int F, V, k, nchunks, pool_count;
     unsigned int *counters;     // [0] rows finished, [(1+f) * kCounterStride] chunks of row f finished
-    uint64_t *part_keys;        // [F][nchunks][RADAR_K_MAX]
+    uint64_t *part_keys;        // [F][nchunks][RADAR_K_MAX] best first, 0 where a chunk has fewer
     double *part_l;             // [F][nchunks] sum of exp(x - part_m) over the chunk
     float *part_m;              // [F][nchunks] chunk maximum
 };
 
 struct ExpandSmem {
-    TopkSmem topk;
-    float wave_m[4];
-    double wave_l[4];
-    int tok[RADAR_F_MAX * RADAR_K_MAX];
-    unsigned int ticket;
+    WaveTopkSmem wtk[kExpWaves];                  // one scratch per wavefront
+    uint64_t wtop[kExpWaves * 16];                // the wavefront lists of a chunk
+    float wave_m[kExpWaves];
+    double wave_l[kExpWaves];
+    // last workgroup only: candidate (row f, rank r) at f * 16 + r
+    uint64_t cand_key[RADAR_F_MAX * 16];
+    float cand_sc[RADAR_F_MAX * 16];
+    int cand_tok[RADAR_F_MAX * 16];
+    float row_m[RADAR_F_MAX];
+    double row_l[RADAR_F_MAX];
+    unsigned int ticket, ticket2;
 };
 
-// sum over the four wavefront entries of l_i * exp(m_i - m): lanes 0..3 of a wavefront take one
-// term each (fp64 exp), the terms are then added in a fixed order.  Every lane gets the result.
-__device__ __forceinline__ double combine4(const float *wm, const double *wl, float m) {
+// sum over the wavefront entries of l_i * exp(m_i - m): lanes 0..7 of a wavefront take one term
+// each (weights by the fp32 exponential, as the terms themselves were), added in a fixed order.
+// Every lane gets the result.
+__device__ __forceinline__ double combine_waves(const float *wm, const double *wl, float m) {
     const int lane = lane_id();
     double t = 0.0;
-    if (lane < 4 && wm[lane] > -INFINITY) t = wl[lane] * exp((double)wm[lane] - (double)m);
+    if (lane < kExpWaves && wm[lane] > -INFINITY) t = wl[lane] * (double)__builtin_amdgcn_exp2f((wm[lane] - m) * kLog2eF);
     const uint64_t b = (uint64_t)__double_as_longlong(t);
-    const double t0 = __longlong_as_double((long long)readlane_u64(b, 0));
-    const double t1 = __longlong_as_double((long long)readlane_u64(b, 1));
-    const double t2 = __longlong_as_double((long long)readlane_u64(b, 2));
-    const double t3 = __longlong_as_double((long long)readlane_u64(b, 3));
-    return (t0 + t1) + (t2 + t3);
+    double sum[kExpWaves];
+#pragma unroll
+    for (int i = 0; i < kExpWaves; ++i) sum[i] = __longlong_as_double((long long)readlane_u64(b, i));
+    return ((sum[0] + sum[1]) + (sum[2] + sum[3])) + ((sum[4] + sum[5]) + (sum[6] + sum[7]));
 }
 
-template <bool VEC4>
-__global__ __launch_bounds__(kExpThreads, 4) void expand_kernel(ExpandArgs a) {
+// 512 slots, starting at c0, of one row's chunk lists in the workspace (device-scope loads)
+__device__ __forceinline__ void load_key_block(const uint64_t *pk, int nslot, int c0, int K, uint64_t (&kk)[9]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int i = c0 + topk_slot_of(e);
+        const uint64_t key = load_shared_result(pk + min(i, nslot - 1));     // branch-free: clamp, load, mask
+        kk[e] = (i < nslot && (i & 15) < K) ? key : 0;
+    }
+    kk[8] = 0;
+}
+
+// top-K of one row's chunk lists by one wavefront; kk holds the first 512 slots already
+__device__ __forceinline__ uint64_t row_topk(uint64_t (&kk)[9], const uint64_t *pk, int nslot, int K, WaveTopkSmem &scratch) {
+    uint64_t top = wave_topk<9>(kk, K, scratch);
+    for (int c0 = 8 * kWave; c0 < nslot; c0 += 8 * kWave) {        // V > 131072 only
+        load_key_block(pk, nslot, c0, K, kk);
+        kk[8] = top;                                                 // the running selection rides along
+        top = wave_topk<9>(kk, K, scratch);
+    }
+    return top;
+}
+
+template <bool VEC4, int EPT>
+__global__ __launch_bounds__(kExpThreads, 2) void expand_kernel(ExpandArgs a) {
+    static_assert(EPT == 8 || EPT == 12 || EPT == 16, "EPT");
+    constexpr int kChunk = kExpThreads * EPT;
     __shared__ ExpandSmem s;
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int f = blockIdx.y, chunk = blockIdx.x;
     const float *row = a.logits + (size_t)f * a.V;
-    const int base = chunk * kExpChunk;
+    const int base = chunk * kChunk;
+    const int K = a.k;
 
-    // ---- stream the chunk: 4 x (256 lanes x 16 B), coalesced
-    float x[kExpEPT];
-    uint64_t keys[kExpEPT];
+    // ---- stream the chunk: EPT/4 x (512 lanes x 16 B), coalesced; all loads are issued before
+    // anything is computed from them (out-of-range lanes read a valid address and are masked)
+    float4 raw[EPT / 4];
 #pragma unroll
-    for (int g = 0; g < kExpEPT / 4; ++g) {
+    for (int g = 0; g < EPT / 4; ++g) {
         const int idx0 = base + g * (kExpThreads * 4) + tid * 4;
-        // branch-free: out-of-range lanes read a valid address and are masked afterwards
-        float4 v;
         if (VEC4) {
-            v = *reinterpret_cast<const float4 *>(row + (idx0 < a.V ? idx0 : 0));
+            raw[g] = *reinterpret_cast<const float4 *>(row + (idx0 < a.V ? idx0 : 0));
         } else {
-            v.x = row[min(idx0 + 0, a.V - 1)];
-            v.y = row[min(idx0 + 1, a.V - 1)];
-            v.z = row[min(idx0 + 2, a.V - 1)];
-            v.w = row[min(idx0 + 3, a.V - 1)];
+            raw[g].x = row[min(idx0 + 0, a.V - 1)];
+            raw[g].y = row[min(idx0 + 1, a.V - 1)];
+            raw[g].z = row[min(idx0 + 2, a.V - 1)];
+            raw[g].w = row[min(idx0 + 3, a.V - 1)];
         }
-        if (idx0 + 0 >= a.V) v.x = -INFINITY;
-        if (idx0 + 1 >= a.V) v.y = -INFINITY;
-        if (idx0 + 2 >= a.V) v.z = -INFINITY;
-        if (idx0 + 3 >= a.V) v.w = -INFINITY;
-        x[4 * g + 0] = v.x; x[4 * g + 1] = v.y; x[4 * g + 2] = v.z; x[4 * g + 3] = v.w;
+    }
+    float x[EPT];
+    uint64_t keys[EPT];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            keys[4 * g + j] = (idx0 + j < a.V) ? make_key(x[4 * g + j], uint32_t(idx0 + j)) : 0;
+    for (int g = 0; g < EPT / 4; ++g) {
+        const int idx0 = base + g * (kExpThreads * 4) + tid * 4;
+        const float v[4] = {raw[g].x, raw[g].y, raw[g].z, raw[g].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool valid = idx0 + j < a.V;
+            x[4 * g + j] = valid ? v[j] : -INFINITY;
+            keys[4 * g + j] = make_key(v[j], uint32_t(idx0 + j)) & (0ull - (uint64_t)valid);   // no branch
+        }
     }
 
-    // ---- chunk log-sum-exp partial per wavefront (exp2 of fp32 differences, sums in fp64)
+    // ---- log-sum-exp partial per wavefront (exp2 of fp32 differences, sums in fp64)
     float tm = x[0];
 #pragma unroll
-    for (int e = 1; e < kExpEPT; ++e) tm = fmaxf(tm, x[e]);
+    for (int e = 1; e < EPT; ++e) tm = fmaxf(tm, x[e]);
     const float wm = wave_max_f32(tm);
     double tl = 0.0;
     if (wm > -INFINITY) {
 #pragma unroll
-        for (int e = 0; e < kExpEPT; ++e) tl += (double)__builtin_amdgcn_exp2f((x[e] - wm) * kLog2eF);
+        for (int e = 0; e < EPT; ++e) tl += (double)__builtin_amdgcn_exp2f((x[e] - wm) * kLog2eF);
     }
     const double wl = wave_sum_f64(tl);
     if (lane == 0) { s.wave_m[w] = wm; s.wave_l[w] = wl; }
 
-    // ---- chunk top-k
-    block_topk<kExpEPT>(keys, a.k, s.topk);          // synchronises; wave_m / wave_l visible after it
+    // ---- top-k of each wavefront's logits, then of the eight lists
+    uint64_t wt;
+    {
+        uint64_t kk[9];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) kk[e] = keys[e];
+        kk[8] = 0;
+        wt = wave_topk<9>(kk, K, s.wtk[w]);
+        if (EPT > 8) {                                             // the rest, with the selection so far
+            uint64_t k2[EPT - 8 + 1];
+#pragma unroll
+            for (int e = 8; e < EPT; ++e) k2[e - 8] = keys[e];
+            k2[EPT - 8] = wt;
+            wt = wave_topk<EPT - 8 + 1>(k2, K, s.wtk[w]);
+        }
+    }
+    if (lane < 16) s.wtop[w * 16 + lane] = wt;
+    __syncthreads();
 
     const size_t pslot = (size_t)f * a.nchunks + chunk;
-    if (tid < a.k) store_shared_result(&a.part_keys[pslot * RADAR_K_MAX + tid], s.topk.top[tid]);
-    if (w == 1) {                                     // a wavefront that stores no keys
-        const float m = fmaxf(fmaxf(s.wave_m[0], s.wave_m[1]), fmaxf(s.wave_m[2], s.wave_m[3]));
-        const double l = combine4(s.wave_m, s.wave_l, m);
+    if (w == 0) {
+        uint64_t kk[9];
+#pragma unroll
+        for (int e = 0; e < 9; ++e) kk[e] = 0;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int i = topk_slot_of(e);
+            kk[e] = (i & 15) < K ? s.wtop[i] : 0;
+        }
+        const uint64_t top = wave_topk<9>(kk, K, s.wtk[0]);
+        if (lane < K) store_shared_result(a.part_keys + pslot * RADAR_K_MAX + lane, top);
+    } else if (w == 1) {
+        float m = s.wave_m[0];
+#pragma unroll
+        for (int i = 1; i < kExpWaves; ++i) m = fmaxf(m, s.wave_m[i]);
+        const double l = combine_waves(s.wave_m, s.wave_l, m);
         if (lane == 0) {
             store_shared_result(&a.part_m[pslot], m);
             store_shared_result(&a.part_l[pslot], l);
         }
     }
-    if (publish_then_ticket(&a.counters[(1 + f) * kCounterStride], &s.ticket) != (unsigned int)(a.nchunks - 1)) return;
+    unsigned int *row_counter = &a.counters[(1 + f) * kCounterStride];
+    if (publish_then_ticket(row_counter, &s.ticket) != (unsigned int)(a.nchunks - 1)) return;
 
-    // ================= last workgroup of row f: merge the row
-    // all loads of the hand-over data are issued together (one round trip)
-    const int nk = a.nchunks * a.k;
-    uint64_t mk[kExpEPT];
-#pragma unroll
-    for (int e = 0; e < kExpEPT; ++e) {
-        const int i = tid + e * kExpThreads;
-        const int ic = min(i, nk - 1);                            // branch-free: clamp, load, mask
-        const int c = ic / a.k, r = ic - c * a.k;
-        const uint64_t key = load_shared_result(&a.part_keys[((size_t)f * a.nchunks + c) * RADAR_K_MAX + r]);
-        mk[e] = (i < nk) ? key : 0;
+    // ---- last chunk of row f: the row is complete; count it.  Only the workgroup that completes
+    // the last row goes on (its predecessors' partials were all acknowledged before their tickets).
+    if (tid == 0) {
+        store_shared_result(row_counter, 0u);                      // leave the row counter clean
+        s.ticket2 = __hip_atomic_fetch_add(&a.counters[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    const int cc = min(tid, a.nchunks - 1);                       // nchunks <= 256: one chunk per lane
-    float cm = load_shared_result(&a.part_m[(size_t)f * a.nchunks + cc]);
-    const double cl = load_shared_result(&a.part_l[(size_t)f * a.nchunks + cc]);
-    if (tid >= a.nchunks) cm = -INFINITY;
-    const float pscore = a.parent_scores[f];
-    const int ppool = a.parent_pool_idx[f];
-    const float rm = wave_max_f32(cm);
-    if (lane == 0) s.wave_m[w] = rm;
-
-    block_topk<kExpEPT>(mk, a.k, s.topk);                         // synchronises
-
-    // row log-sum-exp in fp64 from the chunk partials (fixed association order)
-    const float M = fmaxf(fmaxf(s.wave_m[0], s.wave_m[1]), fmaxf(s.wave_m[2], s.wave_m[3]));
-    const double term = (cm > -INFINITY) ? cl * exp((double)cm - (double)M) : 0.0;
-    const double wsum = wave_sum_f64(term);
-    if (lane == 0) s.wave_l[w] = wsum;
     __syncthreads();
-    if (tid < a.k) {
-        const double L = (s.wave_l[0] + s.wave_l[1]) + (s.wave_l[2] + s.wave_l[3]);
-        const double lse = (double)M + log(L);
-        const uint64_t key = s.topk.top[tid];
+    if (s.ticket2 != (unsigned int)(a.F - 1)) return;
+    if (tid == 0) store_shared_result(&a.counters[0], 0u);
+
+    // ================= last workgroup of the call.  One wavefront per row (rows w, w+8, ...; two
+    // rows' loads in flight together): top-k of the chunk lists and (max, sum) of the row.
+    const int nslot = a.nchunks * RADAR_K_MAX;
+    for (int fr0 = w; fr0 < a.F; fr0 += 2 * kExpWaves) {
+        const int fr1 = fr0 + kExpWaves;
+        const bool two = fr1 < a.F;                                // wave-uniform
+        const uint64_t *pk0 = a.part_keys + (size_t)fr0 * nslot;
+        const uint64_t *pk1 = a.part_keys + (size_t)(two ? fr1 : fr0) * nslot;
+        uint64_t k0[9], k1[9];
+        load_key_block(pk0, nslot, 0, K, k0);
+        load_key_block(pk1, nslot, 0, K, k1);
+        float cm[2];
+        double cl[2];
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {                              // chunk partials, one chunk per lane first
+            const int fr = r == 0 ? fr0 : (two ? fr1 : fr0);
+            const int c = min(lane, a.nchunks - 1);
+            cm[r] = load_shared_result(&a.part_m[(size_t)fr * a.nchunks + c]);
+            cl[r] = load_shared_result(&a.part_l[(size_t)fr * a.nchunks + c]);
+            if (lane >= a.nchunks) { cm[r] = -INFINITY; cl[r] = 0.0; }
+        }
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            if (r == 1 && !two) break;
+            const int fr = r == 0 ? fr0 : fr1;
+            const uint64_t top = r == 0 ? row_topk(k0, pk0, nslot, K, s.wtk[w]) : row_topk(k1, pk1, nslot, K, s.wtk[w]);
+            if (lane < 16) s.cand_key[fr * 16 + lane] = top;
+            float ml = cm[r];
+            double ll = cl[r];
+            for (int c = lane + kWave; c < a.nchunks; c += kWave) {        // V > 262144 only
+                const float m2 = load_shared_result(&a.part_m[(size_t)fr * a.nchunks + c]);
+                const double l2 = load_shared_result(&a.part_l[(size_t)fr * a.nchunks + c]);
+                const float mn = fmaxf(ml, m2);
+                if (mn > -INFINITY)
+                    ll = ll * (double)__builtin_amdgcn_exp2f((ml - mn) * kLog2eF) + l2 * (double)__builtin_amdgcn_exp2f((m2 - mn) * kLog2eF);
+                ml = mn;
+            }
+            const float M = wave_max_f32(ml);
+            const double L = wave_sum_f64(ml > -INFINITY ? ll * (double)__builtin_amdgcn_exp2f((ml - M) * kLog2eF) : 0.0);
+            if (lane == 0) { s.row_m[fr] = M; s.row_l[fr] = L; }
+        }
+    }
+    __syncthreads();
+
+    // ---- cumulative scores of the F * k candidates (slot t: row t / 16, rank t % 16), pool append
+    for (int t = tid; t < a.F * 16; t += kExpThreads) {
+        const int fr = t >> 4, r = t & 15;
+        if (r >= K) continue;
+        const double lse = (double)s.row_m[fr] + log(s.row_l[fr]);
+        const uint64_t key = s.cand_key[t];
         const int tok = (int)key_index(key);
         const double logp = (double)key_value(key) - lse;
-        const float cum = (float)((double)pscore + logp);
-        const int c = f * a.k + tid;
-        store_shared_result(&a.cand_tokens[c], tok);
-        store_shared_result(&a.cand_scores[c], cum);
+        const float cum = (float)((double)a.parent_scores[fr] + logp);
+        const int c = fr * K + r;
+        a.cand_tokens[c] = tok;
+        a.cand_scores[c] = cum;
         a.pool_tokens[a.pool_count + c] = tok;
         a.pool_scores[a.pool_count + c] = cum;
-        a.pool_parents[a.pool_count + c] = ppool;
+        a.pool_parents[a.pool_count + c] = a.parent_pool_idx[fr];
+        s.cand_sc[t] = cum;
+        s.cand_tok[t] = tok;
     }
-    if (tid == 0) store_shared_result(&a.counters[(1 + f) * kCounterStride], 0u);   // leave the row counter clean
-    if (publish_then_ticket(&a.counters[0], &s.ticket) != (unsigned int)(a.F - 1)) return;
+    __syncthreads();
+    if (w != 0) return;
 
-    // ================= last workgroup of the call: choose the next frontier
-    const int C = a.F * a.k;                                      // <= 64 * 16 = 1024
-    uint64_t ck[4];
+    // ---- next frontier: top-k of the candidates by cumulative score (candidate index breaks ties)
+    const int nfs = a.F * 16;
+    uint64_t top;
+    if (nfs <= 3 * kWave) {
+        uint64_t kk[9];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const int c = tid + e * kExpThreads;
-        const int cs = min(c, C - 1);
-        const float sc = load_shared_result(&a.cand_scores[cs]);
-        s.tok[cs] = load_shared_result(&a.cand_tokens[cs]);
-        ck[e] = (c < C) ? make_key(sc, uint32_t(c)) : 0;
+        for (int e = 0; e < 9; ++e) kk[e] = 0;
+#pragma unroll
+        for (int e = 0; e < 3; ++e) {
+            const int i = topk_slot_of(e);
+            const float sc = s.cand_sc[min(i, nfs - 1)];
+            kk[e] = (i < nfs && (i & 15) < K) ? make_key(sc, uint32_t((i >> 4) * K + (i & 15))) : 0;
+        }
+        top = wave_topk<9>(kk, K, s.wtk[0]);
+    } else {
+        top = 0;
+        for (int c0 = 0; c0 < nfs; c0 += 8 * kWave) {
+            uint64_t kk[9];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int i = c0 + topk_slot_of(e);
+                const float sc = s.cand_sc[min(i, nfs - 1)];
+                kk[e] = (i < nfs && (i & 15) < K) ? make_key(sc, uint32_t((i >> 4) * K + (i & 15))) : 0;
+            }
+            kk[8] = top;
+            top = wave_topk<9>(kk, K, s.wtk[0]);
+        }
     }
-    block_topk<4>(ck, a.k, s.topk);                               // synchronises: s.tok visible
-    if (tid < a.k) {
-        const uint64_t key = s.topk.top[tid];
-        int c = (int)key_index(key);
+    if (lane < K) {
+        const int C = a.F * K;
+        int c = (int)key_index(top);
         if (c < 0 || c >= C) c = 0;                               // only reachable with NaN scores
-        // candidate scores never are -0.0 results of the sum above unless both terms are zero;
-        // the key holds the score exactly otherwise
-        const float sc = key_value(key);
-        a.frontier_pool_idx[tid] = a.pool_count + c;
-        a.frontier_tokens[tid] = s.tok[c];
-        a.frontier_scores[tid] = sc;
-        a.frontier_conf[tid] = (float)exp((double)sc);
+        const int fr = c / K, r = c - fr * K;
+        const float sc = s.cand_sc[fr * 16 + r];
+        a.frontier_pool_idx[lane] = a.pool_count + c;
+        a.frontier_tokens[lane] = s.cand_tok[fr * 16 + r];
+        a.frontier_scores[lane] = sc;
+        a.frontier_conf[lane] = (float)exp((double)sc);
     }
-    if (tid == 0) store_shared_result(&a.counters[0], 0u);
 }
 
 // ------------------------------------------------------------------ rerank
@@ -285,9 +394,20 @@ __global__ __launch_bounds__(kTopkThreads) void rerank_kernel(RerankArgs a) {
 
 using namespace radar;
 
+// Logits per lane: the fewest (shortest critical path per workgroup) that keep the launch at one
+// workgroup per CU; launches too large for that take the most, i.e. the fewest workgroups.
+static int plan_expand_ept(int F, int V) {
+    if (const char *o = getenv("RADAR_EXPAND_EPT")) { const int v = atoi(o); if (v == 8 || v == 12 || v == 16) return v; }
+    for (int ept = kExpMinEPT; ept <= 16; ept += 4) {
+        const int64_t chunk = (int64_t)kExpThreads * ept;
+        if ((int64_t)F * (((int64_t)V + chunk - 1) / chunk) <= 256) return ept;
+    }
+    return 16;
+}
+
 extern "C" size_t radar_draft_expand_workspace_bytes(const radar_expand_desc *d) {
     if (!d || d->F < 1 || d->V < 1) return 0;
-    const size_t nchunks = ((size_t)d->V + kExpChunk - 1) / kExpChunk;
+    const size_t nchunks = ((size_t)d->V + kExpThreads * kExpMinEPT - 1) / (kExpThreads * kExpMinEPT);   // most chunks any plan uses
     size_t bytes = kCounterBytes;
     bytes += (size_t)d->F * nchunks * RADAR_K_MAX * sizeof(uint64_t);
     bytes += (size_t)d->F * nchunks * (sizeof(double) + sizeof(float));
@@ -307,7 +427,9 @@ extern "C" radar_status radar_draft_expand(const float *logits, const float *par
     if (d->F < 1 || d->V < 1 || d->k < 1 || d->k > d->V || d->pool_count < 0 ||
         (int64_t)d->pool_count + (int64_t)d->F * d->k > (int64_t)d->pool_capacity)
         return RADAR_INVALID_ARG;
-    const int64_t nchunks = ((int64_t)d->V + kExpChunk - 1) / kExpChunk;
+    const int ept = plan_expand_ept(d->F, d->V);
+    const int64_t chunk = (int64_t)kExpThreads * ept;
+    const int64_t nchunks = ((int64_t)d->V + chunk - 1) / chunk;
     if (d->F > RADAR_F_MAX || d->k > RADAR_K_MAX || nchunks > kExpMaxChunks) return RADAR_UNSUPPORTED_SHAPE;
     if (workspace_bytes < radar_draft_expand_workspace_bytes(d)) return RADAR_WORKSPACE_TOO_SMALL;
     if (((uintptr_t)workspace & 255) != 0) return RADAR_INVALID_ARG;
@@ -329,8 +451,13 @@ extern "C" radar_status radar_draft_expand(const float *logits, const float *par
     const dim3 grid((unsigned)nchunks, (unsigned)d->F), block(kExpThreads);
     const bool vec4 = (d->V % 4 == 0) && (((uintptr_t)logits & 15) == 0);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const hipError_t e = vec4 ? launch("expand", expand_kernel<true>, grid, block, 0, st, a)
-                              : launch("expand", expand_kernel<false>, grid, block, 0, st, a);
+    hipError_t e;
+    if (ept == 8)       e = vec4 ? launch("expand", expand_kernel<true, 8>, grid, block, 0, st, a)
+                                 : launch("expand", expand_kernel<false, 8>, grid, block, 0, st, a);
+    else if (ept == 12) e = vec4 ? launch("expand", expand_kernel<true, 12>, grid, block, 0, st, a)
+                                 : launch("expand", expand_kernel<false, 12>, grid, block, 0, st, a);
+    else                e = vec4 ? launch("expand", expand_kernel<true, 16>, grid, block, 0, st, a)
+                                 : launch("expand", expand_kernel<false, 16>, grid, block, 0, st, a);
     return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
 }
 

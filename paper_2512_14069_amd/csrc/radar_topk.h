@@ -107,4 +107,85 @@ __device__ __forceinline__ void block_topk(const uint64_t (&keys)[EPT], int K, T
     __syncthreads();
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same selection inside ONE wavefront, without workgroup barriers: K <= 16 largest of the
+// 64 * EPL keys its lanes hold.  The 16 quads of the wavefront are the groups (tau = K-th
+// largest quad maximum, so at least K keys pass; callers spread their keys over the quads, or
+// few quads hold anything and tau filters little), survivors are compacted into the
+// wavefront's private LDS scratch and ranked exactly.  Returns the r-th largest key in lane r
+// (r < 16; 0 where fewer exist, and in lanes >= 16).  Callers on different wavefronts pass
+// different scratch; all 64 lanes must call.
+constexpr int kWaveTopkMaxEPL = 9;
+
+// Threshold for a selection of the K <= 16 largest values held by the lanes of one wavefront
+// (v = largest value of the lane, 0 if it holds none): the K-th largest of the 16 quad maxima.
+// At least K values are >= the result (one per quad that reaches it), and unlike the smallest
+// quad maximum it does not collapse when a few quads happen to hold only small values.
+// Never 0, so that absent entries (0) fail the test "value >= threshold".
+__device__ __forceinline__ uint32_t quad_threshold(uint32_t v, int K) {
+    uint32_t g = v;
+    g = max(g, dpp_u32<0xB1>(g));
+    g = max(g, dpp_u32<0x4E>(g));                 // quad maximum in every lane of the quad
+    int larger = 0;                               // quads whose maximum is strictly larger than this lane's
+#pragma unroll
+    for (int q = 0; q < 16; ++q) larger += (readlane_u32(g, 4 * q) > g) ? 1 : 0;
+    uint32_t c = larger < K ? g : 0xffffffffu;    // the K largest quad maxima (and their ties) stay
+    c = min(c, dpp_u32<0x141>(c));
+    c = min(c, dpp_u32<0x140>(c));                // smallest of them within the 16-lane row
+    const uint32_t t = min(min(readlane_u32(c, 0), readlane_u32(c, 16)), min(readlane_u32(c, 32), readlane_u32(c, 48)));
+    return max(t, 1u);
+}
+
+
+struct WaveTopkSmem {
+    uint64_t surv[kWave * kWaveTopkMaxEPL + 8];   // +8: the ranking reads keys eight at a time
+    uint64_t top[16];
+};
+
+template <int EPL>
+__device__ __forceinline__ uint64_t wave_topk(const uint64_t (&keys)[EPL], int K, WaveTopkSmem &s) {
+    static_assert(EPL <= kWaveTopkMaxEPL, "scratch too small");
+    const int lane = lane_id();
+    uint32_t tmax = 0;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) tmax = max(tmax, uint32_t(keys[e] >> 32));
+    const uint32_t tau = quad_threshold(tmax, K);
+
+    int n = 0;                                    // survivors so far (wave-uniform)
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        const bool keep = uint32_t(keys[e] >> 32) >= tau;
+        const uint64_t m = __ballot(keep);
+        if (keep) s.surv[n + lanes_below(m)] = keys[e];
+        n += __popcll(m);
+    }
+    if (lane < 8) s.surv[n + lane] = 0;           // padding for the grouped reads
+    if (lane < 16) s.top[lane] = 0;
+    wave_lds_sync();
+    for (int i0 = 0; i0 < n; i0 += kWave) {       // one pass unless nearly everything survived
+        const int i = i0 + lane;
+        const uint64_t key = s.surv[min(i, n - 1)];
+        int rank = 0;
+        for (int j = 0; j < n; j += 8) {          // broadcast reads (every lane reads the same keys),
+            uint64_t kj[8];                       // eight in flight so that their latencies overlap
+#pragma unroll
+            for (int u = 0; u < 8; ++u) kj[u] = s.surv[j + u];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) rank += (kj[u] > key) ? 1 : 0;
+        }
+        if (i < n && rank < K) s.top[rank] = key;
+    }
+    wave_lds_sync();
+    const uint64_t r = s.top[lane & 15];
+    wave_lds_sync();                              // scratch may be reused right after the return
+    return lane < 16 ? r : 0;
+}
+
+// Lists of 16 slots of which the first K are used (slot i: list i / 16, rank i % 16), taken 64
+// slots per step: which slot a lane takes at step e.  Lanes rotate by 4 per step, so a lane
+// meets slots of different ranks and every quad of lanes holds used slots.
+__device__ __forceinline__ int topk_slot_of(int e) {
+    return e * kWave + ((lane_id() + 4 * e) & (kWave - 1));
+}
+
 }  // namespace radar
