@@ -10,16 +10,14 @@
 // (top-k of the chunk lists, log-sum-exp in fp64, cumulative scores, pool
 // append), and picks the next frontier.  There is no second launch and no
 // host round trip.
-#include <stdlib.h>
-
 #include "radar_topk.h"
 #include "radar_host.h"
 
 namespace radar {
 
-constexpr int kExpThreads = 512;
+constexpr int kExpThreads = 1024;
 constexpr int kExpWaves = kExpThreads / kWave;
-constexpr int kExpMinEPT = 8;                         // logits per lane: 8, 12 or 16 (chosen per call)
+constexpr int kExpMinEPT = 4;                         // logits per lane: 4, 8 or 16 (chosen per call)
 constexpr int kExpMaxChunks = 256;                    // V <= 1,048,576
 constexpr int kCounterStride = 32;                    // arrival counters sit 128 B apart: fetch-adds on one
                                                       // cache line serialise at roughly 10 ns each
@@ -52,26 +50,25 @@ struct ExpandSmem {
     float wave_m[kExpWaves];
     double wave_l[kExpWaves];
     // last workgroup only: candidate (row f, rank r) at f * 16 + r
-    uint64_t cand_key[RADAR_F_MAX * 16];
     float cand_sc[RADAR_F_MAX * 16];
     int cand_tok[RADAR_F_MAX * 16];
-    float row_m[RADAR_F_MAX];
-    double row_l[RADAR_F_MAX];
     unsigned int ticket, ticket2;
 };
 
-// sum over the wavefront entries of l_i * exp(m_i - m): lanes 0..7 of a wavefront take one term
+// sum over the wavefront entries of l_i * exp(m_i - m): lanes 0..15 of a wavefront take one term
 // each (weights by the fp32 exponential, as the terms themselves were), added in a fixed order.
 // Every lane gets the result.
 __device__ __forceinline__ double combine_waves(const float *wm, const double *wl, float m) {
     const int lane = lane_id();
     double t = 0.0;
     if (lane < kExpWaves && wm[lane] > -INFINITY) t = wl[lane] * (double)__builtin_amdgcn_exp2f((wm[lane] - m) * kLog2eF);
-    const uint64_t b = (uint64_t)__double_as_longlong(t);
-    double sum[kExpWaves];
-#pragma unroll
-    for (int i = 0; i < kExpWaves; ++i) sum[i] = __longlong_as_double((long long)readlane_u64(b, i));
-    return ((sum[0] + sum[1]) + (sum[2] + sum[3])) + ((sum[4] + sum[5]) + (sum[6] + sum[7]));
+    // a 16-lane row sum by DPP, fixed association order
+    auto step = [](double x, uint64_t moved) { return x + __longlong_as_double((long long)moved); };
+    t = step(t, dpp_u64<0xB1>((uint64_t)__double_as_longlong(t)));
+    t = step(t, dpp_u64<0x4E>((uint64_t)__double_as_longlong(t)));
+    t = step(t, dpp_u64<0x141>((uint64_t)__double_as_longlong(t)));
+    t = step(t, dpp_u64<0x140>((uint64_t)__double_as_longlong(t)));
+    return __longlong_as_double((long long)readlane_u64((uint64_t)__double_as_longlong(t), 0));
 }
 
 // 512 slots, starting at c0, of one row's chunk lists in the workspace (device-scope loads)
@@ -97,8 +94,8 @@ __device__ __forceinline__ uint64_t row_topk(uint64_t (&kk)[9], const uint64_t *
 }
 
 template <bool VEC4, int EPT>
-__global__ __launch_bounds__(kExpThreads, 2) void expand_kernel(ExpandArgs a) {
-    static_assert(EPT == 8 || EPT == 12 || EPT == 16, "EPT");
+__global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
+    static_assert(EPT == 4 || EPT == 8 || EPT == 16, "EPT");
     constexpr int kChunk = kExpThreads * EPT;
     __shared__ ExpandSmem s;
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
@@ -107,7 +104,7 @@ __global__ __launch_bounds__(kExpThreads, 2) void expand_kernel(ExpandArgs a) {
     const int base = chunk * kChunk;
     const int K = a.k;
 
-    // ---- stream the chunk: EPT/4 x (512 lanes x 16 B), coalesced; all loads are issued before
+    // ---- stream the chunk: EPT/4 x (1024 lanes x 16 B), coalesced; all loads are issued before
     // anything is computed from them (out-of-range lanes read a valid address and are masked)
     float4 raw[EPT / 4];
 #pragma unroll
@@ -152,17 +149,17 @@ __global__ __launch_bounds__(kExpThreads, 2) void expand_kernel(ExpandArgs a) {
     // ---- top-k of each wavefront's logits, then of the eight lists
     uint64_t wt;
     {
-        uint64_t kk[9];
+        constexpr int E1 = EPT < 8 ? EPT : 8;
+        uint64_t kk[E1];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) kk[e] = keys[e];
-        kk[8] = 0;
-        wt = wave_topk<9>(kk, K, s.wtk[w]);
+        for (int e = 0; e < E1; ++e) kk[e] = keys[e];
+        wt = wave_topk<E1>(kk, K, s.wtk[w]);
         if (EPT > 8) {                                             // the rest, with the selection so far
-            uint64_t k2[EPT - 8 + 1];
+            uint64_t k2[EPT - E1 + 1];
 #pragma unroll
-            for (int e = 8; e < EPT; ++e) k2[e - 8] = keys[e];
-            k2[EPT - 8] = wt;
-            wt = wave_topk<EPT - 8 + 1>(k2, K, s.wtk[w]);
+            for (int e = E1; e < EPT; ++e) k2[e - E1] = keys[e];
+            k2[EPT - E1] = wt;
+            wt = wave_topk<EPT - E1 + 1>(k2, K, s.wtk[w]);
         }
     }
     if (lane < 16) s.wtop[w * 16 + lane] = wt;
@@ -170,15 +167,13 @@ __global__ __launch_bounds__(kExpThreads, 2) void expand_kernel(ExpandArgs a) {
 
     const size_t pslot = (size_t)f * a.nchunks + chunk;
     if (w == 0) {
-        uint64_t kk[9];
+        uint64_t kk[kExpWaves / 4];                               // 16 lists of 16 slots
 #pragma unroll
-        for (int e = 0; e < 9; ++e) kk[e] = 0;
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
+        for (int e = 0; e < kExpWaves / 4; ++e) {
             const int i = topk_slot_of(e);
             kk[e] = (i & 15) < K ? s.wtop[i] : 0;
         }
-        const uint64_t top = wave_topk<9>(kk, K, s.wtk[0]);
+        const uint64_t top = wave_topk<kExpWaves / 4>(kk, K, s.wtk[0]);
         if (lane < K) store_shared_result(a.part_keys + pslot * RADAR_K_MAX + lane, top);
     } else if (w == 1) {
         float m = s.wave_m[0];
@@ -203,67 +198,48 @@ __global__ __launch_bounds__(kExpThreads, 2) void expand_kernel(ExpandArgs a) {
     if (s.ticket2 != (unsigned int)(a.F - 1)) return;
     if (tid == 0) store_shared_result(&a.counters[0], 0u);
 
-    // ================= last workgroup of the call.  One wavefront per row (rows w, w+8, ...; two
-    // rows' loads in flight together): top-k of the chunk lists and (max, sum) of the row.
+    // ================= last workgroup of the call.  One wavefront per row (rows w, w+16, ...):
+    // top-k of the row's chunk lists, log-sum-exp of the row, cumulative scores, pool append.
     const int nslot = a.nchunks * RADAR_K_MAX;
-    for (int fr0 = w; fr0 < a.F; fr0 += 2 * kExpWaves) {
-        const int fr1 = fr0 + kExpWaves;
-        const bool two = fr1 < a.F;                                // wave-uniform
-        const uint64_t *pk0 = a.part_keys + (size_t)fr0 * nslot;
-        const uint64_t *pk1 = a.part_keys + (size_t)(two ? fr1 : fr0) * nslot;
-        uint64_t k0[9], k1[9];
-        load_key_block(pk0, nslot, 0, K, k0);
-        load_key_block(pk1, nslot, 0, K, k1);
-        float cm[2];
-        double cl[2];
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {                              // chunk partials, one chunk per lane first
-            const int fr = r == 0 ? fr0 : (two ? fr1 : fr0);
+    for (int fr = w; fr < a.F; fr += kExpWaves) {
+        const uint64_t *pk = a.part_keys + (size_t)fr * nslot;
+        uint64_t kk[9];
+        load_key_block(pk, nslot, 0, K, kk);
+        float ml;
+        double ll;
+        {                                                          // chunk partials, one chunk per lane first
             const int c = min(lane, a.nchunks - 1);
-            cm[r] = load_shared_result(&a.part_m[(size_t)fr * a.nchunks + c]);
-            cl[r] = load_shared_result(&a.part_l[(size_t)fr * a.nchunks + c]);
-            if (lane >= a.nchunks) { cm[r] = -INFINITY; cl[r] = 0.0; }
+            ml = load_shared_result(&a.part_m[(size_t)fr * a.nchunks + c]);
+            ll = load_shared_result(&a.part_l[(size_t)fr * a.nchunks + c]);
+            if (lane >= a.nchunks) { ml = -INFINITY; ll = 0.0; }
         }
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            if (r == 1 && !two) break;
-            const int fr = r == 0 ? fr0 : fr1;
-            const uint64_t top = r == 0 ? row_topk(k0, pk0, nslot, K, s.wtk[w]) : row_topk(k1, pk1, nslot, K, s.wtk[w]);
-            if (lane < 16) s.cand_key[fr * 16 + lane] = top;
-            float ml = cm[r];
-            double ll = cl[r];
-            for (int c = lane + kWave; c < a.nchunks; c += kWave) {        // V > 262144 only
-                const float m2 = load_shared_result(&a.part_m[(size_t)fr * a.nchunks + c]);
-                const double l2 = load_shared_result(&a.part_l[(size_t)fr * a.nchunks + c]);
-                const float mn = fmaxf(ml, m2);
-                if (mn > -INFINITY)
-                    ll = ll * (double)__builtin_amdgcn_exp2f((ml - mn) * kLog2eF) + l2 * (double)__builtin_amdgcn_exp2f((m2 - mn) * kLog2eF);
-                ml = mn;
-            }
-            const float M = wave_max_f32(ml);
-            const double L = wave_sum_f64(ml > -INFINITY ? ll * (double)__builtin_amdgcn_exp2f((ml - M) * kLog2eF) : 0.0);
-            if (lane == 0) { s.row_m[fr] = M; s.row_l[fr] = L; }
+        const float pscore = a.parent_scores[fr];
+        const int ppool = a.parent_pool_idx[fr];
+        const uint64_t top = row_topk(kk, pk, nslot, K, s.wtk[w]);
+        for (int c = lane + kWave; c < a.nchunks; c += kWave) {        // V > 262144 only
+            const float m2 = load_shared_result(&a.part_m[(size_t)fr * a.nchunks + c]);
+            const double l2 = load_shared_result(&a.part_l[(size_t)fr * a.nchunks + c]);
+            const float mn = fmaxf(ml, m2);
+            if (mn > -INFINITY)
+                ll = ll * (double)__builtin_amdgcn_exp2f((ml - mn) * kLog2eF) + l2 * (double)__builtin_amdgcn_exp2f((m2 - mn) * kLog2eF);
+            ml = mn;
         }
-    }
-    __syncthreads();
-
-    // ---- cumulative scores of the F * k candidates (slot t: row t / 16, rank t % 16), pool append
-    for (int t = tid; t < a.F * 16; t += kExpThreads) {
-        const int fr = t >> 4, r = t & 15;
-        if (r >= K) continue;
-        const double lse = (double)s.row_m[fr] + log(s.row_l[fr]);
-        const uint64_t key = s.cand_key[t];
-        const int tok = (int)key_index(key);
-        const double logp = (double)key_value(key) - lse;
-        const float cum = (float)((double)a.parent_scores[fr] + logp);
-        const int c = fr * K + r;
-        a.cand_tokens[c] = tok;
-        a.cand_scores[c] = cum;
-        a.pool_tokens[a.pool_count + c] = tok;
-        a.pool_scores[a.pool_count + c] = cum;
-        a.pool_parents[a.pool_count + c] = a.parent_pool_idx[fr];
-        s.cand_sc[t] = cum;
-        s.cand_tok[t] = tok;
+        const float M = wave_max_f32(ml);
+        const double L = wave_sum_f64(ml > -INFINITY ? ll * (double)__builtin_amdgcn_exp2f((ml - M) * kLog2eF) : 0.0);
+        const double lse = (double)M + log(L);
+        if (lane < K) {
+            const int tok = (int)key_index(top);
+            const double logp = (double)key_value(top) - lse;
+            const float cum = (float)((double)pscore + logp);
+            const int c = fr * K + lane;
+            a.cand_tokens[c] = tok;
+            a.cand_scores[c] = cum;
+            a.pool_tokens[a.pool_count + c] = tok;
+            a.pool_scores[a.pool_count + c] = cum;
+            a.pool_parents[a.pool_count + c] = ppool;
+            s.cand_sc[fr * 16 + lane] = cum;
+            s.cand_tok[fr * 16 + lane] = tok;
+        }
     }
     __syncthreads();
     if (w != 0) return;
@@ -397,8 +373,7 @@ using namespace radar;
 // Logits per lane: the fewest (shortest critical path per workgroup) that keep the launch at one
 // workgroup per CU; launches too large for that take the most, i.e. the fewest workgroups.
 static int plan_expand_ept(int F, int V) {
-    if (const char *o = getenv("RADAR_EXPAND_EPT")) { const int v = atoi(o); if (v == 8 || v == 12 || v == 16) return v; }
-    for (int ept = kExpMinEPT; ept <= 16; ept += 4) {
+    for (int ept = kExpMinEPT; ept <= 16; ept *= 2) {
         const int64_t chunk = (int64_t)kExpThreads * ept;
         if ((int64_t)F * (((int64_t)V + chunk - 1) / chunk) <= 256) return ept;
     }
@@ -452,12 +427,12 @@ extern "C" radar_status radar_draft_expand(const float *logits, const float *par
     const bool vec4 = (d->V % 4 == 0) && (((uintptr_t)logits & 15) == 0);
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
-    if (ept == 8)       e = vec4 ? launch("expand", expand_kernel<true, 8>, grid, block, 0, st, a)
-                                 : launch("expand", expand_kernel<false, 8>, grid, block, 0, st, a);
-    else if (ept == 12) e = vec4 ? launch("expand", expand_kernel<true, 12>, grid, block, 0, st, a)
-                                 : launch("expand", expand_kernel<false, 12>, grid, block, 0, st, a);
-    else                e = vec4 ? launch("expand", expand_kernel<true, 16>, grid, block, 0, st, a)
-                                 : launch("expand", expand_kernel<false, 16>, grid, block, 0, st, a);
+    if (ept == 4)      e = vec4 ? launch("expand", expand_kernel<true, 4>, grid, block, 0, st, a)
+                                : launch("expand", expand_kernel<false, 4>, grid, block, 0, st, a);
+    else if (ept == 8) e = vec4 ? launch("expand", expand_kernel<true, 8>, grid, block, 0, st, a)
+                                : launch("expand", expand_kernel<false, 8>, grid, block, 0, st, a);
+    else               e = vec4 ? launch("expand", expand_kernel<true, 16>, grid, block, 0, st, a)
+                                : launch("expand", expand_kernel<false, 16>, grid, block, 0, st, a);
     return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
 }
 
