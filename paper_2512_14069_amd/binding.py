@@ -141,6 +141,28 @@ def _check(rc, what):
         raise RadarError(rc, what)
 
 
+class BoundCall:
+    """A library call with its arguments already marshalled: calling it again costs one foreign
+    call.  It replays exactly the pointers, sizes and stream it was made with (`keep` holds the
+    tensors alive); host-side counters such as DraftPool.count are not advanced by a replay.
+    `out` is what the plain wrapper would have returned."""
+    __slots__ = ("name", "fn", "args", "keep", "out")
+
+    def __init__(self, name, fn, args, keep, out):
+        self.name, self.fn, self.args, self.keep, self.out = name, fn, args, keep, out
+
+    def __call__(self):
+        rc = self.fn(*self.args)
+        if rc != RADAR_OK:
+            raise RadarError(rc, self.name)
+        return self.out
+
+
+def _finish(name, fn, args, keep, out, prepared):
+    call = BoundCall(name, fn, args, keep, out)
+    return call if prepared else call()
+
+
 def _ws_args(ws):
     if ws is None:
         return None, 0
@@ -181,7 +203,7 @@ def radar_tree_attention_workspace_bytes(desc):
 
 
 def radar_tree_attention(q, k_cache, v_cache, parents, ctx_lens, n_nodes=None, out=None, lse_out=None,
-                         desc=None, workspace=None, keys_per_split=0, softmax_scale=0.0, variant=0):
+                         desc=None, workspace=None, keys_per_split=0, softmax_scale=0.0, variant=0, prepared=False):
     """q bf16 [B,T,Hq,D]; k_cache, v_cache bf16 [B,Hkv,S,D] (same strides, D contiguous);
     parents i32 [B,T]; ctx_lens i32 [B]; n_nodes i32 [B] or None.  Returns out bf16 [B,T,Hq,D]."""
     if q.stride(-1) != 1 or k_cache.stride(-1) != 1 or v_cache.stride() != k_cache.stride():
@@ -194,15 +216,15 @@ def radar_tree_attention(q, k_cache, v_cache, parents, ctx_lens, n_nodes=None, o
     if workspace is None:
         workspace = new_workspace(radar_tree_attention_workspace_bytes(desc), q.device)
     wp, wn = _ws_args(workspace)
-    rc = load().radar_tree_attention(
+    args = (
         _ptr(q, torch.bfloat16, "q"), _ptr(k_cache, torch.bfloat16, "k_cache"),
         _ptr(v_cache, torch.bfloat16, "v_cache"), _ptr(_dense(parents, "parents"), torch.int32, "parents"),
         _ptr(_dense(ctx_lens, "ctx_lens"), torch.int32, "ctx_lens"),
         _ptr(None if n_nodes is None else _dense(n_nodes, "n_nodes"), torch.int32, "n_nodes"),
         _ptr(out, torch.bfloat16, "out"), _ptr(lse_out, torch.float32, "lse_out"),
         ctypes.byref(desc), wp, wn, _stream())
-    _check(rc, "radar_tree_attention")
-    return out
+    keep = (q, k_cache, v_cache, parents, ctx_lens, n_nodes, out, lse_out, desc, workspace)
+    return _finish("radar_tree_attention", load().radar_tree_attention, args, keep, out, prepared)
 
 
 # ------------------------------------------------------------ draft expansion
@@ -238,7 +260,7 @@ def radar_draft_expand_workspace_bytes(desc):
     return int(load().radar_draft_expand_workspace_bytes(ctypes.byref(desc)))
 
 
-def radar_draft_expand(logits, parent_scores, parent_pool_idx, k, pool, out=None, workspace=None):
+def radar_draft_expand(logits, parent_scores, parent_pool_idx, k, pool, out=None, workspace=None, prepared=False):
     """logits f32 [F,V]; parent_scores f32 [F]; parent_pool_idx i32 [F]; pool: DraftPool
     (appended to; pool.count advances by F*k).  Returns an ExpandOut."""
     F, V = logits.shape
@@ -248,7 +270,7 @@ def radar_draft_expand(logits, parent_scores, parent_pool_idx, k, pool, out=None
     if workspace is None:
         workspace = new_workspace(radar_draft_expand_workspace_bytes(desc), logits.device)
     wp, wn = _ws_args(workspace)
-    rc = load().radar_draft_expand(
+    args = (
         _ptr(_dense(logits, "logits"), torch.float32, "logits"),
         _ptr(_dense(parent_scores, "parent_scores"), torch.float32, "parent_scores"),
         _ptr(_dense(parent_pool_idx, "parent_pool_idx"), torch.int32, "parent_pool_idx"),
@@ -257,9 +279,9 @@ def radar_draft_expand(logits, parent_scores, parent_pool_idx, k, pool, out=None
         _ptr(out.frontier_scores, torch.float32), _ptr(out.frontier_conf, torch.float32),
         _ptr(pool.tokens, torch.int32), _ptr(pool.scores, torch.float32), _ptr(pool.parents, torch.int32),
         ctypes.byref(desc), wp, wn, _stream())
-    _check(rc, "radar_draft_expand")
+    keep = (logits, parent_scores, parent_pool_idx, out, pool, desc, workspace)
     pool.count += F * k
-    return out
+    return _finish("radar_draft_expand", load().radar_draft_expand, args, keep, out, prepared)
 
 
 class TreeOut:
@@ -276,19 +298,18 @@ def radar_draft_rerank_workspace_bytes(pool_count, N):
     return int(load().radar_draft_rerank_workspace_bytes(int(pool_count), int(N)))
 
 
-def radar_draft_rerank(pool, N, root_token, out=None, workspace=None):
+def radar_draft_rerank(pool, N, root_token, out=None, workspace=None, prepared=False):
     """Keep the best N pool entries; returns a TreeOut (device tensors)."""
     if out is None:
         out = TreeOut(N, pool.tokens.device)
     wp, wn = _ws_args(workspace)
-    rc = load().radar_draft_rerank(
+    args = (
         _ptr(pool.tokens, torch.int32), _ptr(pool.scores, torch.float32), _ptr(pool.parents, torch.int32),
         int(pool.count), int(N), int(root_token),
         _ptr(out.tokens, torch.int32), _ptr(out.parents, torch.int32), _ptr(out.scores, torch.float32),
         _ptr(out.depth, torch.int32), _ptr(out.pool_idx, torch.int32), _ptr(out.n_nodes, torch.int32),
         wp, wn, _stream())
-    _check(rc, "radar_draft_rerank")
-    return out
+    return _finish("radar_draft_rerank", load().radar_draft_rerank, args, (pool, out, workspace), out, prepared)
 
 
 # ------------------------------------------------------------ verification
@@ -304,7 +325,7 @@ def radar_verify_accept_workspace_bytes(desc):
 
 
 def radar_verify_accept(target_logits, draft_tokens, parents, n_nodes=None, uniforms=None, mode=RADAR_ACCEPT_GREEDY,
-                        temperature=1.0, D_max=None, out=None, workspace=None):
+                        temperature=1.0, D_max=None, out=None, workspace=None, prepared=False):
     """target_logits f32 [B,T,V]; draft_tokens, parents i32 [B,T]; n_nodes i32 [B] or None;
     uniforms f32 [B,T+1] (sampling).  Returns (accept_len [B], accept_path [B,D_max+1], bonus_token [B])."""
     B, T, V = target_logits.shape
@@ -319,7 +340,7 @@ def radar_verify_accept(target_logits, draft_tokens, parents, n_nodes=None, unif
     if workspace is None:
         workspace = new_workspace(radar_verify_accept_workspace_bytes(desc), dev)
     wp, wn = _ws_args(workspace)
-    rc = load().radar_verify_accept(
+    args = (
         _ptr(_dense(target_logits, "target_logits"), torch.float32, "target_logits"),
         _ptr(_dense(draft_tokens, "draft_tokens"), torch.int32, "draft_tokens"),
         _ptr(_dense(parents, "parents"), torch.int32, "parents"),
@@ -327,8 +348,8 @@ def radar_verify_accept(target_logits, draft_tokens, parents, n_nodes=None, unif
         _ptr(None if uniforms is None else _dense(uniforms, "uniforms"), torch.float32, "uniforms"),
         _ptr(out[0], torch.int32), _ptr(out[1], torch.int32), _ptr(out[2], torch.int32),
         ctypes.byref(desc), wp, wn, _stream())
-    _check(rc, "radar_verify_accept")
-    return out
+    keep = (target_logits, draft_tokens, parents, n_nodes, uniforms, out, desc, workspace)
+    return _finish("radar_verify_accept", load().radar_verify_accept, args, keep, out, prepared)
 
 
 def radar_debug_validate_tree(parents, n_nodes=None):

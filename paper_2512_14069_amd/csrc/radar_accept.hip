@@ -1,24 +1,30 @@
 // Verification walk of RADAR's speculative-sampling cycle (Sec. 3, Eq. 1-2; tree
 // form per Sec. 4.3, Eq. 11-13) as one HIP launch for gfx950.
 //
-// Phase 1, grid (chunks of 4096 logits, tree rows, sequences): one streaming
-// read of the target logits (T*V*4 bytes per sequence) leaves per chunk the
-// arg-max key and, in sampling mode, (max, sum exp) of the temperature-scaled
-// row.  Phase 2: the workgroup whose arrival ticket is the last of its ROW
-// merges that row's chunk partials (one per lane).  Phase 3: the workgroup whose
-// ticket is the last of its SEQUENCE walks the tree in a single wavefront (one
-// lane per node, sibling sets found with ballots); the residual draw needs one
-// more pass over a single 16 KB chunk.  Arrival counters sit 64 B apart.
+// Phase 1, grid (blocks of the vocabulary, tree rows, sequences): one streaming
+// read of the target logits (T*V*4 bytes per sequence).  Every wavefront owns
+// 1024 consecutive logits and leaves their arg-max key and, in sampling mode,
+// (max, sum exp) of the temperature-scaled values; nothing is combined inside a
+// workgroup.  Phase 2: the workgroup whose arrival ticket is the last of its ROW
+// merges that row's partials in one wavefront and turns the sums into masses
+// relative to the row maximum.  Phase 3: the workgroup whose ticket is the last
+// of its SEQUENCE walks the tree in one wavefront, one lane per node: sibling
+// sets come from ballots, everything the walk compares sits in registers and is
+// passed between lanes by lane reads or DPP scans.  The residual draw scans the
+// 1024-logit masses across lanes and then re-reads one such block (4 KB).
 #include "radar_device.h"
 #include "radar_host.h"
 
 namespace radar {
 
 constexpr int kAccThreads = 256;
+constexpr int kAccWaves = kAccThreads / kWave;
 constexpr int kAccEPT = 16;
-constexpr int kAccChunk = kAccThreads * kAccEPT;
-constexpr int kAccMaxChunks = 256;
+constexpr int kAccSub = kWave * kAccEPT;              // 1024 logits per wavefront = one partial
+constexpr int kAccChunk = kAccThreads * kAccEPT;      // logits per workgroup
+constexpr int kAccMaxSubs = 4096;                     // V <= 4,194,304
 constexpr int kAccCounterStride = 16;   // counters 64 B apart (same-line fetch-adds serialise)
+constexpr float kAccLog2e = 1.4426950408889634f;
 
 struct AcceptArgs {
     const float *logits;
@@ -29,304 +35,410 @@ struct AcceptArgs {
     int32_t *accept_len;
     int32_t *accept_path;
     int32_t *bonus;
-    int B, T, V, D_max, mode, nchunks;
+    int B, T, V, D_max, mode, nwg, nsub;   // nwg workgroups and nsub 1024-logit blocks per row
+    int exact_scale;            // 1/temperature is exactly representable in fp32
     float inv_temp_f;
     double inv_temp;
-    unsigned int *counters;     // [(b*T + r) * stride] chunks of a row, [(B*T + b) * stride] rows of a sequence
+    unsigned int *counters;     // [(b*T + r) * stride] workgroups of a row, [(B*T + b) * stride] rows of a sequence
     uint64_t *row_key;          // [B][T] arg-max key of the row
-    double *row_L;              // [B][T] sum of exp(y - row_M)
+    double *row_L;              // [B][T] sum of exp(y - row_M), y = logit / temperature
     float *row_M;               // [B][T]
-    uint64_t *part_key;         // [B][T][nchunks] arg-max key of the chunk
-    double *part_l;             // [B][T][nchunks] sum of exp(y - part_m) over the chunk, y = logit / temperature
-    float *part_m;              // [B][T][nchunks] reference maximum of the chunk
+    uint64_t *part_key;         // [B][T][nsub] arg-max key of the block
+    double *part_l;             // [B][T][nsub] sum of exp(y - part_m) over the block; once the row is merged:
+                                //              sum of exp(y - row_M) over the block
+    float *part_m;              // [B][T][nsub] reference maximum of the block
 };
 
 struct AcceptSmem {
-    uint64_t wave_key[4];
-    float wave_m[4];
-    double wave_l[4];
     unsigned int ticket;
-    // phase 2
-    int row_arg[RADAR_T_MAX];
     double row_lse[RADAR_T_MAX];
-    float row_M[RADAR_T_MAX];
-    double row_L[RADAR_T_MAX];
-    int par[RADAR_T_MAX], tok[RADAR_T_MAX];
-    double pc[RADAR_T_MAX];
-    int rej[RADAR_T_MAX];
-    int path[RADAR_T_MAX];
-    int nrej, cur, chunk_pick, bonus, owner, last_pos;
-    double R, residual_target;
-    double mass[kAccMaxChunks];
-    double tsum[kAccThreads];
+    int row_arg[RADAR_T_MAX];
+    double rej_e[RADAR_T_MAX];                    // what each rejected token carries, and the block it lies in
+    int rej_sub[RADAR_T_MAX];
+    unsigned int rej_bits[kWave];                 // pass (b): which of a lane's 16 tokens are rejected ones
+    unsigned char seen[4096];                     // sibling tokens, hashed
 };
+
+// exp(x / temperature - ref) for one logit, as a double.  The exponent difference is rounded to
+// fp32 once (an fp32 FMA does that when the scale is exact in fp32, else it is formed in fp64);
+// the exponential itself is the fp32 one.  The sums that use it are kept in fp64.
+__device__ __forceinline__ double scaled_exp(float x, const AcceptArgs &a, float ref) {
+    if (a.exact_scale) return (double)__builtin_amdgcn_exp2f(__builtin_fmaf(x, a.inv_temp_f, -ref) * kAccLog2e);
+    return (double)expf((float)((double)x * a.inv_temp - (double)ref));
+}
+
+__device__ __forceinline__ double readlane_f64(double v, int lane) {
+    return __longlong_as_double((long long)readlane_u64((uint64_t)__double_as_longlong(v), lane));
+}
+
+// Inclusive prefix sum over the lanes of a wavefront by DPP moves (shift by 1, 2, 4, 8 inside each
+// 16-lane row, then the row totals are carried into the following rows); fixed association order.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_take_f64(double v) {
+    const uint64_t b = (uint64_t)__double_as_longlong(v);
+    // lanes without a source lane, and rows outside ROW_MASK, receive 0
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)b, CTRL, ROW_MASK, 0xF, true);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(b >> 32), CTRL, ROW_MASK, 0xF, true);
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+__device__ __forceinline__ double wave_scan_f64(double v) {
+    v += dpp_take_f64<0x111, 0xF>(v);             // row_shr:1
+    v += dpp_take_f64<0x112, 0xF>(v);             // row_shr:2
+    v += dpp_take_f64<0x114, 0xF>(v);             // row_shr:4
+    v += dpp_take_f64<0x118, 0xF>(v);             // row_shr:8
+    v += dpp_take_f64<0x142, 0xA>(v);             // row_bcast:15 -> rows 1 and 3
+    v += dpp_take_f64<0x143, 0xC>(v);             // row_bcast:31 -> rows 2 and 3
+    return v;
+}
+
+// 16 logits per lane of one 1024-logit block: lane l takes [16 * l, 16 * l + 16) when CONTIG (pass
+// (b) needs token order inside a lane), else 4 x (64 lanes x 16 B) interleaved (widest requests).
+template <bool VEC4, bool CONTIG>
+__device__ __forceinline__ void load_block(const float *row, int i_block, int V, float (&x)[kAccEPT], int (&first)[kAccEPT / 4]) {
+    const int lane = lane_id();
+    float4 raw[kAccEPT / 4];
+#pragma unroll
+    for (int g = 0; g < kAccEPT / 4; ++g) {
+        const int i = i_block + (CONTIG ? lane * kAccEPT + 4 * g : g * (kWave * 4) + lane * 4);
+        first[g] = i;
+        // branch-free: out-of-range lanes read a valid address and are masked afterwards
+        if (VEC4) {
+            raw[g] = *reinterpret_cast<const float4 *>(row + (i < V ? i : 0));
+        } else {
+            raw[g].x = row[min(i + 0, V - 1)];
+            raw[g].y = row[min(i + 1, V - 1)];
+            raw[g].z = row[min(i + 2, V - 1)];
+            raw[g].w = row[min(i + 3, V - 1)];
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < kAccEPT / 4; ++g) {
+        const float v[4] = {raw[g].x, raw[g].y, raw[g].z, raw[g].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) x[4 * g + j] = (first[g] + j < V) ? v[j] : -INFINITY;
+    }
+}
 
 template <bool VEC4>
 __global__ __launch_bounds__(kAccThreads) void accept_kernel(AcceptArgs a) {
     __shared__ AcceptSmem s;
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
-    const int chunk = blockIdx.x, r = blockIdx.y, b = blockIdx.z;
+    const int r = blockIdx.y, b = blockIdx.z;
     int nn = a.n_nodes ? a.n_nodes[b] : a.T;
     nn = max(1, min(nn, a.T));
     if (r >= nn) return;
     const bool sampling = (a.mode == RADAR_ACCEPT_SAMPLE);
     const float *row = a.logits + ((size_t)b * a.T + r) * a.V;
-    const int base = chunk * kAccChunk;
+    const int sub = blockIdx.x * kAccWaves + w;              // this wavefront's 1024-logit block
 
-    // ---------------- phase 1: chunk arg-max (and scaled max / sum-exp)
-    float x[kAccEPT];
-    uint64_t best = 0;
+    // ---------------- phase 1: per-wavefront arg-max (and scaled max / sum-exp)
+    if (sub < a.nsub) {
+        float x[kAccEPT];
+        int first[kAccEPT / 4];
+        load_block<VEC4, false>(row, sub * kAccSub, a.V, x, first);
+        // the lane's elements come in ascending index order, so "strictly greater" keeps the lowest
+        // index among equal values (and -0.0 ties with +0.0, as the key order has it)
+        float bx = -INFINITY;
+        int bi = first[0];
 #pragma unroll
-    for (int g = 0; g < kAccEPT / 4; ++g) {
-        const int idx0 = base + g * (kAccThreads * 4) + tid * 4;
-        // branch-free: out-of-range lanes read a valid address and are masked afterwards
-        float4 v;
-        if (VEC4) {
-            v = *reinterpret_cast<const float4 *>(row + (idx0 < a.V ? idx0 : 0));
-        } else {
-            v.x = row[min(idx0 + 0, a.V - 1)];
-            v.y = row[min(idx0 + 1, a.V - 1)];
-            v.z = row[min(idx0 + 2, a.V - 1)];
-            v.w = row[min(idx0 + 3, a.V - 1)];
+        for (int e = 0; e < kAccEPT; ++e) {
+            const bool better = x[e] > bx;
+            bx = better ? x[e] : bx;
+            bi = better ? first[e / 4] + (e & 3) : bi;
         }
-        if (idx0 + 0 >= a.V) v.x = -INFINITY;
-        if (idx0 + 1 >= a.V) v.y = -INFINITY;
-        if (idx0 + 2 >= a.V) v.z = -INFINITY;
-        if (idx0 + 3 >= a.V) v.w = -INFINITY;
-        x[4 * g + 0] = v.x; x[4 * g + 1] = v.y; x[4 * g + 2] = v.z; x[4 * g + 3] = v.w;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (idx0 + j < a.V) best = max_u64(best, make_key(x[4 * g + j], uint32_t(idx0 + j)));
-    }
-    best = wave_max_u64(best);
-    if (lane == 0) s.wave_key[w] = best;
-    if (sampling) {
-        // exponent differences are formed in fp64 and the sums are kept in fp64, so that the
-        // only fp32 rounding left is the one inside expf (unbiased, averaging out over a chunk)
-        float tm = -INFINITY;
-#pragma unroll
-        for (int e = 0; e < kAccEPT; ++e) tm = fmaxf(tm, x[e] * a.inv_temp_f);
-        const float wm = wave_max_f32(tm);
-        double tl = 0.0;
-        if (wm > -INFINITY) {
-#pragma unroll
-            for (int e = 0; e < kAccEPT; ++e)
-                tl += (double)expf((float)((double)x[e] * a.inv_temp - (double)wm));
-        }
-        const double wl = wave_sum_f64(tl);
-        if (lane == 0) { s.wave_m[w] = wm; s.wave_l[w] = wl; }
-    }
-    __syncthreads();
-    const size_t pslot = ((size_t)b * a.T + r) * a.nchunks + chunk;
-    if (w == 0) {
-        const uint64_t bk = max_u64(max_u64(s.wave_key[0], s.wave_key[1]), max_u64(s.wave_key[2], s.wave_key[3]));
-        if (lane == 0) store_shared_result(&a.part_key[pslot], bk);
+        uint64_t best = bi < a.V ? make_key(bx, uint32_t(bi)) : 0;
+        best = wave_max_u64(best);
+        const size_t pslot = ((size_t)b * a.T + r) * a.nsub + sub;
         if (sampling) {
-            const float m = fmaxf(fmaxf(s.wave_m[0], s.wave_m[1]), fmaxf(s.wave_m[2], s.wave_m[3]));
-            double t = 0.0;                                  // lanes 0..3: one fp64 term each
-            if (lane < 4 && s.wave_m[lane] > -INFINITY) t = s.wave_l[lane] * exp((double)s.wave_m[lane] - (double)m);
-            const uint64_t tb = (uint64_t)__double_as_longlong(t);
-            const double l = (__longlong_as_double((long long)readlane_u64(tb, 0)) +
-                              __longlong_as_double((long long)readlane_u64(tb, 1))) +
-                             (__longlong_as_double((long long)readlane_u64(tb, 2)) +
-                              __longlong_as_double((long long)readlane_u64(tb, 3)));
+            float tm = -INFINITY;
+#pragma unroll
+            for (int e = 0; e < kAccEPT; ++e) tm = fmaxf(tm, x[e] * a.inv_temp_f);
+            const float wm = wave_max_f32(tm);
+            double tl = 0.0;
+            if (wm > -INFINITY) {
+#pragma unroll
+                for (int e = 0; e < kAccEPT; ++e) tl += scaled_exp(x[e], a, wm);
+            }
+            const double wl = wave_sum_f64(tl);
             if (lane == 0) {
-                store_shared_result(&a.part_m[pslot], m);
-                store_shared_result(&a.part_l[pslot], l);
+                store_shared_result(&a.part_m[pslot], wm);
+                store_shared_result(&a.part_l[pslot], wl);
             }
         }
+        if (lane == 0) store_shared_result(&a.part_key[pslot], best);
     }
     unsigned int *row_counter = &a.counters[((size_t)b * a.T + r) * kAccCounterStride];
-    if (publish_then_ticket(row_counter, &s.ticket) != (unsigned int)(a.nchunks - 1)) return;
+    if (publish_then_ticket(row_counter, &s.ticket) != (unsigned int)(a.nwg - 1)) return;
+    if (w != 0) {                                            // one wavefront does the rest; the others only
+        __syncthreads();                                     // take part in the next ticket's barriers
+        __syncthreads();
+        return;
+    }
 
-    // ---------------- phase 2: last workgroup of row r -- merge its chunk partials (one per lane)
+    // ---------------- phase 2: last workgroup of row r -- merge the row's partials.
+    // What only the walk needs (lane c is tree node c) is fetched here, so that it has arrived by
+    // the time the walk starts.
+    int p = -1, t = -1;
+    float xg = 0.f, uc = 0.f, ubonus = 0.f;
+    bool tree_ok = false;
     {
-        const size_t p0 = ((size_t)b * a.T + r) * a.nchunks;
-        const int c = min(tid, a.nchunks - 1);
-        uint64_t kb = load_shared_result(&a.part_key[p0 + c]);
-        float mc = -INFINITY;
-        double lc = 0.0;
+        const int c = lane;
+        if (c < nn) { p = a.parents[(size_t)b * a.T + c]; t = a.tokens[(size_t)b * a.T + c]; }
+        tree_ok = (c > 0 && c < nn && p >= 0 && p < c);
         if (sampling) {
-            mc = load_shared_result(&a.part_m[p0 + c]);
-            lc = load_shared_result(&a.part_l[p0 + c]);
+            const float *u = a.uniforms + (size_t)b * (a.T + 1);
+            uc = u[min(c, a.T)];
+            ubonus = u[a.T];
+            if (tree_ok && t >= 0 && t < a.V) xg = a.logits[((size_t)b * a.T + p) * a.V + t];
         }
-        if (tid >= a.nchunks) { kb = 0; mc = -INFINITY; }
+        const size_t p0 = ((size_t)b * a.T + r) * a.nsub;
+        // the first 128 partials (all of them up to V = 131072) are taken in one round trip
+        uint64_t kb = 0;
+        float m_[2];
+        double l_[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int c0 = i * kWave + lane;
+            const int cc = min(c0, a.nsub - 1);                  // branch-free: clamp, load, mask
+            const uint64_t k2 = load_shared_result(&a.part_key[p0 + cc]);
+            kb = max_u64(kb, c0 < a.nsub ? k2 : 0);
+            m_[i] = -INFINITY; l_[i] = 0.0;
+            if (sampling) {
+                const float m2 = load_shared_result(&a.part_m[p0 + cc]);
+                const double l2 = load_shared_result(&a.part_l[p0 + cc]);
+                if (c0 < a.nsub) { m_[i] = m2; l_[i] = l2; }
+            }
+        }
+        float mmax = fmaxf(m_[0], m_[1]);
+        for (int c0 = 2 * kWave + lane; c0 < a.nsub; c0 += kWave) {
+            kb = max_u64(kb, load_shared_result(&a.part_key[p0 + c0]));
+            if (sampling) mmax = fmaxf(mmax, load_shared_result(&a.part_m[p0 + c0]));
+        }
         kb = wave_max_u64(kb);
-        const float wmx = wave_max_f32(mc);
-        if (lane == 0) { s.wave_key[w] = kb; s.wave_m[w] = wmx; }
-        __syncthreads();
-        const float M = fmaxf(fmaxf(s.wave_m[0], s.wave_m[1]), fmaxf(s.wave_m[2], s.wave_m[3]));
-        const double term = (sampling && mc > -INFINITY) ? lc * exp((double)mc - (double)M) : 0.0;
-        const double ws = wave_sum_f64(term);
-        if (lane == 0) s.wave_l[w] = ws;
-        __syncthreads();
-        if (tid == 0) {
+        const float M = wave_max_f32(mmax);
+        double lsum = 0.0;
+        if (sampling) {
+            // each block's mass relative to the row maximum: summed for the row, and left in part_l
+            // for the residual draw
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int c0 = i * kWave + lane;
+                const double mass = m_[i] > -INFINITY ? l_[i] * exp((double)m_[i] - (double)M) : 0.0;
+                if (c0 < a.nsub) store_shared_result(&a.part_l[p0 + c0], mass);
+                lsum += mass;
+            }
+            for (int c0 = 2 * kWave + lane; c0 < a.nsub; c0 += kWave) {
+                const float m2 = load_shared_result(&a.part_m[p0 + c0]);
+                const double l2 = load_shared_result(&a.part_l[p0 + c0]);
+                const double mass = m2 > -INFINITY ? l2 * exp((double)m2 - (double)M) : 0.0;
+                store_shared_result(&a.part_l[p0 + c0], mass);
+                lsum += mass;
+            }
+        }
+        const double L = wave_sum_f64(lsum);
+        if (lane == 0) {
             const size_t rs = (size_t)b * a.T + r;
-            store_shared_result(&a.row_key[rs],
-                                max_u64(max_u64(s.wave_key[0], s.wave_key[1]), max_u64(s.wave_key[2], s.wave_key[3])));
+            store_shared_result(&a.row_key[rs], kb);
             if (sampling) {
                 store_shared_result(&a.row_M[rs], M);
-                store_shared_result(&a.row_L[rs], (s.wave_l[0] + s.wave_l[1]) + (s.wave_l[2] + s.wave_l[3]));
+                store_shared_result(&a.row_L[rs], L);
             }
             store_shared_result(row_counter, 0u);            // leave the row counter clean for the next call
         }
     }
     unsigned int *seq_counter = &a.counters[((size_t)a.B * a.T + b) * kAccCounterStride];
     if (publish_then_ticket(seq_counter, &s.ticket) != (unsigned int)(nn - 1)) return;
-    if (tid == 0) store_shared_result(seq_counter, 0u);
+    if (lane == 0) store_shared_result(seq_counter, 0u);
 
-    // ---------------- phase 3: last workgroup of sequence b
-    if (tid < RADAR_T_MAX) {
-        const size_t rs = (size_t)b * a.T + min(tid, nn - 1);
-        const uint64_t kb = load_shared_result(&a.row_key[rs]);
-        s.row_arg[tid] = (int)key_index(kb);
-        if (sampling) {
-            const float M = load_shared_result(&a.row_M[rs]);
-            const double L = load_shared_result(&a.row_L[rs]);
-            s.row_M[tid] = M; s.row_L[tid] = L; s.row_lse[tid] = (double)M + log(L);
-        }
+    // ---------------- phase 3: last workgroup of sequence b, one wavefront
+    const int c = lane;
+    const size_t rs = (size_t)b * a.T + min(c, nn - 1);
+    const int arg = (int)key_index(load_shared_result(&a.row_key[rs]));
+    float Mc = 0.f;
+    double Lc = 1.0;
+    if (sampling) {
+        Mc = load_shared_result(&a.row_M[rs]);
+        Lc = load_shared_result(&a.row_L[rs]);
+        s.row_lse[c] = (double)Mc + log(Lc);
     }
-    if (tid < RADAR_T_MAX) {
-        int p = -1, t = -1;
-        if (tid < nn) { p = a.parents[(size_t)b * a.T + tid]; t = a.tokens[(size_t)b * a.T + tid]; }
-        s.par[tid] = p; s.tok[tid] = t;
-    }
-    __syncthreads();
+    s.row_arg[c] = arg;
+    wave_lds_sync();
 
+    int cur = 0, len = 0, mypath = 0;                        // lane i keeps path[i]
     int32_t *path = a.accept_path + (size_t)b * (a.D_max + 1);
-    if (w == 0) {
-        const int c = lane;
-        const int p = s.par[c], t = s.tok[c];
-        const bool valid = (c > 0 && c < nn && p >= 0 && p < c);
-        int cur = 0, len = 0;
-        if (lane == 0) s.path[0] = 0;
-        if (!sampling) {
-            const bool match = valid && s.row_arg[p] == t;
-            while (len < a.D_max) {
-                const uint64_t m = __ballot(match && p == cur);
-                if (!m) break;
-                cur = __ffsll((long long)m) - 1;
-                ++len;
-                if (lane == 0) s.path[len] = cur;
+    if (!sampling) {
+        const bool match = tree_ok && s.row_arg[p] == t;
+        while (len < a.D_max) {
+            const uint64_t m = __ballot(match && p == cur);
+            if (!m) break;
+            cur = __ffsll((long long)m) - 1;
+            ++len;
+            if (lane == len) mypath = cur;
+        }
+        if (lane == 0) { a.accept_len[b] = len; a.bonus[b] = s.row_arg[cur]; }
+        if (c <= a.D_max) path[c] = (c <= len) ? mypath : -1;
+        return;
+    }
+
+    // probability of each node's token under its parent's row
+    double pc = 0.0;
+    if (tree_ok && t >= 0 && t < a.V) pc = exp((double)xg * a.inv_temp - s.row_lse[p]);
+    double R = 0.0;
+    int nrej = 0, rejtok = -1;                               // lane j keeps the j-th rejected token
+    for (;;) {
+        uint64_t kids = (len < a.D_max) ? __ballot(tree_ok && p == cur) : 0ull;
+        R = 0.0; nrej = 0;
+        int next = -1;
+        if (__popcll(kids) > 4) {
+            // wide level: all children at once.  A child is reached only if every earlier sibling was
+            // rejected, so its residual is the sum of the earlier siblings' probabilities.
+            const bool kid = (kids >> lane) & 1;
+            // same token as an earlier sibling?  Tokens are hashed into a byte table; a lane that does
+            // not read its own number back shares a bucket, and only then are tokens compared.
+            const uint32_t h = ((uint32_t)t * 2654435761u) >> 20;
+            if (kid) s.seen[h] = (unsigned char)lane;
+            wave_lds_sync();
+            const bool shared = kid && s.seen[h] != (unsigned char)lane;
+            wave_lds_sync();
+            bool dup = false;
+            if (__ballot(shared)) {
+                for (uint64_t m = kids; m; m &= m - 1) {
+                    const int cc = __ffsll((long long)m) - 1;
+                    const int tcc = (int)readlane_u32((uint32_t)t, cc);
+                    dup = dup || (kid && lane > cc && t == tcc);
+                }
             }
-            if (lane == 0) { a.accept_len[b] = len; a.bonus[b] = s.row_arg[cur]; }
+            const bool live = kid && !dup;
+            const double mine = live ? pc : 0.0;
+            const double before = wave_scan_f64(mine) - mine;
+            const uint64_t acc = __ballot(live && (double)uc * (1.0 - before) < pc);
+            uint64_t rejected = __ballot(live);
+            if (acc) {
+                next = __ffsll((long long)acc) - 1;
+                rejected &= (1ull << next) - 1;
+            }
+            nrej = __popcll(rejected);
+            R = nrej ? readlane_f64(before + mine, 63 - __clzll((long long)rejected)) : 0.0;
+            // lane j takes the token of the j-th rejected child
+            if ((rejected >> lane) & 1) s.row_arg[lanes_below(rejected)] = t;      // row_arg is free by now
+            wave_lds_sync();
+            rejtok = lane < nrej ? s.row_arg[lane] : -1;
+            wave_lds_sync();
         } else {
-            // probability of each node's token under its parent's row
-            double pcv = 0.0;
-            if (valid && t >= 0 && t < a.V) {
-                const float xv = a.logits[((size_t)b * a.T + p) * a.V + t];
-                pcv = exp((double)xv * a.inv_temp - s.row_lse[p]);
-            }
-            s.pc[c] = pcv;
-            wave_lds_sync();
-            bool dup = false;                         // same token as an earlier sibling
-            for (int o = 1; o < c; ++o) dup = dup || (valid && o > p && s.par[o] == p && s.tok[o] == t);
-            const float *u = a.uniforms + (size_t)b * (a.T + 1);
-            double R = 0.0;
-            int nrej = 0;
-            for (;;) {
-                uint64_t kids = (len < a.D_max) ? __ballot(valid && !dup && p == cur) : 0ull;
-                R = 0.0; nrej = 0;
-                int next = -1;
-                while (kids) {
-                    const int cc = __ffsll((long long)kids) - 1;
-                    kids &= kids - 1;
-                    const double pcc = s.pc[cc];
-                    if ((double)u[cc] * (1.0 - R) < pcc) { next = cc; break; }
-                    R += pcc;
-                    if (lane == 0) s.rej[nrej] = s.tok[cc];
-                    ++nrej;
-                }
-                if (next < 0) break;
-                cur = next;
-                ++len;
-                if (lane == 0) s.path[len] = cur;
-            }
-            wave_lds_sync();
-            // residual draw: find the chunk that holds the target mass
-            const float M = s.row_M[cur];
-            const size_t p0 = ((size_t)b * a.T + cur) * a.nchunks;
-            const float *xr = a.logits + ((size_t)b * a.T + cur) * a.V;
-            for (int cch = lane; cch < a.nchunks; cch += kWave) {
-                const float mc = load_shared_result(&a.part_m[p0 + cch]);
-                const double lc = load_shared_result(&a.part_l[p0 + cch]);
-                double mass = (mc > -INFINITY) ? lc * exp((double)mc - (double)M) : 0.0;
-                for (int j = 0; j < nrej; ++j) {
-                    const int tj = s.rej[j];
-                    if (tj >= 0 && tj < a.V && tj / kAccChunk == cch)
-                        mass -= exp((double)xr[tj] * a.inv_temp - (double)M);
-                }
-                s.mass[cch] = mass > 0.0 ? mass : 0.0;
-            }
-            wave_lds_sync();
-            const double target = (double)u[a.T] * (1.0 - R) * s.row_L[cur];
-            double cum = 0.0;
-            int pick = -1;
-            for (int cch = 0; cch < a.nchunks; ++cch) {
-                const double mcc = s.mass[cch];
-                if (cum + mcc > target) { pick = cch; break; }
-                cum += mcc;
-            }
-            if (pick < 0) {                            // rounding pushed the target past the total
-                for (int cch = a.nchunks - 1; cch >= 0; --cch)
-                    if (s.mass[cch] > 0.0) { pick = cch; break; }
-                if (pick < 0) pick = 0;
-                cum = target;                          // nothing will exceed it: fall back to the last token with mass
-            }
-            if (lane == 0) {
-                a.accept_len[b] = len;
-                s.cur = cur; s.nrej = nrej; s.R = R; s.chunk_pick = pick; s.residual_target = target - cum;
-                s.owner = kAccThreads; s.last_pos = -1; s.bonus = -1;
+            while (kids) {
+                const int cc = __ffsll((long long)kids) - 1;
+                kids &= kids - 1;
+                const int tcc = (int)readlane_u32((uint32_t)t, cc);
+                if (__ballot(lane < nrej && rejtok == tcc)) continue;   // same token as an earlier sibling
+                const double pcc = readlane_f64(pc, cc);
+                const float ucc = readlane_f32(uc, cc);
+                if ((double)ucc * (1.0 - R) < pcc) { next = cc; break; }
+                R += pcc;
+                if (lane == nrej) rejtok = tcc;
+                ++nrej;
             }
         }
-        wave_lds_sync();
-        if (c <= a.D_max) path[c] = (c <= len) ? s.path[c] : -1;
+        if (next < 0) break;
+        cur = next;
+        ++len;
+        if (lane == len) mypath = cur;
     }
-    if (!sampling) return;
-    __syncthreads();
+    if (c <= a.D_max) path[c] = (c <= len) ? mypath : -1;
+    if (lane == 0) a.accept_len[b] = len;
 
-    // (b) residual draw inside the chosen chunk: every lane owns 16 consecutive tokens
-    {
-        const int cur = s.cur, nrej = s.nrej;
-        const float M = s.row_M[cur];
-        const float *xr = a.logits + ((size_t)b * a.T + cur) * a.V;
-        const int i0 = s.chunk_pick * kAccChunk + tid * kAccEPT;
-        double pv[kAccEPT];
-        double sum = 0.0;
-        int lastpos = -1;
+    // ---- residual draw, (a): the 1024-logit block that holds the target mass
+    const float M = readlane_f32(Mc, cur);
+    const double L = readlane_f64(Lc, cur);
+    const size_t p0 = ((size_t)b * a.T + cur) * a.nsub;
+    const float *xr = a.logits + ((size_t)b * a.T + cur) * a.V;
+    // masses of the first 128 blocks: requested together with the rejected tokens' logits
+    double mass0 = (lane < a.nsub) ? load_shared_result(&a.part_l[p0 + lane]) : 0.0;
+    double mass1 = (kWave + lane < a.nsub) ? load_shared_result(&a.part_l[p0 + kWave + lane]) : 0.0;
+    {   // what the rejected children's tokens carry (the same arithmetic as pass (b) uses)
+        float xj = -INFINITY;
+        int sj = -1;
+        if (lane < nrej && rejtok >= 0 && rejtok < a.V) {
+            xj = xr[rejtok];
+            sj = rejtok / kAccSub;
+        }
+        s.rej_e[lane] = sj >= 0 ? scaled_exp(xj, a, M) : 0.0;
+        s.rej_sub[lane] = sj;
+        wave_lds_sync();
+    }
+    const double target = (double)ubonus * (1.0 - R) * L;
+    double before = 0.0;                                     // mass of the blocks before this group of 64
+    int pick = -1, lastc = -1;
+    double resid = 0.0;
+    for (int c0 = 0; c0 < a.nsub && pick < 0; c0 += kWave) {
+        const int cs = c0 + lane;
+        double mass = c0 == 0 ? mass0 : mass1;
+        if (c0 >= 2 * kWave) mass = (cs < a.nsub) ? load_shared_result(&a.part_l[p0 + cs]) : 0.0;
+        for (int j0 = 0; j0 < nrej; j0 += 8) {                // broadcast LDS reads, eight in flight; entries
+#pragma unroll                                                 // past nrej name no block
+            for (int j = j0; j < j0 + 8; ++j) {
+                const double e = s.rej_e[j];                 // read unconditionally: no branch per entry
+                mass -= (s.rej_sub[j] == cs) ? e : 0.0;
+            }
+        }
+        mass = mass > 0.0 ? mass : 0.0;
+        const double incl = before + wave_scan_f64(mass);
+        const uint64_t hit = __ballot(cs < a.nsub && incl > target);
+        const uint64_t pos = __ballot(cs < a.nsub && mass > 0.0);
+        if (pos) lastc = c0 + 63 - __clzll((long long)pos);
+        if (hit) {
+            const int hl = __ffsll((long long)hit) - 1;
+            pick = c0 + hl;
+            resid = target - (readlane_f64(incl, hl) - readlane_f64(mass, hl));
+        }
+        before = readlane_f64(incl, kWave - 1);
+    }
+    if (pick < 0) {                                          // rounding pushed the target past the total:
+        pick = lastc >= 0 ? lastc : 0;                       // the last token with mass is taken
+        resid = INFINITY;
+    }
+
+    // ---- residual draw, (b): inside the chosen block every lane owns 16 consecutive tokens
+    s.rej_bits[lane] = 0;
+    wave_lds_sync();
+    if (lane < nrej && rejtok >= 0 && rejtok / kAccSub == pick) {
+        const int off = rejtok - pick * kAccSub;
+        atomicOr(&s.rej_bits[off / kAccEPT], 1u << (off % kAccEPT));
+    }
+    float xv[kAccEPT];
+    int first[kAccEPT / 4];
+    load_block<VEC4, true>(xr, pick * kAccSub, a.V, xv, first);
+    wave_lds_sync();
+    const unsigned int rejected = s.rej_bits[lane];
+    const int i0 = pick * kAccSub + lane * kAccEPT;
+    double pv[kAccEPT];
+    double sum = 0.0;
+    int lastpos = -1;
+#pragma unroll
+    for (int e = 0; e < kAccEPT; ++e) {
+        const int i = i0 + e;
+        const double v = (i < a.V && !((rejected >> e) & 1)) ? scaled_exp(xv[e], a, M) : 0.0;
+        pv[e] = v;
+        sum += v;
+        if (v > 0.0) lastpos = i;
+    }
+    const double incl = wave_scan_f64(sum);
+    const uint64_t hit = __ballot(incl > resid);
+    const int lp = (int)wave_max_u32((uint32_t)(lastpos + 1)) - 1;      // last token of the block with mass
+    int bonus = lp;
+    if (hit) {
+        const int owner = __ffsll((long long)hit) - 1;
+        int mine = -1;
+        double cdf = incl - sum;
 #pragma unroll
         for (int e = 0; e < kAccEPT; ++e) {
-            const int i = i0 + e;
-            double v = 0.0;
-            if (i < a.V) {
-                v = exp((double)xr[i] * a.inv_temp - (double)M);
-                for (int j = 0; j < nrej; ++j) if (s.rej[j] == i) v = 0.0;
-            }
-            pv[e] = v;
-            sum += v;
-            if (v > 0.0) lastpos = i;
+            cdf += pv[e];
+            if (mine < 0 && pv[e] > 0.0 && cdf > resid) mine = i0 + e;
         }
-        s.tsum[tid] = sum;
-        __syncthreads();
-        double prefix = 0.0;
-        for (int j = 0; j < tid; ++j) prefix += s.tsum[j];
-        const double target = s.residual_target;
-        if (prefix + sum > target) atomicMin(&s.owner, tid);
-        if (lastpos >= 0) atomicMax(&s.last_pos, lastpos);
-        __syncthreads();
-        if (s.owner == tid) {
-            double cdf = prefix;
-            int pick = -1;
-#pragma unroll
-            for (int e = 0; e < kAccEPT; ++e) {
-                cdf += pv[e];
-                if (pick < 0 && pv[e] > 0.0 && cdf > target) pick = i0 + e;
-            }
-            s.bonus = pick >= 0 ? pick : lastpos;
-        }
-        __syncthreads();
-        if (tid == 0) a.bonus[b] = (s.owner < kAccThreads && s.bonus >= 0) ? s.bonus : s.last_pos;
+        if (mine < 0) mine = lastpos;
+        const int got = (int)readlane_u32((uint32_t)mine, owner);
+        if (got >= 0) bonus = got;
     }
+    if (lane == 0) a.bonus[b] = bonus;
 }
 
 __global__ void validate_tree_kernel(const int32_t *parents, const int32_t *n_nodes, int B, int T, int32_t *bad) {
@@ -352,9 +464,9 @@ __global__ void validate_tree_kernel(const int32_t *parents, const int32_t *n_no
 using namespace radar;
 
 // Workspace layout: arrival counters (one 64-byte slot per row and per sequence), row results,
-// chunk partials.  Returns the total size; fills the pointers when `ws` is given.
-static size_t accept_layout(int B, int T, size_t nchunks, char *ws, AcceptArgs *a) {
-    const size_t rows = (size_t)B * T, slots = rows * nchunks;
+// per-wavefront partials.  Returns the total size; fills the pointers when `ws` is given.
+static size_t accept_layout(int B, int T, size_t nsub, char *ws, AcceptArgs *a) {
+    const size_t rows = (size_t)B * T, slots = rows * nsub;
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t o = off; off += (bytes + 255) & ~size_t(255); return o; };
     const size_t o_cnt = take((rows + B) * kAccCounterStride * sizeof(unsigned int));
@@ -374,8 +486,8 @@ static size_t accept_layout(int B, int T, size_t nchunks, char *ws, AcceptArgs *
 
 extern "C" size_t radar_verify_accept_workspace_bytes(const radar_accept_desc *d) {
     if (!d || d->B < 1 || d->T_max < 1 || d->V < 1) return 0;
-    const size_t nchunks = ((size_t)d->V + kAccChunk - 1) / kAccChunk;
-    return accept_layout(d->B, d->T_max, nchunks, nullptr, nullptr);
+    const size_t nsub = ((size_t)d->V + kAccSub - 1) / kAccSub;
+    return accept_layout(d->B, d->T_max, nsub, nullptr, nullptr);
 }
 
 extern "C" radar_status radar_verify_accept(const float *target_logits, const int32_t *draft_tokens,
@@ -388,8 +500,9 @@ extern "C" radar_status radar_verify_accept(const float *target_logits, const in
     if (d->B < 1 || d->T_max < 1 || d->V < 1 || d->D_max < 0) return RADAR_INVALID_ARG;
     if (d->mode != RADAR_ACCEPT_GREEDY && d->mode != RADAR_ACCEPT_SAMPLE) return RADAR_INVALID_ARG;
     if (d->mode == RADAR_ACCEPT_SAMPLE && (!(d->temperature > 0.0f) || !uniforms)) return RADAR_INVALID_ARG;
-    const int64_t nchunks = ((int64_t)d->V + kAccChunk - 1) / kAccChunk;
-    if (d->T_max > RADAR_T_MAX || d->D_max >= RADAR_T_MAX || d->B > 65535 || nchunks > kAccMaxChunks)
+    const int64_t nsub = ((int64_t)d->V + kAccSub - 1) / kAccSub;
+    const int64_t nwg = (nsub + kAccWaves - 1) / kAccWaves;
+    if (d->T_max > RADAR_T_MAX || d->D_max >= RADAR_T_MAX || d->B > 65535 || nsub > kAccMaxSubs)
         return RADAR_UNSUPPORTED_SHAPE;
     if (workspace_bytes < radar_verify_accept_workspace_bytes(d)) return RADAR_WORKSPACE_TOO_SMALL;
     if (((uintptr_t)workspace & 255) != 0) return RADAR_INVALID_ARG;
@@ -397,12 +510,14 @@ extern "C" radar_status radar_verify_accept(const float *target_logits, const in
     AcceptArgs a;
     a.logits = target_logits; a.tokens = draft_tokens; a.parents = parents; a.n_nodes = n_nodes; a.uniforms = uniforms;
     a.accept_len = accept_len; a.accept_path = accept_path; a.bonus = bonus_token;
-    a.B = d->B; a.T = d->T_max; a.V = d->V; a.D_max = d->D_max; a.mode = d->mode; a.nchunks = (int)nchunks;
+    a.B = d->B; a.T = d->T_max; a.V = d->V; a.D_max = d->D_max; a.mode = d->mode;
+    a.nsub = (int)nsub; a.nwg = (int)nwg;
     a.inv_temp = d->mode == RADAR_ACCEPT_SAMPLE ? 1.0 / (double)d->temperature : 1.0;
     a.inv_temp_f = (float)a.inv_temp;
-    accept_layout(d->B, d->T_max, (size_t)nchunks, static_cast<char *>(workspace), &a);
+    a.exact_scale = ((double)a.inv_temp_f == a.inv_temp) ? 1 : 0;
+    accept_layout(d->B, d->T_max, (size_t)nsub, static_cast<char *>(workspace), &a);
 
-    const dim3 grid((unsigned)nchunks, (unsigned)d->T_max, (unsigned)d->B), block(kAccThreads);
+    const dim3 grid((unsigned)nwg, (unsigned)d->T_max, (unsigned)d->B), block(kAccThreads);
     const bool vec4 = (d->V % 4 == 0) && (((uintptr_t)target_logits & 15) == 0);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const hipError_t e = vec4 ? launch("accept", accept_kernel<true>, grid, block, 0, st, a)
