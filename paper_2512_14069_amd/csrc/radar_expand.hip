@@ -305,20 +305,21 @@ struct RerankSmem {
     int32_t parent[RADAR_T_MAX];
 };
 
+template <int EPT>                       // pool entries per lane: 4 (pools up to 1024) or 16
 __global__ __launch_bounds__(kTopkThreads) void rerank_kernel(RerankArgs a) {
     __shared__ RerankSmem s;
     const int tid = threadIdx.x;
     const int keep = min(a.N, a.pool_count);
 
-    uint64_t keys[kTopkMaxEPT];
+    uint64_t keys[EPT];
 #pragma unroll
-    for (int e = 0; e < kTopkMaxEPT; ++e) {
+    for (int e = 0; e < EPT; ++e) {
         const int i = tid + e * kTopkThreads;
         const float sc = a.pool_scores[max(0, min(i, a.pool_count - 1))];
         keys[e] = (i < a.pool_count) ? make_key(sc, uint32_t(i)) : 0;
-        if (i < RADAR_POOL_MAX) s.node_of[i] = -1;
     }
-    if (keep > 0) block_topk<kTopkMaxEPT>(keys, keep, s.topk);
+    for (int i = tid; i < a.pool_count; i += kTopkThreads) s.node_of[i] = -1;
+    if (keep > 0) block_topk<EPT>(keys, keep, s.topk);
     else __syncthreads();
 
     int my_pool = -1;
@@ -458,6 +459,8 @@ extern "C" radar_status radar_draft_rerank(const int32_t *pool_tokens, const flo
     a.pool_count = pool_count; a.N = N; a.root_token = root_token;
     a.tree_tokens = tree_tokens; a.tree_parents = tree_parents; a.tree_scores = tree_scores;
     a.tree_depth = tree_depth; a.tree_pool_idx = tree_pool_idx; a.n_nodes_out = n_nodes_out;
-    const hipError_t e = launch("rerank", rerank_kernel, dim3(1), dim3(kTopkThreads), 0, static_cast<hipStream_t>(stream), a);
+    const hipError_t e = pool_count <= 4 * kTopkThreads
+        ? launch("rerank", rerank_kernel<4>, dim3(1), dim3(kTopkThreads), 0, static_cast<hipStream_t>(stream), a)
+        : launch("rerank", rerank_kernel<16>, dim3(1), dim3(kTopkThreads), 0, static_cast<hipStream_t>(stream), a);
     return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
 }

@@ -1,20 +1,14 @@
-// Workgroup-wide selection of the K largest 64-bit keys held in registers.
+// Selection of the K largest 64-bit keys held in registers, by a workgroup (rerank) or by one
+// wavefront (draft expansion).
 //
-// Used by draft expansion (per-chunk top-k, per-row merge, frontier choice) and
-// by rerank.  A key is (monotone image of an fp32 value) << 32 | ~index, so the
-// larger key wins under "value descending, index ascending"; key 0 means
-// "no element".  256 threads, four 64-wide wavefronts.
+// A key is (monotone image of an fp32 value) << 32 | ~index, so the larger key wins under
+// "value descending, index ascending"; key 0 means "no element".
 //
-// Method (loop-free except for the final count).  The lanes are cut into G >= K
-// groups (16-lane DPP rows for K <= 16, quads for K <= 64) and each group's
-// largest value is found with DPP steps.  tau = the smallest group maximum is a
-// valid threshold: at least G >= K elements are >= tau.  On non-degenerate data
-// only a few dozen elements pass it; they are compacted into LDS (ballot +
-// prefix count, one LDS fetch-add per wavefront) and ranked exactly, one
-// survivor per lane, by counting larger keys with broadcast LDS reads.  Every
-// step is exact; the threshold only limits how much is ranked.  Data with huge
-// runs of equal values makes everything survive and is ranked by the same code
-// in a slower loop.
+// Method: find a threshold tau that at least K elements reach, cheaply and without looking at
+// every element pair; compact the elements >= tau into LDS (ballot + prefix count); rank those
+// survivors exactly by counting larger keys with broadcast LDS reads.  Every step is exact; the
+// threshold only limits how much is ranked.  Data with huge runs of equal values makes
+// everything survive and is ranked by the same code in a slower loop.
 #pragma once
 
 #include "radar_device.h"
@@ -27,51 +21,49 @@ constexpr int kTopkMaxK = 64;
 constexpr int kTopkMaxEPT = 16;
 
 struct TopkSmem {
-    uint64_t surv[kTopkThreads * kTopkMaxEPT + 2];    // compacted survivors (+2: vector reads past the end)
+    uint64_t surv[kTopkThreads * kTopkMaxEPT + 8];    // compacted survivors (+8: grouped reads past the end)
     uint64_t top[kTopkMaxK];                          // result, best first; 0 where fewer than K exist
-    uint32_t gmax[64];                                // group maxima
+    uint32_t lmax[kTopkThreads];                      // largest value of each lane
+    uint32_t tau;
     int count;                                        // number of survivors
 };
 
-// keys[e] == 0 marks an absent element.  All 256 threads must call this
-// (it synchronises the workgroup).  On return s.top[0..K) is valid for every
-// thread.  1 <= K <= kTopkMaxK, EPT <= kTopkMaxEPT.
+// Workgroup version, 256 lanes, 1 <= K <= 64, EPT <= 16 keys per lane.  tau = the K-th largest
+// of the 256 lane maxima (each lane ranks its maximum against all of them).  keys[e] == 0 marks
+// an absent element.  All 256 threads must call this (it synchronises the workgroup).  On
+// return s.top[0..K) is valid for every thread.
 template <int EPT>
 __device__ __forceinline__ void block_topk(const uint64_t (&keys)[EPT], int K, TopkSmem &s) {
-    const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
+    const int tid = threadIdx.x, lane = lane_id();
 
     uint32_t tmax = 0;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) tmax = max(tmax, uint32_t(keys[e] >> 32));
-
-    // ---- group maxima: quads always; 16-lane rows when 16 groups are enough
-    uint32_t g = tmax;
-    g = max(g, dpp_u32<0xB1>(g));
-    g = max(g, dpp_u32<0x4E>(g));
-    const bool rows = (K <= 16);
-    if (rows) {
-        g = max(g, dpp_u32<0x141>(g));
-        g = max(g, dpp_u32<0x140>(g));
-        if ((lane & 15) == 0) s.gmax[w * 4 + (lane >> 4)] = g;
-    } else {
-        if ((lane & 3) == 0) s.gmax[w * 16 + (lane >> 2)] = g;
-    }
-    if (tid == 0) s.count = 0;
+    s.lmax[tid] = tmax;
+    if (tid == 0) { s.count = 0; s.tau = 0xffffffffu; }
     if (tid < kTopkMaxK) s.top[tid] = 0;
     __syncthreads();
 
-    // ---- tau = smallest group maximum (an empty group makes it 0: everything present survives)
-    uint32_t tau;
+    // ---- tau: smallest lane maximum that fewer than K lane maxima exceed
     {
-        const int ng = rows ? 16 : 64;
-        uint32_t v = s.gmax[lane & (ng - 1)];
-        v = min(v, dpp_u32<0xB1>(v));
-        v = min(v, dpp_u32<0x4E>(v));
-        v = min(v, dpp_u32<0x141>(v));
-        v = min(v, dpp_u32<0x140>(v));           // minimum over each 16-lane row = over 16 groups
-        if (!rows) v = min(min(readlane_u32(v, 0), readlane_u32(v, 16)), min(readlane_u32(v, 32), readlane_u32(v, 48)));
-        tau = max(readlane_u32(v, 0), 1u);       // >= 1 so that absent keys (0) never pass
+        int larger = 0;
+        for (int j = 0; j < kTopkThreads; j += 16) {              // broadcast reads, 16 values in flight
+            uint32_t v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) v[u] = s.lmax[j + u];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) larger += (v[u] > tmax) ? 1 : 0;
+        }
+        uint32_t c = larger < K ? tmax : 0xffffffffu;
+        c = min(c, dpp_u32<0xB1>(c));
+        c = min(c, dpp_u32<0x4E>(c));
+        c = min(c, dpp_u32<0x141>(c));
+        c = min(c, dpp_u32<0x140>(c));
+        const uint32_t wmin = min(min(readlane_u32(c, 0), readlane_u32(c, 16)), min(readlane_u32(c, 32), readlane_u32(c, 48)));
+        if (lane == 0) atomicMin(&s.tau, wmin);
     }
+    __syncthreads();
+    const uint32_t tau = max(s.tau, 1u);                          // >= 1 so that absent keys (0) never pass
 
     // ---- compaction: count, reserve a range per wavefront, write
     int cnt = 0;
@@ -90,18 +82,21 @@ __device__ __forceinline__ void block_topk(const uint64_t (&keys)[EPT], int K, T
         }
     }
     __syncthreads();
+    const int n = s.count;
+    if (tid < 8) s.surv[n + tid] = 0;                             // padding for the grouped reads
+    __syncthreads();
 
     // ---- exact ranks among the n survivors; all lanes read the same LDS words (broadcast)
-    const int n = s.count;
     for (int i = tid; i < n; i += kTopkThreads) {
         const uint64_t key = s.surv[i];
         int rank = 0;
-        int j = 0;
-        for (; j + 4 <= n; j += 4) {
-            const uint64_t k0 = s.surv[j], k1 = s.surv[j + 1], k2 = s.surv[j + 2], k3 = s.surv[j + 3];
-            rank += (k0 > key) + (k1 > key) + (k2 > key) + (k3 > key);
+        for (int j = 0; j < n; j += 8) {
+            uint64_t kj[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) kj[u] = s.surv[j + u];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) rank += (kj[u] > key) ? 1 : 0;
         }
-        for (; j < n; ++j) rank += (s.surv[j] > key) ? 1 : 0;
         if (rank < K) s.top[rank] = key;
     }
     __syncthreads();
