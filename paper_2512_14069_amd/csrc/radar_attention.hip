@@ -56,7 +56,7 @@ struct AttnArgs {
     const int32_t *parents, *ctx_lens, *n_nodes;
     __bf16 *out;
     float *lse;
-    int B, T, Hq, Hkv, G, S, kps, max_splits, n_qblk;
+    int B, T, Hq, Hkv, G, S, kps, max_splits, n_ublk, nqb;   // nqb 32-row blocks per head, n_ublk workgroups per KV range
     int64_t q_sb, q_st, q_sh, kv_sb, kv_sh, kv_ss, o_sb, o_st, o_sh;
     float scale_log2;                      // softmax scale * log2(e), > 0
     unsigned int *counters;                // key-split: [(b*Hq + h) * kAttnCounterStride]
@@ -495,24 +495,97 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_ks_kernel(AttnArgs a) 
 }
 
 // ===================================================================== group-share kernel
-template <int D, int NQB>
-__global__ __launch_bounds__(kAttnThreads) void tree_attn_gs_kernel(AttnArgs a) {
-    constexpr int CH = D / 8;               // 16-byte chunks per cache row
-    constexpr int DB = D / 32;              // 32-row blocks of O^T
-    constexpr int KLOADS = kKT * CH / kAttnThreads;     // 16-byte K loads per lane per tile
-    constexpr int VITEMS = CH * (kKT / 4);                // (chunk, 4-key group) work items per tile
-    constexpr int VPASSES = (VITEMS + kAttnThreads - 1) / kAttnThreads;
-    static_assert(KLOADS >= 1 && kKT * CH % kAttnThreads == 0, "tile too small for 256 lanes");
+// 512 lanes: eight wavefronts, two per SIMD, so that one wavefront's MFMAs run underneath the
+// other's softmax arithmetic.  A wavefront is one (query head, block of 32 tree rows); the eight of
+// a workgroup share every K/V tile through LDS.
+constexpr int kGsThreads = 512;
+constexpr int kGsWaves = kGsThreads / kWave;
 
+// Stages 32 query rows (row0 .. row0+31 of head h) into LDS, swizzled like a K tile; rows >= T and
+// inactive wavefronts give zeros.  One wavefront, lane t.
+template <int D>
+__device__ __forceinline__ void stage_q32(const AttnArgs &a, int b, int h, bool active, int row0, unsigned char *Qs, int t) {
+    constexpr int CH = D / 8, N = 32 * CH / kWave;
+    const __bf16 *qbase = a.q + (size_t)b * a.q_sb + (size_t)h * a.q_sh;
+    u32x4 raw[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {                               // all loads first: one round trip
+        const int c = i * kWave + t, row = row0 + c / CH, ch = c % CH;
+        raw[i] = *reinterpret_cast<const u32x4 *>(qbase + (uint32_t)(min(row, a.T - 1) * (int)a.q_st + ch * 8));
+        and_mask(raw[i], active && row < a.T);
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const int c = i * kWave + t;
+        *reinterpret_cast<u32x4 *>(Qs + ks_off<D>(c / CH, c % CH)) = raw[i];
+    }
+}
+
+// Staging of one 64-row K/V tile by the 512 lanes of the workgroup, four 16-byte loads per lane and
+// no request made twice: lanes 0..255 fetch K (row-major chunks), lanes 256..511 fetch V, one
+// (chunk, four-key group) item each, which they transpose on the way into LDS.  Branch-free loads:
+// rows past the range re-read the last valid row; V is zeroed afterwards (0 * anything must stay
+// 0), K is masked by the softmax.
+template <int D>
+struct GsTileRegs {
+    static constexpr int CH = D / 8;
+    static constexpr int KL = kKT * CH / 256;                              // K loads per K lane (4 at D = 128)
+    static constexpr int VITEMS = CH * (kKT / 4);                          // 256 at D = 128
+    u32x4 r[4];
+};
+
+template <int D>
+__device__ __forceinline__ void gs_load_tile(GsTileRegs<D> &g, const __bf16 *kbase, const __bf16 *vbase, int kv_ss,
+                                             int t0, int kend, int tid) {
+    constexpr int CH = GsTileRegs<D>::CH;
+    if (tid < 256) {                                                       // wave-uniform
+#pragma unroll
+        for (int i = 0; i < GsTileRegs<D>::KL; ++i) {
+            const int c = i * 256 + tid;
+            const int kpos = min(t0 + c / CH, kend - 1);
+            g.r[i] = *reinterpret_cast<const u32x4 *>(kbase + (uint32_t)(kpos * kv_ss + (c % CH) * 8));
+        }
+    } else {
+        const int item = min(tid - 256, GsTileRegs<D>::VITEMS - 1);
+        const int ch = item % CH, kg = item / CH;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int kpos = t0 + kg * 4 + i;
+            u32x4 v = *reinterpret_cast<const u32x4 *>(vbase + (uint32_t)(min(kpos, kend - 1) * kv_ss + ch * 8));
+            and_mask(v, kpos < kend);
+            g.r[i] = v;
+        }
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void gs_store_tile(const GsTileRegs<D> &g, unsigned char *Ks, unsigned char *Vt, int tid) {
+    constexpr int CH = GsTileRegs<D>::CH;
+    if (tid < 256) {
+#pragma unroll
+        for (int i = 0; i < GsTileRegs<D>::KL; ++i) {
+            const int c = i * 256 + tid;
+            *reinterpret_cast<u32x4 *>(Ks + ks_off<D>(c / CH, c % CH)) = g.r[i];
+        }
+    } else if (tid - 256 < GsTileRegs<D>::VITEMS) {
+        const int item = tid - 256;
+        store_vt4(Vt, item % CH, item / CH, g.r);
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
+    constexpr int DB = D / 32;              // 32-row blocks of O^T
+    constexpr int QBYTES = 32 * D * 2;      // one wavefront's query block
+
+    constexpr int TILE = 2 * kKT * D * 2;   // one K tile ([64][D] bf16, swizzled) + one V^T tile ([D][64], swizzled)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char *Ks = smem;                                  // [64][D] bf16, swizzled
-    unsigned char *Vt = smem + kKT * D * 2;                    // [D][64] bf16, transposed + swizzled
-    unsigned char *Qs = smem + 2 * kKT * D * 2 + threadIdx.x / kWave * (64 * D * 2);   // this wavefront's head
-    int *s_par = reinterpret_cast<int *>(smem + (2 + kAttnWaves) * kKT * D * 2);
+    unsigned char *Qs = smem + 2 * TILE + threadIdx.x / kWave * QBYTES;          // this wavefront's query block
+    int *s_par = reinterpret_cast<int *>(smem + 2 * TILE + kGsWaves * QBYTES);
 
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int sp = blockIdx.x;
-    const int hk = blockIdx.y / a.n_qblk, qblk = blockIdx.y % a.n_qblk;
+    const int hk = blockIdx.y / a.n_ublk, ublk = blockIdx.y % a.n_ublk;
     const int b = blockIdx.z;
     const int L = a.ctx_lens[b];
     int nn = a.n_nodes ? a.n_nodes[b] : a.T;
@@ -523,82 +596,78 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_gs_kernel(AttnArgs a) 
     const int kend = min(total, kbeg + a.kps);
     const int nsplit = (total + a.kps - 1) / a.kps;
 
-    const int g = qblk * kAttnWaves + w;                  // query head within the group
+    const int u = ublk * kGsWaves + w;                    // (head within the group, block of 32 rows)
+    const int g = u / a.nqb, qb = u % a.nqb;
     const bool active = g < a.G;
     const int h = hk * a.G + (active ? g : 0);
     const int j32 = lane & 31, g2 = lane >> 5;
+    const int i = 32 * qb + j32;                          // this lane's tree row
 
     const __bf16 *kbase = a.k + (size_t)b * a.kv_sb + (size_t)hk * a.kv_sh;
     const __bf16 *vbase = a.v + (size_t)b * a.kv_sb + (size_t)hk * a.kv_sh;
     const int kv_ss = (int)a.kv_ss;          // 32-bit offsets inside one head's cache (checked on the host)
 
-    TileRegs<D, kAttnThreads> regs;                       // staging by the whole workgroup
-    load_tile<D, kAttnThreads>(regs, kbase, vbase, kv_ss, kbeg, kend, tid);
-    stage_q<D, kWave>(a, b, h, active, Qs, lane);
+    const int ntiles = (kend - kbeg + kKT - 1) / kKT;
+    GsTileRegs<D> regs;                                   // staging by the whole workgroup
+    gs_load_tile<D>(regs, kbase, vbase, kv_ss, kbeg, kend, tid);
+    stage_q32<D>(a, b, h, active, 32 * qb, Qs, lane);
     if (tid < RADAR_T_MAX) s_par[tid] = a.parents[(size_t)b * a.T + min(tid, nn - 1)];
+    gs_store_tile<D>(regs, smem, smem + TILE / 2, tid);
     __syncthreads();
-    uint64_t anc[NQB];
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-        const int i = 32 * qb + j32;
-        anc[qb] = (kend > L && i < nn) ? ancestor_word(s_par, i) : 0ull;
-    }
+    if (ntiles > 1) gs_load_tile<D>(regs, kbase, vbase, kv_ss, kbeg + kKT, kend, tid);
+    uint64_t anc[1];
+    anc[0] = (kend > L && i < nn) ? ancestor_word(s_par, i) : 0ull;
 
-    floatx16 oacc[DB][NQB];
+    floatx16 oacc[DB][1];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[db][qb][r] = 0.f;
-    float m_run[NQB], l_run[NQB];
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) { m_run[qb] = kNegBig; l_run[qb] = 0.f; }
+        for (int r = 0; r < 16; ++r) oacc[db][0][r] = 0.f;
+    float m_run[1] = {kNegBig}, l_run[1] = {0.f};
 
-    const int ntiles = (kend - kbeg + kKT - 1) / kKT;
+    // Two tile buffers: while tile t is consumed from one, every wavefront drops its share of tile
+    // t+1 (in registers since the previous iteration) into the other as soon as it is done with t.
+    // One barrier per tile: it publishes tile t+1 and tells that nobody reads tile t any more.
     for (int t = 0; t < ntiles; ++t) {
-        const int t0 = kbeg + t * kKT;
-        __syncthreads();                      // previous tile fully consumed
-        store_tile<D, kAttnThreads>(regs, Ks, Vt, tid);
-        __syncthreads();
-        if (t + 1 < ntiles) load_tile<D, kAttnThreads>(regs, kbase, vbase, kv_ss, t0 + kKT, kend, tid);   // in flight while this tile is computed
-        if (active) wave_tile<D, NQB>(Ks, Vt, Qs, oacc, m_run, l_run, anc, t0, L, kend, t == 0, a.scale_log2);
+        unsigned char *cur = smem + (t & 1) * TILE, *nxt = smem + ((t + 1) & 1) * TILE;
+        if (active) wave_tile<D, 1>(cur, cur + TILE / 2, Qs, oacc, m_run, l_run, anc, kbeg + t * kKT, L, kend, t == 0, a.scale_log2);
+        if (t + 1 < ntiles) {
+            gs_store_tile<D>(regs, nxt, nxt + TILE / 2, tid);
+            __syncthreads();
+            if (t + 2 < ntiles) gs_load_tile<D>(regs, kbase, vbase, kv_ss, kbeg + (t + 2) * kKT, kend, tid);
+        }
     }
     if (!active) return;
 
-    // ---- epilogue: a lane owns query i = 32*qb + j32; its registers hold d = 32*db + 8*(r/4) + 4*g2 + r%4
+    // ---- epilogue: a lane owns query i; its registers hold d = 32*db + 8*(r/4) + 4*g2 + r%4
+    const float l_tot = l_run[0] + __shfl_xor(l_run[0], 32);
+    if (nsplit == 1) {
+        if (i >= a.T) return;
+        __bf16 *orow = a.out + (size_t)b * a.o_sb + (size_t)i * a.o_st + (size_t)h * a.o_sh;
+        const float inv = (i < nn && l_tot > 0.f) ? 1.0f / l_tot : 0.f;
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-        const int i = 32 * qb + j32;
-        const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32);
-        if (nsplit == 1) {
-            if (i >= a.T) continue;
-            __bf16 *orow = a.out + (size_t)b * a.o_sb + (size_t)i * a.o_st + (size_t)h * a.o_sh;
-            const float inv = (i < nn && l_tot > 0.f) ? 1.0f / l_tot : 0.f;
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+            for (int r4 = 0; r4 < 4; ++r4) {
+                bf16x4 o4;
 #pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    bf16x4 o4;
+                for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(i < nn ? oacc[db][0][4 * r4 + e] * inv : 0.f);
+                *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * r4 + 4 * g2) = o4;
+            }
+        if (a.lse && g2 == 0)
+            a.lse[((size_t)b * a.T + i) * a.Hq + h] = (i < nn) ? (m_run[0] + __builtin_amdgcn_logf(l_tot)) * kLn2 : 0.f;
+    } else {
+        const size_t unit = ((size_t)b * a.Hq + h) * a.max_splits + sp;
+        float *po = a.part_o + unit * (size_t)(D * 64);
+        float *pml = a.part_ml + unit * 128;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(i < nn ? oacc[db][qb][4 * r4 + e] * inv : 0.f);
-                    *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * r4 + 4 * g2) = o4;
-                }
-            if (a.lse && g2 == 0)
-                a.lse[((size_t)b * a.T + i) * a.Hq + h] = (i < nn) ? (m_run[qb] + __builtin_amdgcn_logf(l_tot)) * kLn2 : 0.f;
-        } else {
-            const size_t unit = ((size_t)b * a.Hq + h) * a.max_splits + sp;
-            float *po = a.part_o + unit * (size_t)(D * 64);
-            float *pml = a.part_ml + unit * 128;
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int d = 32 * db + 8 * (r >> 2) + 4 * g2 + (r & 3);
-                    po[d * 64 + i] = oacc[db][qb][r];
-                }
-            if (g2 == 0) { pml[i] = m_run[qb]; pml[64 + i] = l_tot; }
-        }
+            for (int r = 0; r < 16; ++r) {
+                const int d = 32 * db + 8 * (r >> 2) + 4 * g2 + (r & 3);
+                po[d * 64 + i] = oacc[db][0][r];
+            }
+        if (g2 == 0) { pml[i] = m_run[0]; pml[64 + i] = l_tot; }
     }
 }
 
@@ -672,14 +741,15 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_merge_kernel(AttnArgs 
 // ------------------------------------------------------------------ host-side planning
 struct AttnPlan {
     bool key_split;
-    int kps, max_splits, n_qblk;
+    int kps, max_splits, n_ublk, nqb;
     size_t off_counters, off_part_o, off_part_ml, bytes;
 };
 
 static AttnPlan plan_attention(const radar_attn_desc *d) {
     AttnPlan p;
     const int G = d->Hq / d->Hkv;
-    p.n_qblk = (G + kAttnWaves - 1) / kAttnWaves;
+    p.nqb = d->T_max <= 32 ? 1 : 2;
+    p.n_ublk = (G * p.nqb + kGsWaves - 1) / kGsWaves;
     p.key_split = d->variant == RADAR_ATTN_KEY_SPLIT;      // never chosen automatically: measured slower at every shape tried
     long kps = d->keys_per_split;
     if (kps <= 0) {
@@ -691,13 +761,21 @@ static AttnPlan plan_attention(const radar_attn_desc *d) {
             kps = ((long)d->S_max + ns - 1) / ns;
             kps = (kps + 4 * kKT - 1) / (4 * kKT) * (4 * kKT);
         } else {
-            const long units = (long)d->B * d->Hkv * p.n_qblk;
-            long ns = (512 + units - 1) / units;
-            if (ns < 1) ns = 1;
-            kps = ((long)d->S_max + ns - 1) / ns;
-            kps = (kps + kKT - 1) / kKT * kKT;
-            if (kps < 128) kps = 128;
-            if (kps > 2048) kps = 2048;
+            // Number of key ranges: the one that minimises a small cost model, in units of one tile of
+            // one workgroup (measured ~2.7 us): rounds of 256 resident workgroups x (tiles per range +
+            // 3 for prologue and epilogue), plus what the merge of the ranges costs.  Counting whole
+            // rounds matters: 576 workgroups take as long as 768.
+            const long units = (long)d->B * d->Hkv * p.n_ublk;
+            const long tiles_all = ((long)d->S_max + kKT - 1) / kKT;
+            double best = 1e30;
+            long best_ns = 1;
+            for (long ns = 1; ns <= 64 && ns <= tiles_all; ++ns) {
+                const long tiles = (tiles_all + ns - 1) / ns;
+                const long rounds = (units * ns + 255) / 256;
+                const double cost = (double)rounds * (double)(tiles + 3) + (ns > 1 ? 1.6 + 0.14 * (double)ns : 0.0);
+                if (cost < best) { best = cost; best_ns = ns; }
+            }
+            kps = (tiles_all + best_ns - 1) / best_ns * kKT;
         }
     }
     p.kps = (int)kps;
@@ -735,18 +813,18 @@ extern "C" size_t radar_tree_attention_workspace_bytes(const radar_attn_desc *d)
 }
 
 template <int D>
-constexpr int gs_smem_bytes() { return (2 + kAttnWaves) * kKT * D * 2 + RADAR_T_MAX * 4; }
+constexpr int gs_smem_bytes() { return 2 * (2 * kKT * D * 2) + kGsWaves * 32 * D * 2 + RADAR_T_MAX * 4; }
 
-template <int D, int NQB>
+template <int D>
 static hipError_t launch_gs(const AttnArgs &a, dim3 grid, hipStream_t s) {
     static bool configured = false;                        // raise the dynamic LDS limit once per instantiation
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_gs_kernel<D, NQB>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_gs_kernel<D>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, gs_smem_bytes<D>());
         if (e != hipSuccess) return e;
         configured = true;
     }
-    return launch("tree_attn_group_share", tree_attn_gs_kernel<D, NQB>, grid, dim3(kAttnThreads), gs_smem_bytes<D>(), s, a);
+    return launch("tree_attn_group_share", tree_attn_gs_kernel<D>, grid, dim3(kGsThreads), gs_smem_bytes<D>(), s, a);
 }
 
 template <int D, int NQB>
@@ -778,7 +856,7 @@ extern "C" radar_status radar_tree_attention(const void *q, const void *k_cache,
     a.parents = parents; a.ctx_lens = ctx_lens; a.n_nodes = n_nodes;
     a.out = static_cast<__bf16 *>(out); a.lse = lse_out;
     a.B = d->B; a.T = d->T_max; a.Hq = d->Hq; a.Hkv = d->Hkv; a.G = d->Hq / d->Hkv; a.S = d->S_max;
-    a.kps = p.kps; a.max_splits = p.max_splits; a.n_qblk = p.n_qblk;
+    a.kps = p.kps; a.max_splits = p.max_splits; a.n_ublk = p.n_ublk; a.nqb = p.nqb;
     const int64_t D = d->D;
     a.q_sh = d->q_stride_h ? d->q_stride_h : D;
     a.q_st = d->q_stride_t ? d->q_stride_t : D * d->Hq;
@@ -814,12 +892,11 @@ extern "C" radar_status radar_tree_attention(const void *q, const void *k_cache,
         else             e = narrow ? launch_ks<64, 1>(a, grid, s) : launch_ks<64, 2>(a, grid, s);
         return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
     }
-    if ((long)a.Hkv * a.n_qblk > 65535) return RADAR_UNSUPPORTED_SHAPE;
-    const dim3 grid((unsigned)a.max_splits, (unsigned)(a.Hkv * a.n_qblk), (unsigned)a.B);
+    if ((long)a.Hkv * a.n_ublk > 65535) return RADAR_UNSUPPORTED_SHAPE;
+    const dim3 grid((unsigned)a.max_splits, (unsigned)(a.Hkv * a.n_ublk), (unsigned)a.B);
     {
         hipError_t e;
-        if (d->D == 128) e = narrow ? launch_gs<128, 1>(a, grid, s) : launch_gs<128, 2>(a, grid, s);
-        else             e = narrow ? launch_gs<64, 1>(a, grid, s) : launch_gs<64, 2>(a, grid, s);
+        e = d->D == 128 ? launch_gs<128>(a, grid, s) : launch_gs<64>(a, grid, s);
         if (e != hipSuccess) return RADAR_HIP_ERROR;
     }
     if (a.max_splits > 1) {
