@@ -671,11 +671,14 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
     }
 }
 
-// Merges the group-share kernel's per-split partials of one (sequence, query head): 64 query
-// rows x D.  Splits are taken four at a time so that a batch's loads are in flight together.
+// Merges the group-share kernel's per-split partials.  A workgroup takes one (sequence, query
+// head, 32-wide slice of the head dimension): lane = (tree row i, 8 consecutive d), so that the
+// reads of a d-row of the [D][64] partial are 256 contiguous bytes.  Splits are taken four at a
+// time so that a batch's loads are in flight together.
 template <int D>
 __global__ __launch_bounds__(kAttnThreads) void tree_attn_merge_kernel(AttnArgs a) {
-    const int h = blockIdx.x, b = blockIdx.y;
+    constexpr int SL = 32, DQ = 8;                          // slice width, floats per lane
+    const int slice = blockIdx.x % (D / SL), h = blockIdx.x / (D / SL), b = blockIdx.y;
     const int L = a.ctx_lens[b];
     int nn = a.n_nodes ? a.n_nodes[b] : a.T;
     nn = max(1, min(nn, a.T));
@@ -683,20 +686,18 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_merge_kernel(AttnArgs 
     const int nsplit = (total + a.kps - 1) / a.kps;
     if (L < 0 || nsplit <= 1) return;                       // the split kernel wrote the result itself
 
-    const int i = threadIdx.x & 63, part = threadIdx.x >> 6; // query row, quarter of the head dim
+    const int i = threadIdx.x & 63, part = threadIdx.x >> 6; // query row, which 8 of the slice's 32
     if (i >= a.T) return;
+    const int d0 = slice * SL + part * DQ;
     const size_t unit0 = ((size_t)b * a.Hq + h) * a.max_splits;
-    __bf16 *orow = a.out + (size_t)b * a.o_sb + (size_t)i * a.o_st + (size_t)h * a.o_sh;
-    constexpr int DQ = D / 4;
+    __bf16 *orow = a.out + (size_t)b * a.o_sb + (size_t)i * a.o_st + (size_t)h * a.o_sh + d0;
+    const bool lse_lane = a.lse && slice == 0 && part == 0;
     if (i >= nn) {
+        bf16x8 z;
 #pragma unroll
-        for (int c = 0; c < DQ / 8; ++c) {
-            bf16x8 z;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) z[e] = (__bf16)0.f;
-            *reinterpret_cast<bf16x8 *>(orow + part * DQ + 8 * c) = z;
-        }
-        if (a.lse && part == 0) a.lse[((size_t)b * a.T + i) * a.Hq + h] = 0.f;
+        for (int e = 0; e < 8; ++e) z[e] = (__bf16)0.f;
+        *reinterpret_cast<bf16x8 *>(orow) = z;
+        if (lse_lane) a.lse[((size_t)b * a.T + i) * a.Hq + h] = 0.f;
         return;
     }
     float M = kNegBig, lsum = 0.f;
@@ -712,7 +713,7 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_merge_kernel(AttnArgs 
             ls[j] = a.part_ml[(unit0 + sc) * 128 + 64 + i];
             const float *po = a.part_o + (unit0 + sc) * (size_t)(D * 64);
 #pragma unroll
-            for (int d = 0; d < DQ; ++d) ov[j][d] = po[(part * DQ + d) * 64 + i];
+            for (int d = 0; d < DQ; ++d) ov[j][d] = po[(d0 + d) * 64 + i];
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -728,14 +729,11 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_merge_kernel(AttnArgs 
         }
     }
     const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
+    bf16x8 o8;
 #pragma unroll
-    for (int c = 0; c < DQ / 8; ++c) {
-        bf16x8 o8;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o8[e] = (__bf16)(acc[8 * c + e] * inv);
-        *reinterpret_cast<bf16x8 *>(orow + part * DQ + 8 * c) = o8;
-    }
-    if (a.lse && part == 0) a.lse[((size_t)b * a.T + i) * a.Hq + h] = (M + __builtin_amdgcn_logf(lsum)) * kLn2;
+    for (int e = 0; e < 8; ++e) o8[e] = (__bf16)(acc[e] * inv);
+    *reinterpret_cast<bf16x8 *>(orow) = o8;
+    if (lse_lane) a.lse[((size_t)b * a.T + i) * a.Hq + h] = (M + __builtin_amdgcn_logf(lsum)) * kLn2;
 }
 
 // ------------------------------------------------------------------ host-side planning
@@ -900,7 +898,7 @@ extern "C" radar_status radar_tree_attention(const void *q, const void *k_cache,
         if (e != hipSuccess) return RADAR_HIP_ERROR;
     }
     if (a.max_splits > 1) {
-        const dim3 mgrid((unsigned)a.Hq, (unsigned)a.B);
+        const dim3 mgrid((unsigned)(a.Hq * (d->D / 32)), (unsigned)a.B);
         const hipError_t e = d->D == 128 ? launch("tree_attn_merge", tree_attn_merge_kernel<128>, mgrid, block, 0, s, a)
                                          : launch("tree_attn_merge", tree_attn_merge_kernel<64>, mgrid, block, 0, s, a);
         if (e != hipSuccess) return RADAR_HIP_ERROR;
