@@ -42,6 +42,8 @@ def parse():
     ap.add_argument("--attn-variant", type=int, default=0, help="0 auto, 1 key-split, 2 group-share")
     ap.add_argument("--only", default="", help="time only 'attention', 'expand' or 'accept' (for profiling)")
     ap.add_argument("--no-marks", action="store_true", help="no stream events between the phases of a step")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run five 64 MiB device copies (a kernel of known traffic, for scaling hardware counters)")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not attach timing events to the launches")
     return ap.parse_args()
 
@@ -203,6 +205,12 @@ def main():
             step(W + i)
         torch.cuda.synchronize()
         kern = b.radar_profile_end()
+    if args.calibrate_copy:
+        src = torch.empty(64 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     for m in null_marks:                       # cost of an empty pair of marks, taken off each phase
         m[0].record(); m[1].record()
     torch.cuda.synchronize()

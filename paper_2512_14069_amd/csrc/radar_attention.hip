@@ -665,9 +665,9 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int d = 32 * db + 8 * (r >> 2) + 4 * g2 + (r & 3);
-                po[d * 64 + i] = oacc[db][0][r];
-            }
-        if (g2 == 0) { pml[i] = m_run[0]; pml[64 + i] = l_tot; }
+                store_shared_result(&po[d * 64 + i], oacc[db][0][r]);     // written through: nothing is left
+            }                                                              // dirty in L2 for the end of the kernel
+        if (g2 == 0) { store_shared_result(&pml[i], m_run[0]); store_shared_result(&pml[64 + i], l_tot); }
     }
 }
 
@@ -761,8 +761,9 @@ static AttnPlan plan_attention(const radar_attn_desc *d) {
         } else {
             // Number of key ranges: the one that minimises a small cost model, in units of one tile of
             // one workgroup (measured ~2.7 us): rounds of 256 resident workgroups x (tiles per range +
-            // 3 for prologue and epilogue), plus what the merge of the ranges costs.  Counting whole
-            // rounds matters: 576 workgroups take as long as 768.
+            // 3 for prologue and epilogue), plus what the merge of the ranges costs (every range writes
+            // and re-reads T*Hq*D fp32 of partial output, which soon exceeds the KV bytes themselves).
+            // Counting whole rounds matters: 576 workgroups take as long as 768.
             const long units = (long)d->B * d->Hkv * p.n_ublk;
             const long tiles_all = ((long)d->S_max + kKT - 1) / kKT;
             double best = 1e30;
@@ -770,7 +771,7 @@ static AttnPlan plan_attention(const radar_attn_desc *d) {
             for (long ns = 1; ns <= 64 && ns <= tiles_all; ++ns) {
                 const long tiles = (tiles_all + ns - 1) / ns;
                 const long rounds = (units * ns + 255) / 256;
-                const double cost = (double)rounds * (double)(tiles + 3) + (ns > 1 ? 1.6 + 0.14 * (double)ns : 0.0);
+                const double cost = (double)rounds * (double)(tiles + 3) + (ns > 1 ? 1.6 + 0.3 * (double)ns : 0.0);
                 if (cost < best) { best = cost; best_ns = ns; }
             }
             kps = (tiles_all + best_ns - 1) / best_ns * kKT;
