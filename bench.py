@@ -39,7 +39,6 @@ def parse():
     ap.add_argument("--attn-sets", type=int, default=64, help="distinct KV caches cycled through (9.6 MB each)")
     ap.add_argument("--cycle-sets", type=int, default=8, help="distinct logits sets cycled through (72 MB each)")
     ap.add_argument("--attn-kps", type=int, default=0, help="keys_per_split override for the attention call (0 = library's choice)")
-    ap.add_argument("--attn-variant", type=int, default=0, help="0 auto, 1 key-split, 2 group-share")
     ap.add_argument("--only", default="", help="time only 'attention', 'expand' or 'accept' (for profiling)")
     ap.add_argument("--no-marks", action="store_true", help="no stream events between the phases of a step")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -98,7 +97,7 @@ def main():
         vc = torch.randn((A.B, A.Hkv, S, A.D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
         attn_sets.append((q, kc, vc))
     attn_out = torch.empty((A.B, A.T, A.Hq, A.D), dtype=torch.bfloat16, device=dev)
-    adesc = b.attn_desc(attn_sets[0][0], attn_sets[0][1], keys_per_split=args.attn_kps, variant=args.attn_variant)
+    adesc = b.attn_desc(attn_sets[0][0], attn_sets[0][1], keys_per_split=args.attn_kps)
     attn_ws = b.new_workspace(b.radar_tree_attention_workspace_bytes(adesc))
     kv_rows = A.ctx_lens[0] + A.n_nodes[0]
     attn_bytes = kv_rows * A.Hkv * A.D * 2 * 2 + 2 * A.n_nodes[0] * A.Hq * A.D * 2 + A.T * 4
@@ -229,7 +228,7 @@ def main():
     ea_gbps = ea_bytes / (ea_us * 1e-6) / 1e9 if ea_us > 0 else 0.0
 
     # roofline entries: algorithmic bytes of one launch / that kernel's mean device duration
-    alg_bytes = {"tree_attn_group_share": attn_bytes, "tree_attn_key_split": attn_bytes,
+    alg_bytes = {"tree_attn_group_share": attn_bytes,
                  "expand": expand_bytes, "accept": accept_bytes}
     kernels = []
     for name, t in sorted(kern.items(), key=lambda kv: -kv[1]["total_us"]):

@@ -102,14 +102,7 @@ typedef struct radar_attn_desc {
     float   softmax_scale;      /* 0 => 1/sqrt(D); must not be negative */
     int32_t keys_per_split;     /* 0 => chosen by the library; else a multiple of 64: cache rows one
                                    workgroup streams before partial results are merged */
-    int32_t variant;            /* RADAR_ATTN_AUTO, or force one work decomposition (same results) */
 } radar_attn_desc;
-
-#define RADAR_ATTN_AUTO         0
-#define RADAR_ATTN_KEY_SPLIT    1   /* workgroup = one query head, wavefronts split the cache rows:
-                                       lowest latency while the whole KV cache is small (re-read G times) */
-#define RADAR_ATTN_GROUP_SHARE  2   /* workgroup = up to 4 grouped query heads sharing each K/V tile:
-                                       KV is read once; for long contexts and batches */
 
 size_t radar_tree_attention_workspace_bytes(const radar_attn_desc *desc);
 

@@ -17,9 +17,6 @@ _lib = None
 RADAR_OK = 0
 RADAR_ACCEPT_GREEDY = 0
 RADAR_ACCEPT_SAMPLE = 1
-RADAR_ATTN_AUTO = 0
-RADAR_ATTN_KEY_SPLIT = 1
-RADAR_ATTN_GROUP_SHARE = 2
 RADAR_T_MAX = 64
 RADAR_K_MAX = 16
 RADAR_F_MAX = 64
@@ -39,7 +36,7 @@ class AttnDesc(ctypes.Structure):
                 ("kv_stride_b", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64), ("kv_stride_s", ctypes.c_int64),
                 ("out_stride_b", ctypes.c_int64), ("out_stride_t", ctypes.c_int64), ("out_stride_h", ctypes.c_int64),
                 ("softmax_scale", ctypes.c_float), ("keys_per_split", ctypes.c_int32),
-                ("variant", ctypes.c_int32)]
+]
 
 
 class ExpandDesc(ctypes.Structure):
@@ -184,7 +181,7 @@ def radar_workspace_init(ws):
 
 # ------------------------------------------------------------ tree attention
 
-def attn_desc(q, k_cache, keys_per_split=0, softmax_scale=0.0, variant=0):
+def attn_desc(q, k_cache, keys_per_split=0, softmax_scale=0.0):
     B, T, Hq, D = q.shape
     Bk, Hkv, S, Dk = k_cache.shape
     d = AttnDesc()
@@ -194,7 +191,6 @@ def attn_desc(q, k_cache, keys_per_split=0, softmax_scale=0.0, variant=0):
     d.out_stride_b = d.out_stride_t = d.out_stride_h = 0
     d.softmax_scale = float(softmax_scale)
     d.keys_per_split = int(keys_per_split)
-    d.variant = int(variant)
     return d
 
 
@@ -203,13 +199,13 @@ def radar_tree_attention_workspace_bytes(desc):
 
 
 def radar_tree_attention(q, k_cache, v_cache, parents, ctx_lens, n_nodes=None, out=None, lse_out=None,
-                         desc=None, workspace=None, keys_per_split=0, softmax_scale=0.0, variant=0, prepared=False):
+                         desc=None, workspace=None, keys_per_split=0, softmax_scale=0.0, prepared=False):
     """q bf16 [B,T,Hq,D]; k_cache, v_cache bf16 [B,Hkv,S,D] (same strides, D contiguous);
     parents i32 [B,T]; ctx_lens i32 [B]; n_nodes i32 [B] or None.  Returns out bf16 [B,T,Hq,D]."""
     if q.stride(-1) != 1 or k_cache.stride(-1) != 1 or v_cache.stride() != k_cache.stride():
         raise ValueError("innermost axis must be contiguous and k/v caches must share strides")
     if desc is None:
-        desc = attn_desc(q, k_cache, keys_per_split, softmax_scale, variant)
+        desc = attn_desc(q, k_cache, keys_per_split, softmax_scale)
     if out is None:
         out = torch.empty(q.shape, dtype=torch.bfloat16, device=q.device)
     _dense(out, "out")

@@ -8,30 +8,23 @@
 // beyond one exchange with lane^32, the rescaling factor is lane-local, and the
 // exponentiated scores already sit in the register order the next MFMA wants as
 // its B operand (the key order inside a 16-key step is permuted consistently for
-// P^T and V^T, which a contraction does not care about).  A wavefront handles the
-// T <= 64 tree rows of one query head against tiles of 64 cache rows; the running
-// output is rescaled only when some lane's maximum actually moved.
+// P^T and V^T, which a contraction does not care about).  The running output is
+// rescaled only when some lane's maximum actually moved.
 //
 // The ancestor mask is never materialised in memory: each lane walks parents[]
 // once for its query row and keeps the ancestor set as one 64-bit word; a tile
 // that lies entirely in the prefix skips masking altogether.
 //
-// Two work decompositions share that wavefront routine:
-//
-//  * key-split (small caches, e.g. one 8B-class sequence: the KV of all heads fits
-//    the L2s several times over).  A workgroup owns (sequence, QUERY head, range of
-//    cache rows); its four wavefronts take different 64-row tiles of that range,
-//    each staging its own tiles in a private LDS region (no workgroup barrier in
-//    the main loop), and are merged through LDS.  Cutting the rows four ways
-//    inside a workgroup keeps the number of cross-workgroup partials (the
-//    expensive part: T*D fp32 per split) four times lower for the same number of
-//    busy CUs.  The workgroup whose arrival ticket is the last of its head merges
-//    the splits; there is no second launch.
-//
-//  * group-share (large caches, e.g. long contexts and batches: KV must come from
-//    HBM exactly once).  A workgroup owns (sequence, KV head, range of cache rows,
-//    block of up to 4 grouped query heads); its wavefronts are the query heads and
-//    share every K/V tile through LDS.  Splits are merged by a small second kernel.
+// Work decomposition.  A workgroup of eight wavefronts owns (sequence, KV head,
+// range of cache rows, block of eight (query head, 32 tree rows) units); each
+// wavefront is one unit, and all eight share every K/V tile through LDS, so KV
+// comes from HBM once per group of heads.  Two wavefronts per SIMD let one
+// wavefront's MFMAs run underneath the other's softmax arithmetic.  Tiles are
+// double-buffered in LDS (one barrier per tile) and the next tile's global loads
+// are in flight during the arithmetic.  Ranges of cache rows are merged from fp32
+// partials by a small second kernel; how many ranges to cut is decided on the host
+// from a cost model that counts whole rounds of resident workgroups and the
+// partial traffic.
 #include "radar_device.h"
 #include "radar_host.h"
 
@@ -49,7 +42,6 @@ constexpr int kKT = 64;                    // cache rows per LDS tile
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegBig = -1.0e30f;        // finite stand-in for "no score yet" (log2 units)
-constexpr int kAttnCounterStride = 16;     // arrival counters 64 B apart
 
 struct AttnArgs {
     const __bf16 *q, *k, *v;
@@ -59,9 +51,8 @@ struct AttnArgs {
     int B, T, Hq, Hkv, G, S, kps, max_splits, n_ublk, nqb;   // nqb 32-row blocks per head, n_ublk workgroups per KV range
     int64_t q_sb, q_st, q_sh, kv_sb, kv_sh, kv_ss, o_sb, o_st, o_sh;
     float scale_log2;                      // softmax scale * log2(e), > 0
-    unsigned int *counters;                // key-split: [(b*Hq + h) * kAttnCounterStride]
-    float *part_o;                         // key-split: [B][Hq][max_splits][64][D]; group-share: [..][D][64]
-    float *part_ml;                        // key-split: [B][Hq][max_splits][64][2]; group-share: [..][2][64]
+    float *part_o;                         // [B][Hq][max_splits][D][64]: transposed partial outputs
+    float *part_ml;                        // [B][Hq][max_splits][2][64]: running maximum (log2 units) and sum
 };
 
 // byte offset of the 16-byte chunk `chunk` of cache row `key` in a K tile
@@ -219,279 +210,6 @@ __device__ __forceinline__ void wave_tile(const unsigned char *Ks, const unsigne
                                                                            oacc[db][qb], 0, 0, 0);
                 }
     }
-}
-
-// Global -> register staging of one 64-row K/V tile by NT cooperating lanes (lane number t), and
-// the register -> LDS store.  Branch-free: rows past the range re-read the last valid row; V is
-// zeroed afterwards (0 * anything must stay 0), K is masked by the softmax.
-template <int D, int NT>
-struct TileRegs {
-    static constexpr int CH = D / 8;
-    static constexpr int KL = kKT * CH / NT;                               // 16-byte K loads per lane
-    static constexpr int VITEMS = CH * (kKT / 4);                          // (chunk, 4-key group) items
-    static constexpr int VP = (VITEMS + NT - 1) / NT;                      // items per lane
-    u32x4 k[KL];
-    u32x4 v[VP][4];
-};
-
-template <int D, int NT>
-__device__ __forceinline__ void load_tile(TileRegs<D, NT> &r, const __bf16 *kbase, const __bf16 *vbase, int kv_ss,
-                                          int t0, int kend, int t) {
-    constexpr int CH = D / 8;
-#pragma unroll
-    for (int i = 0; i < TileRegs<D, NT>::KL; ++i) {
-        const int c = i * NT + t;
-        const int kpos = min(t0 + c / CH, kend - 1);
-        r.k[i] = *reinterpret_cast<const u32x4 *>(kbase + (uint32_t)(kpos * kv_ss + (c % CH) * 8));
-    }
-#pragma unroll
-    for (int ps = 0; ps < TileRegs<D, NT>::VP; ++ps) {
-        const int item = min(ps * NT + t, TileRegs<D, NT>::VITEMS - 1);
-        const int ch = item % CH, kg = item / CH;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int kpos = t0 + kg * 4 + i;
-            u32x4 v = *reinterpret_cast<const u32x4 *>(vbase + (uint32_t)(min(kpos, kend - 1) * kv_ss + ch * 8));
-            and_mask(v, kpos < kend);
-            r.v[ps][i] = v;
-        }
-    }
-}
-
-template <int D, int NT>
-__device__ __forceinline__ void store_tile(const TileRegs<D, NT> &r, unsigned char *Ks, unsigned char *Vt, int t) {
-    constexpr int CH = D / 8;
-#pragma unroll
-    for (int i = 0; i < TileRegs<D, NT>::KL; ++i) {
-        const int c = i * NT + t;
-        *reinterpret_cast<u32x4 *>(Ks + ks_off<D>(c / CH, c % CH)) = r.k[i];
-    }
-#pragma unroll
-    for (int ps = 0; ps < TileRegs<D, NT>::VP; ++ps) {
-        const int item = ps * NT + t;
-        if (item < TileRegs<D, NT>::VITEMS) store_vt4(Vt, item % CH, item / CH, r.v[ps]);
-    }
-}
-
-// Stages the 64 x D query tile of head h into LDS (swizzled like a K tile); rows >= T are zero.
-// `nthreads` lanes numbered `t` cooperate (a wavefront or the whole workgroup).
-template <int D, int NT>
-__device__ __forceinline__ void stage_q(const AttnArgs &a, int b, int h, bool active, unsigned char *Qs, int t) {
-    constexpr int CH = D / 8, N = 64 * CH / NT;
-    const __bf16 *qbase = a.q + (size_t)b * a.q_sb + (size_t)h * a.q_sh;
-    u32x4 raw[N];
-#pragma unroll
-    for (int i = 0; i < N; ++i) {                               // all loads first: one round trip
-        const int c = i * NT + t, row = c / CH, ch = c % CH;
-        raw[i] = *reinterpret_cast<const u32x4 *>(qbase + (uint32_t)(min(row, a.T - 1) * (int)a.q_st + ch * 8));
-        and_mask(raw[i], active && row < a.T);
-    }
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-        const int c = i * NT + t;
-        *reinterpret_cast<u32x4 *>(Qs + ks_off<D>(c / CH, c % CH)) = raw[i];
-    }
-}
-
-// ===================================================================== key-split kernel
-template <int D>
-struct KsLayout {
-    static constexpr int MROW = D + 4;                           // floats per merge row (padded)
-    static constexpr int WAVE_BYTES = 64 * MROW * 4;             // >= tile bytes (2 * 64 * D * 2)
-    static constexpr int Q_OFF = kAttnWaves * WAVE_BYTES;        // the head's 64 x D query tile (bf16, swizzled)
-    static constexpr int ML_OFF = Q_OFF + 64 * D * 2;            // float [4][2][64]
-    static constexpr int PAR_OFF = ML_OFF + kAttnWaves * 2 * 64 * 4;
-    static constexpr int TICKET_OFF = PAR_OFF + RADAR_T_MAX * 4;
-    static constexpr int BYTES = TICKET_OFF + 16;
-};
-
-template <int D, int NQB>
-__global__ __launch_bounds__(kAttnThreads) void tree_attn_ks_kernel(AttnArgs a) {
-    constexpr int CH = D / 8, DB = D / 32;
-    constexpr int KL = kKT * CH / kWave;                         // 16-byte K loads per lane per tile
-    constexpr int VP = CH * (kKT / 4) / kWave;                   // 4-key V items per lane per tile
-    constexpr int DQ = D / 4;                                    // floats per lane in the merges
-    using Lay = KsLayout<D>;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-
-    const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
-    const int sp = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    const int hk = h / a.G;
-    const int L = a.ctx_lens[b];
-    int nn = a.n_nodes ? a.n_nodes[b] : a.T;
-    nn = max(1, min(nn, a.T));
-    const int total = min(L + nn, a.S);                          // never read past the cache the caller described
-    const int kbeg = sp * a.kps;
-    if (L < 0 || kbeg >= total) return;
-    const int kend = min(total, kbeg + a.kps);
-    const int nsplit = (total + a.kps - 1) / a.kps;
-    const int j32 = lane & 31, g2 = lane >> 5;
-
-    unsigned char *Ks = smem + w * Lay::WAVE_BYTES;
-    unsigned char *Vt = Ks + kKT * D * 2;
-    float *ml = reinterpret_cast<float *>(smem + Lay::ML_OFF);
-    int *s_par = reinterpret_cast<int *>(smem + Lay::PAR_OFF);
-    unsigned int *s_ticket = reinterpret_cast<unsigned int *>(smem + Lay::TICKET_OFF);
-
-    const __bf16 *kbase = a.k + (size_t)b * a.kv_sb + (size_t)hk * a.kv_sh;
-    const __bf16 *vbase = a.v + (size_t)b * a.kv_sb + (size_t)hk * a.kv_sh;
-    const int kv_ss = (int)a.kv_ss;          // 32-bit offsets inside one head's cache (checked on the host)
-    const int ntiles = (kend - kbeg + kKT - 1) / kKT;
-
-    TileRegs<D, kWave> regs;                                     // staging by ONE wavefront
-
-    // every load this wavefront needs first is issued before anything waits.  The query tile
-    // is the same for the four wavefronts: it is staged once in LDS and read back as MFMA
-    // operands after the K/V staging registers have been released.
-    if (w < ntiles) load_tile<D, kWave>(regs, kbase, vbase, kv_ss, kbeg + w * kKT, kend, lane);
-    stage_q<D, kAttnThreads>(a, b, h, true, smem + Lay::Q_OFF, tid);
-    if (tid < RADAR_T_MAX) s_par[tid] = a.parents[(size_t)b * a.T + min(tid, nn - 1)];
-    __syncthreads();
-    uint64_t anc[NQB];
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-        const int i = 32 * qb + j32;
-        anc[qb] = (kend > L && i < nn) ? ancestor_word(s_par, i) : 0ull;
-    }
-
-    floatx16 oacc[DB][NQB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[db][qb][r] = 0.f;
-    float m_run[NQB], l_run[NQB];
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) { m_run[qb] = kNegBig; l_run[qb] = 0.f; }
-
-    // ---- this wavefront's tiles: w, w+4, ...  (private LDS region: no workgroup barrier)
-    for (int t = w; t < ntiles; t += kAttnWaves) {
-        const int t0 = kbeg + t * kKT;
-        if (t != w) load_tile<D, kWave>(regs, kbase, vbase, kv_ss, t0, kend, lane);                                // (the first tile's loads were issued up front;
-                                                                  // staging registers are not kept across the compute)
-        wave_lds_sync();                                          // previous tile's LDS reads are done
-        store_tile<D, kWave>(regs, Ks, Vt, lane);
-        wave_lds_sync();
-        wave_tile<D, NQB>(Ks, Vt, smem + Lay::Q_OFF, oacc, m_run, l_run, anc, t0, L, kend, t == w, a.scale_log2);
-    }
-
-    // ---- merge the four wavefronts through LDS (each writes its own region, all read all)
-    wave_lds_sync();
-    {
-        float *mo = reinterpret_cast<float *>(smem + w * Lay::WAVE_BYTES);
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) {
-            const int i = 32 * qb + j32;
-            const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32);
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    const float4 v = make_float4(oacc[db][qb][4 * r4], oacc[db][qb][4 * r4 + 1],
-                                                 oacc[db][qb][4 * r4 + 2], oacc[db][qb][4 * r4 + 3]);
-                    *reinterpret_cast<float4 *>(mo + i * Lay::MROW + 32 * db + 8 * r4 + 4 * g2) = v;
-                }
-            if (g2 == 0) { ml[(w * 2 + 0) * 64 + i] = m_run[qb]; ml[(w * 2 + 1) * 64 + i] = l_tot; }
-        }
-        if (NQB == 1 && g2 == 0) { ml[(w * 2 + 0) * 64 + 32 + j32] = kNegBig; ml[(w * 2 + 1) * 64 + 32 + j32] = 0.f; }
-    }
-    __syncthreads();
-
-    const int i = tid >> 2, dq = tid & 3;                         // merge role: query row, quarter of the head dim
-    float acc[DQ];
-    float M = kNegBig, Lsum = 0.f;
-    {
-        float mw[kAttnWaves], wg[kAttnWaves];
-#pragma unroll
-        for (int ww = 0; ww < kAttnWaves; ++ww) { mw[ww] = ml[(ww * 2) * 64 + i]; M = fmaxf(M, mw[ww]); }
-#pragma unroll
-        for (int ww = 0; ww < kAttnWaves; ++ww) {
-            wg[ww] = __builtin_amdgcn_exp2f(mw[ww] - M);
-            Lsum += wg[ww] * ml[(ww * 2 + 1) * 64 + i];
-        }
-#pragma unroll
-        for (int d = 0; d < DQ; ++d) acc[d] = 0.f;
-        if (NQB == 2 || i < 32) {
-#pragma unroll
-            for (int ww = 0; ww < kAttnWaves; ++ww) {
-                const float *mo = reinterpret_cast<const float *>(smem + ww * Lay::WAVE_BYTES) + i * Lay::MROW + dq * DQ;
-#pragma unroll
-                for (int d4 = 0; d4 < DQ / 4; ++d4) {
-                    const float4 v = *reinterpret_cast<const float4 *>(mo + 4 * d4);
-                    acc[4 * d4 + 0] += wg[ww] * v.x; acc[4 * d4 + 1] += wg[ww] * v.y;
-                    acc[4 * d4 + 2] += wg[ww] * v.z; acc[4 * d4 + 3] += wg[ww] * v.w;
-                }
-            }
-        }
-    }
-
-    auto write_out = [&](float Mv, float Lv) {
-        if (i >= a.T) return;
-        __bf16 *orow = a.out + (size_t)b * a.o_sb + (size_t)i * a.o_st + (size_t)h * a.o_sh + dq * DQ;
-        const float inv = (i < nn && Lv > 0.f) ? 1.0f / Lv : 0.f;
-#pragma unroll
-        for (int c = 0; c < DQ / 8; ++c) {
-            bf16x8 o8;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o8[e] = (__bf16)(i < nn ? acc[8 * c + e] * inv : 0.f);
-            *reinterpret_cast<bf16x8 *>(orow + 8 * c) = o8;
-        }
-        if (a.lse && dq == 0)
-            a.lse[((size_t)b * a.T + i) * a.Hq + h] = (i < nn) ? (Mv + __builtin_amdgcn_logf(Lv)) * kLn2 : 0.f;
-    };
-
-    if (nsplit == 1) { write_out(M, Lsum); return; }
-
-    // ---- hand the workgroup's partial over (device-scope stores), take a ticket
-    const size_t unit0 = ((size_t)b * a.Hq + h) * a.max_splits;
-    {
-        uint64_t *po = reinterpret_cast<uint64_t *>(a.part_o + ((unit0 + sp) * 64 + i) * D + dq * DQ);
-#pragma unroll
-        for (int e = 0; e < DQ / 2; ++e)
-            store_shared_result(po + e, (uint64_t)__float_as_uint(acc[2 * e]) | ((uint64_t)__float_as_uint(acc[2 * e + 1]) << 32));
-        if (dq == 0)
-            store_shared_result(reinterpret_cast<uint64_t *>(a.part_ml) + (unit0 + sp) * 64 + i,
-                                (uint64_t)__float_as_uint(M) | ((uint64_t)__float_as_uint(Lsum) << 32));
-    }
-    unsigned int *counter = &a.counters[((size_t)b * a.Hq + h) * kAttnCounterStride];
-    if (publish_then_ticket(counter, s_ticket) != (unsigned int)(nsplit - 1)) return;
-    if (tid == 0) store_shared_result(counter, 0u);               // leave the counter clean for the next call
-
-    // ---- last workgroup of this (sequence, head): merge the splits, four at a time so that
-    // all loads of a batch are in flight together
-    M = kNegBig; Lsum = 0.f;
-#pragma unroll
-    for (int d = 0; d < DQ; ++d) acc[d] = 0.f;
-    for (int s0 = 0; s0 < nsplit; s0 += 4) {
-        uint64_t mlv[4];
-        uint64_t ov[4][DQ / 2];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int sc = min(s0 + j, nsplit - 1);
-            mlv[j] = load_shared_result(reinterpret_cast<const uint64_t *>(a.part_ml) + (unit0 + sc) * 64 + i);
-            const uint64_t *po = reinterpret_cast<const uint64_t *>(a.part_o + ((unit0 + sc) * 64 + i) * D + dq * DQ);
-#pragma unroll
-            for (int e = 0; e < DQ / 2; ++e) ov[j][e] = load_shared_result(po + e);
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bool valid = s0 + j < nsplit;
-            const float ms = valid ? __uint_as_float((uint32_t)mlv[j]) : kNegBig;
-            const float ls = valid ? __uint_as_float((uint32_t)(mlv[j] >> 32)) : 0.f;
-            const float Mn = fmaxf(M, ms);
-            const float aold = __builtin_amdgcn_exp2f(M - Mn);
-            const float wnew = valid ? __builtin_amdgcn_exp2f(ms - Mn) : 0.f;
-            Lsum = Lsum * aold + wnew * ls;
-#pragma unroll
-            for (int e = 0; e < DQ / 2; ++e) {
-                acc[2 * e] = acc[2 * e] * aold + wnew * __uint_as_float((uint32_t)ov[j][e]);
-                acc[2 * e + 1] = acc[2 * e + 1] * aold + wnew * __uint_as_float((uint32_t)(ov[j][e] >> 32));
-            }
-            M = Mn;
-        }
-    }
-    write_out(M, Lsum);
 }
 
 // ===================================================================== group-share kernel
@@ -738,9 +456,8 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_merge_kernel(AttnArgs 
 
 // ------------------------------------------------------------------ host-side planning
 struct AttnPlan {
-    bool key_split;
     int kps, max_splits, n_ublk, nqb;
-    size_t off_counters, off_part_o, off_part_ml, bytes;
+    size_t off_part_o, off_part_ml, bytes;
 };
 
 static AttnPlan plan_attention(const radar_attn_desc *d) {
@@ -748,40 +465,30 @@ static AttnPlan plan_attention(const radar_attn_desc *d) {
     const int G = d->Hq / d->Hkv;
     p.nqb = d->T_max <= 32 ? 1 : 2;
     p.n_ublk = (G * p.nqb + kGsWaves - 1) / kGsWaves;
-    p.key_split = d->variant == RADAR_ATTN_KEY_SPLIT;      // never chosen automatically: measured slower at every shape tried
     long kps = d->keys_per_split;
     if (kps <= 0) {
-        if (p.key_split) {
-            // a multiple of 4 tiles, so that each wavefront gets whole tiles; about 256 workgroups
-            const long units = (long)d->B * d->Hq;
-            long ns = (256 + units - 1) / units;
-            if (ns < 1) ns = 1;
-            kps = ((long)d->S_max + ns - 1) / ns;
-            kps = (kps + 4 * kKT - 1) / (4 * kKT) * (4 * kKT);
-        } else {
-            // Number of key ranges: the one that minimises a small cost model, in units of one tile of
-            // one workgroup (measured ~2.7 us): rounds of 256 resident workgroups x (tiles per range +
-            // 3 for prologue and epilogue), plus what the merge of the ranges costs (every range writes
-            // and re-reads T*Hq*D fp32 of partial output, which soon exceeds the KV bytes themselves).
-            // Counting whole rounds matters: 576 workgroups take as long as 768.
-            const long units = (long)d->B * d->Hkv * p.n_ublk;
-            const long tiles_all = ((long)d->S_max + kKT - 1) / kKT;
-            double best = 1e30;
-            long best_ns = 1;
-            for (long ns = 1; ns <= 64 && ns <= tiles_all; ++ns) {
-                const long tiles = (tiles_all + ns - 1) / ns;
-                const long rounds = (units * ns + 255) / 256;
-                const double cost = (double)rounds * (double)(tiles + 3) + (ns > 1 ? 1.6 + 0.3 * (double)ns : 0.0);
-                if (cost < best) { best = cost; best_ns = ns; }
-            }
-            kps = (tiles_all + best_ns - 1) / best_ns * kKT;
+        // Number of key ranges: the one that minimises a small cost model, in units of one tile of
+        // one workgroup (measured ~2.7 us): rounds of 256 resident workgroups x (tiles per range +
+        // 3 for prologue and epilogue), plus what the merge of the ranges costs (every range writes
+        // and re-reads T*Hq*D fp32 of partial output, which soon exceeds the KV bytes themselves).
+        // Counting whole rounds matters: 576 workgroups take as long as 768.
+        const long units = (long)d->B * d->Hkv * p.n_ublk;
+        const long tiles_all = ((long)d->S_max + kKT - 1) / kKT;
+        double best = 1e30;
+        long best_ns = 1;
+        for (long ns = 1; ns <= 64 && ns <= tiles_all; ++ns) {
+            const long tiles = (tiles_all + ns - 1) / ns;
+            const long rounds = (units * ns + 255) / 256;
+            const double cost = (double)rounds * (double)(tiles + 3) + (ns > 1 ? 1.6 + 0.3 * (double)ns : 0.0);
+            if (cost < best) { best = cost; best_ns = ns; }
         }
-    }
+        kps = (tiles_all + best_ns - 1) / best_ns * kKT;
+}
     p.kps = (int)kps;
     p.max_splits = (int)(((long)d->S_max + kps - 1) / kps);
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t o = off; off += (bytes + 255) & ~size_t(255); return o; };
-    p.off_counters = take((size_t)d->B * d->Hq * kAttnCounterStride * sizeof(unsigned int));
+    take(256);                                             // never empty: callers always pass a workspace
     const size_t units = p.max_splits > 1 ? (size_t)d->B * d->Hq * p.max_splits : 0;
     p.off_part_o = take(units * 64 * d->D * sizeof(float));
     p.off_part_ml = take(units * 128 * sizeof(float));
@@ -799,8 +506,6 @@ static radar_status check_attn_desc(const radar_attn_desc *d) {
         return RADAR_INVALID_ARG;
     if (d->keys_per_split < 0 || d->keys_per_split % kKT != 0) return RADAR_INVALID_ARG;
     if (d->softmax_scale < 0.f) return RADAR_INVALID_ARG;
-    if (d->variant != RADAR_ATTN_AUTO && d->variant != RADAR_ATTN_KEY_SPLIT && d->variant != RADAR_ATTN_GROUP_SHARE)
-        return RADAR_INVALID_ARG;
     if ((d->D != 64 && d->D != 128) || d->T_max > RADAR_T_MAX) return RADAR_UNSUPPORTED_SHAPE;
     if (d->B > 65535 || d->Hq > 65535) return RADAR_UNSUPPORTED_SHAPE;
     return RADAR_OK;
@@ -824,18 +529,6 @@ static hipError_t launch_gs(const AttnArgs &a, dim3 grid, hipStream_t s) {
         configured = true;
     }
     return launch("tree_attn_group_share", tree_attn_gs_kernel<D>, grid, dim3(kGsThreads), gs_smem_bytes<D>(), s, a);
-}
-
-template <int D, int NQB>
-static hipError_t launch_ks(const AttnArgs &a, dim3 grid, hipStream_t s) {
-    static bool configured = false;                        // raise the dynamic LDS limit once per instantiation
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_ks_kernel<D, NQB>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, KsLayout<D>::BYTES);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
-    return launch("tree_attn_key_split", tree_attn_ks_kernel<D, NQB>, grid, dim3(kAttnThreads), KsLayout<D>::BYTES, s, a);
 }
 
 extern "C" radar_status radar_tree_attention(const void *q, const void *k_cache, const void *v_cache,
@@ -877,20 +570,11 @@ extern "C" radar_status radar_tree_attention(const void *q, const void *k_cache,
     const float scale = d->softmax_scale != 0.f ? d->softmax_scale : 1.0f / sqrtf((float)d->D);
     a.scale_log2 = scale * kLog2e;
     char *ws = static_cast<char *>(workspace);
-    a.counters = reinterpret_cast<unsigned int *>(ws + p.off_counters);
     a.part_o = reinterpret_cast<float *>(ws + p.off_part_o);
     a.part_ml = reinterpret_cast<float *>(ws + p.off_part_ml);
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 block(kAttnThreads);
-    const bool narrow = d->T_max <= 32;
-    if (p.key_split) {
-        const dim3 grid((unsigned)a.max_splits, (unsigned)a.Hq, (unsigned)a.B);
-        hipError_t e;
-        if (d->D == 128) e = narrow ? launch_ks<128, 1>(a, grid, s) : launch_ks<128, 2>(a, grid, s);
-        else             e = narrow ? launch_ks<64, 1>(a, grid, s) : launch_ks<64, 2>(a, grid, s);
-        return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
-    }
     if ((long)a.Hkv * a.n_ublk > 65535) return RADAR_UNSUPPORTED_SHAPE;
     const dim3 grid((unsigned)a.max_splits, (unsigned)(a.Hkv * a.n_ublk), (unsigned)a.B);
     {

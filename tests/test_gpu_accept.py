@@ -134,3 +134,36 @@ def test_workspace_reuse_and_determinism(oracle):
         if mode == 1:
             assert all(np.array_equal(p, q) for p, q in zip(first, again))
     assert int(ws[:4096].view(torch.int32).abs().sum().item()) == 0
+
+
+def test_wide_levels_and_duplicate_sibling_tokens(oracle):
+    """Star-shaped trees (up to 63 children of the root, tried all at once on the device) whose
+    sibling tokens repeat: the earliest sibling with a token wins, later copies are skipped, and
+    the residual draw removes every tried token.  Uniforms differ per sequence."""
+    from paper_2512_14069_amd import binding as b
+    B, T, V = 192, 64, 3000
+    rng = np.random.default_rng(11)
+    parents = synth.star_tree(T)
+    parents[40:] = rng.integers(1, 8, size=T - 40)          # a second, narrower level under nodes 1..7
+    tokens = rng.integers(0, V, size=T).astype(np.int32)
+    tokens[5] = tokens[2]; tokens[17] = tokens[2]; tokens[30] = tokens[9]     # repeated sibling tokens
+    logits = synth.normal_logits(rng, (T, V), 1.5)
+    for c in range(1, T):
+        logits[parents[c], tokens[c]] = 3.0 + 0.02 * c       # every draft token carries visible mass
+    x = dict(target_logits=np.broadcast_to(logits, (B, T, V)).copy(),
+             draft_tokens=np.broadcast_to(tokens, (B, T)).copy(),
+             parents=np.broadcast_to(parents, (B, T)).copy(),
+             n_nodes=np.full(B, T, np.int32), uniforms=rng.random((B, T + 1), dtype=np.float32))
+    ref, got = compare(oracle, b, x, 1)
+    assert len(set(ref[0].tolist())) >= 2 and (ref[0] == 0).any() and (ref[0] > 0).any()
+    compare(oracle, b, x, 0)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_large_vocabulary_many_blocks(oracle, mode):
+    """More than 128 blocks of 1024 logits per row: the merge and the residual scan loop."""
+    from paper_2512_14069_amd import binding as b
+    V = 300001
+    a = small_shape(2, 12, (12, 7), (3, 2), k=3)
+    x = synth.accept_inputs(a, V, seed=77)
+    compare(oracle, b, x, mode)

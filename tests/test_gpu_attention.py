@@ -30,13 +30,13 @@ def check_close(got_bits, ref_bits, what=""):
     return err.max(), rel
 
 
-def run_gpu(b, x, keys_per_split=0, want_lse=False, scale=0.0, variant=0):
+def run_gpu(b, x, keys_per_split=0, want_lse=False, scale=0.0):
     q, kc, vc = bf16_dev(x["q"]), bf16_dev(x["k_cache"]), bf16_dev(x["v_cache"])
     B, T, Hq, D = q.shape
     lse = torch.full((B, T, Hq), 7.0, dtype=torch.float32, device="cuda") if want_lse else None
     out = torch.full(q.shape, 3.0, dtype=torch.bfloat16, device="cuda")
     b.radar_tree_attention(q, kc, vc, dev(x["parents"]), dev(x["ctx_lens"]), dev(x["n_nodes"]),
-                           out=out, lse_out=lse, keys_per_split=keys_per_split, softmax_scale=scale, variant=variant)
+                           out=out, lse_out=lse, keys_per_split=keys_per_split, softmax_scale=scale)
     torch.cuda.synchronize()
     return (bf16_bits(out), host(lse)) if want_lse else bf16_bits(out)
 
@@ -58,16 +58,15 @@ CASES = {
 }
 
 
-@pytest.mark.parametrize("variant", [1, 2], ids=["key_split", "group_share"])
 @pytest.mark.parametrize("kps", [0, 64, 128])
 @pytest.mark.parametrize("name", list(CASES))
-def test_small_cases_match_oracle(oracle, name, kps, variant):
+def test_small_cases_match_oracle(oracle, name, kps):
     from paper_2512_14069_amd import binding as b
     a = CASES[name]
     x = synth.attention_inputs(a, seed=synth.seed_for(1, len(name)), shuffle=True)
     ref, ref_lse = oracle.tree_attention(x["q"], x["k_cache"], x["v_cache"], x["parents"], x["ctx_lens"],
                                          x["n_nodes"], want_lse=True)
-    got, lse = run_gpu(b, x, keys_per_split=kps, want_lse=True, variant=variant)
+    got, lse = run_gpu(b, x, keys_per_split=kps, want_lse=True)
     for bb in range(a.B):
         n = a.n_nodes[bb]
         check_close(got[bb, :n], ref[bb, :n], f"{name} b={bb}")
@@ -82,10 +81,9 @@ def test_chain_and_star_trees_depth_63(oracle):
     x["parents"][0] = synth.chain_tree(64)
     x["parents"][1] = synth.star_tree(64)
     ref = oracle.tree_attention(x["q"], x["k_cache"], x["v_cache"], x["parents"], x["ctx_lens"], x["n_nodes"])
-    for variant in (1, 2):
-        for kps in (0, 64):
-            got = run_gpu(b, x, keys_per_split=kps, variant=variant)
-            check_close(got, ref, f"kps={kps} variant={variant}")
+    for kps in (0, 64):
+        got = run_gpu(b, x, keys_per_split=kps)
+        check_close(got, ref, f"kps={kps}")
 
 
 def test_non_ancestors_and_padding_rows_do_not_leak(oracle):
@@ -156,8 +154,8 @@ def test_config2_full(oracle):
     check_close(got, ref, "config 2")
     again = run_gpu(b, x)
     assert np.array_equal(got, again)            # bit-reproducible
-    for variant, kps in ((1, 256), (1, 1024), (2, 0), (2, 512)):
-        check_close(run_gpu(b, x, keys_per_split=kps, variant=variant), ref, f"config 2 variant {variant} kps {kps}")
+    for kps in (64, 256, 512, 1024, 4096):
+        check_close(run_gpu(b, x, keys_per_split=kps), ref, f"config 2 kps {kps}")
 
 
 def test_config4_ragged_sampled(oracle):

@@ -56,6 +56,9 @@ def run_both_step(oracle, b, logits, ps, ppi, k, gpu_pool, cpu_pool, ws=None):
     (2, 10, 10),           # k == V
     (7, 12290, 16),        # largest k, tail of two elements
     (64, 8192, 2),         # most rows
+    (2, 300000, 10),       # more than 64 chunks per row: chunk lists and partials are merged in several blocks
+    (40, 128256, 10),      # too many workgroups for 4 or 8 logits per lane: 16 per lane
+    (5, 20000, 1),         # k = 1
 ])
 def test_expand_step_matches_oracle(oracle, F, V, k):
     from paper_2512_14069_amd import binding as b
