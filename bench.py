@@ -48,7 +48,8 @@ def parse():
 
 
 def read_traffic():
-    """HBM bytes per attention launch measured offline with rocprofv3 --pmc (see profiles/)."""
+    """HBM bytes per launch of the first attention kernel, measured offline with rocprofv3 --pmc
+    (FETCH_SIZE and WRITE_SIZE scaled by a copy of known size; see the file for the commands)."""
     path = os.path.join(ROOT, "profiles", "tree_attention_c2_traffic.txt")
     try:
         for line in open(path):
