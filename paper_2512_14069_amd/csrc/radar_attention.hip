@@ -107,14 +107,14 @@ __device__ __forceinline__ void store_vt4(unsigned char *Vt, int ch, int kg, con
 
 // One wavefront, one 64-row tile that sits in LDS (Ks row-major swizzled, Vt transposed):
 // scores, masked online softmax, and the update of the transposed output accumulators.
-// The head's query rows also sit in LDS (Qs, 64 x D bf16 in the K tile's swizzled layout)
-// and are fetched as MFMA B operands per 32-query block: holding them in registers for
-// the whole kernel costs 64 VGPRs that the staging of the next tile needs more.
+// The lane's query operands are passed in registers (qop: row j32 of the block, d = 16*st + 8*g2
+// .. +8; 32 VGPRs at D = 128): every LDS byte not read matters here, the eight wavefronts of a
+// workgroup already read each K and V tile eight times over.
 //   t0        cache row of the tile's first key;  L = prefix length;  kend = end of this range
 //   first     true if the accumulators are still zero (no rescaling needed)
 template <int D, int NQB>
 __device__ __forceinline__ void wave_tile(const unsigned char *Ks, const unsigned char *Vt,
-                                          const unsigned char *Qs, floatx16 (&oacc)[D / 32][NQB],
+                                          const bf16x8 (&qop)[D / 16], floatx16 (&oacc)[D / 32][NQB],
                                           float (&m_run)[NQB], float (&l_run)[NQB], const uint64_t (&anc)[NQB],
                                           int t0, int L, int kend, bool first, float scale_log2) {
     constexpr int KSTEPS = D / 16, DB = D / 32;
@@ -131,10 +131,7 @@ __device__ __forceinline__ void wave_tile(const unsigned char *Ks, const unsigne
     floatx16 sacc[NQB][2];
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
-        bf16x8 qop[KSTEPS];                  // lane (query j32 of the block, half g2): d = 16*st + 8*g2 .. +8
-#pragma unroll
-        for (int st = 0; st < KSTEPS; ++st)
-            qop[st] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(Qs + ks_off<D>(32 * qb + j32, 2 * st + g2)));
+        static_assert(NQB == 1, "the query operands of one 32-row block are passed in registers");
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
@@ -219,26 +216,6 @@ __device__ __forceinline__ void wave_tile(const unsigned char *Ks, const unsigne
 constexpr int kGsThreads = 512;
 constexpr int kGsWaves = kGsThreads / kWave;
 
-// Stages 32 query rows (row0 .. row0+31 of head h) into LDS, swizzled like a K tile; rows >= T and
-// inactive wavefronts give zeros.  One wavefront, lane t.
-template <int D>
-__device__ __forceinline__ void stage_q32(const AttnArgs &a, int b, int h, bool active, int row0, unsigned char *Qs, int t) {
-    constexpr int CH = D / 8, N = 32 * CH / kWave;
-    const __bf16 *qbase = a.q + (size_t)b * a.q_sb + (size_t)h * a.q_sh;
-    u32x4 raw[N];
-#pragma unroll
-    for (int i = 0; i < N; ++i) {                               // all loads first: one round trip
-        const int c = i * kWave + t, row = row0 + c / CH, ch = c % CH;
-        raw[i] = *reinterpret_cast<const u32x4 *>(qbase + (uint32_t)(min(row, a.T - 1) * (int)a.q_st + ch * 8));
-        and_mask(raw[i], active && row < a.T);
-    }
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-        const int c = i * kWave + t;
-        *reinterpret_cast<u32x4 *>(Qs + ks_off<D>(c / CH, c % CH)) = raw[i];
-    }
-}
-
 // Staging of one 64-row K/V tile by the 512 lanes of the workgroup, four 16-byte loads per lane and
 // no request made twice: lanes 0..255 fetch K (row-major chunks), lanes 256..511 fetch V, one
 // (chunk, four-key group) item each, which they transpose on the way into LDS.  Branch-free loads:
@@ -294,12 +271,10 @@ __device__ __forceinline__ void gs_store_tile(const GsTileRegs<D> &g, unsigned c
 template <int D>
 __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
     constexpr int DB = D / 32;              // 32-row blocks of O^T
-    constexpr int QBYTES = 32 * D * 2;      // one wavefront's query block
 
     constexpr int TILE = 2 * kKT * D * 2;   // one K tile ([64][D] bf16, swizzled) + one V^T tile ([D][64], swizzled)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char *Qs = smem + 2 * TILE + threadIdx.x / kWave * QBYTES;          // this wavefront's query block
-    int *s_par = reinterpret_cast<int *>(smem + 2 * TILE + kGsWaves * QBYTES);
+    int *s_par = reinterpret_cast<int *>(smem + 2 * TILE);
 
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int sp = blockIdx.x;
@@ -328,7 +303,17 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
     const int ntiles = (kend - kbeg + kKT - 1) / kKT;
     GsTileRegs<D> regs;                                   // staging by the whole workgroup
     gs_load_tile<D>(regs, kbase, vbase, kv_ss, kbeg, kend, tid);
-    stage_q32<D>(a, b, h, active, 32 * qb, Qs, lane);
+    // this lane's query operands, kept in registers for the whole kernel: row i, d = 16*st + 8*g2 .. +8
+    bf16x8 qop[D / 16];
+    {
+        const __bf16 *qrow = a.q + (size_t)b * a.q_sb + (size_t)h * a.q_sh + (uint32_t)(min(i, a.T - 1) * (int)a.q_st);
+#pragma unroll
+        for (int st = 0; st < D / 16; ++st) {
+            u32x4 raw = *reinterpret_cast<const u32x4 *>(qrow + 16 * st + 8 * g2);
+            and_mask(raw, active && i < a.T);
+            qop[st] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
     if (tid < RADAR_T_MAX) s_par[tid] = a.parents[(size_t)b * a.T + min(tid, nn - 1)];
     gs_store_tile<D>(regs, smem, smem + TILE / 2, tid);
     __syncthreads();
@@ -348,7 +333,7 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
     // One barrier per tile: it publishes tile t+1 and tells that nobody reads tile t any more.
     for (int t = 0; t < ntiles; ++t) {
         unsigned char *cur = smem + (t & 1) * TILE, *nxt = smem + ((t + 1) & 1) * TILE;
-        if (active) wave_tile<D, 1>(cur, cur + TILE / 2, Qs, oacc, m_run, l_run, anc, kbeg + t * kKT, L, kend, t == 0, a.scale_log2);
+        if (active) wave_tile<D, 1>(cur, cur + TILE / 2, qop, oacc, m_run, l_run, anc, kbeg + t * kKT, L, kend, t == 0, a.scale_log2);
         if (t + 1 < ntiles) {
             gs_store_tile<D>(regs, nxt, nxt + TILE / 2, tid);
             __syncthreads();
@@ -517,7 +502,7 @@ extern "C" size_t radar_tree_attention_workspace_bytes(const radar_attn_desc *d)
 }
 
 template <int D>
-constexpr int gs_smem_bytes() { return 2 * (2 * kKT * D * 2) + kGsWaves * 32 * D * 2 + RADAR_T_MAX * 4; }
+constexpr int gs_smem_bytes() { return 2 * (2 * kKT * D * 2) + RADAR_T_MAX * 4; }
 
 template <int D>
 static hipError_t launch_gs(const AttnArgs &a, dim3 grid, hipStream_t s) {
