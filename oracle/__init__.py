@@ -14,6 +14,7 @@ from .radar_oracle import (  # noqa: F401
     draft_expand,
     draft_rerank,
     verify_accept,
+    accept_length_distribution,
     accept_margins,
     OracleError,
 )

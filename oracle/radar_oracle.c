@@ -444,6 +444,65 @@ int radar_oracle_verify_accept(const float *target_logits, const int32_t *draft_
     return status;
 }
 
+/* ---------------------------------------------- acceptance-length distribution
+ *
+ * Sec. 4.3, Eq. 11-13: the distribution of the acceptance length of one draft
+ * tree under the sampling rule above, without drawing anything.  With
+ * P_acc(child | parent) = p_parent(token of child) (children are fixed tokens,
+ * see mode 1 above):
+ *   reach(root) = 1,  reach(v) = reach(parent) * p_parent(tok_v)
+ *   P_stop(v)   = reach(v) * (1 - sum over children c of p_v(tok_c))      (Eq. 12-13)
+ *   dist[i]     = sum of P_stop(v) over the nodes v of depth i            (Eq. 11)
+ * A child whose token repeats an earlier sibling's is never reached (reach 0)
+ * and takes no mass from its parent.  Nodes at depth D_max stop with all the
+ * mass that reaches them; deeper nodes are never reached (the walk is cut
+ * there, as in radar_oracle_verify_accept).
+ *
+ * dist f64 [B][D_max+1]; every row sums to 1.
+ */
+int radar_oracle_accept_length_distribution(const float *target_logits, const int32_t *draft_tokens,
+                                            const int32_t *parents, const int32_t *n_nodes,
+                                            int B, int T, int V, int D_max, float temperature, double *dist)
+{
+    if (B < 0 || T < 1 || V < 1 || D_max < 0 || !(temperature > 0.0f)) return ORACLE_BAD_ARG;
+    int status = ORACLE_OK;
+#pragma omp parallel for schedule(dynamic)
+    for (int b = 0; b < B; ++b) {
+        const int nn = n_nodes ? n_nodes[b] : T;
+        const int32_t *par = parents + (size_t)b * T;
+        const int32_t *tok = draft_tokens + (size_t)b * T;
+        double *out = dist + (size_t)b * (D_max + 1);
+        for (int d = 0; d <= D_max; ++d) out[d] = 0.0;
+        if (nn < 1 || nn > T) { status = ORACLE_BAD_ARG; continue; }
+        const double inv_t = 1.0 / (double)temperature;
+        double *reach = (double *)calloc((size_t)nn, sizeof(double));
+        double *kids = (double *)calloc((size_t)nn, sizeof(double));     /* mass handed to children */
+        int *depth = (int *)calloc((size_t)nn, sizeof(int));
+        reach[0] = 1.0;
+        for (int v = 1; v < nn; ++v) {
+            const int p = par[v];
+            if (p < 0 || p >= v) { status = ORACLE_BAD_TREE; continue; }
+            depth[v] = depth[p] + 1;
+            if (depth[v] > D_max || tok[v] < 0 || tok[v] >= V) continue;          /* never reached */
+            int dup = 0;
+            for (int o = p + 1; o < v; ++o) dup |= (par[o] == p && tok[o] == tok[v]);
+            if (dup) continue;
+            const float *x = target_logits + ((size_t)b * T + p) * V;
+            const double pc = exp((double)x[tok[v]] * inv_t - row_lse(x, V, inv_t));
+            reach[v] = reach[p] * pc;
+            kids[p] += pc;
+        }
+        for (int v = 0; v < nn; ++v) {
+            if (depth[v] > D_max) continue;
+            double stay = 1.0 - kids[v];
+            if (stay < 0.0) stay = 0.0;
+            out[depth[v]] += reach[v] * stay;
+        }
+        free(reach); free(kids); free(depth);
+    }
+    return status;
+}
+
 /* Margins that tell a test whether a sampling-mode case is decided far from
  * a rounding boundary (so that an fp32 device path must take the same
  * decisions).  For sequence b, walking exactly as above:

@@ -162,6 +162,23 @@ def verify_accept(target_logits, draft_tokens, parents, n_nodes=None, uniforms=N
     return accept_len, path, bonus
 
 
+def accept_length_distribution(target_logits, draft_tokens, parents, n_nodes=None, temperature=1.0, D_max=None):
+    """Sec. 4.3, Eq. 11-13: float64[B, D_max+1], row b = distribution of the accepted length of tree b."""
+    target_logits = _arr(target_logits, np.float32, name="target_logits")
+    B, T, V = target_logits.shape
+    draft_tokens = _arr(draft_tokens, np.int32, (B, T), "draft_tokens")
+    parents = _arr(parents, np.int32, (B, T), "parents")
+    nn = None if n_nodes is None else _arr(n_nodes, np.int32, (B,), "n_nodes")
+    if D_max is None:
+        D_max = T - 1
+    dist = np.zeros((B, D_max + 1), np.float64)
+    rc = _load().radar_oracle_accept_length_distribution(
+        _p(target_logits), _p(draft_tokens), _p(parents), _p(nn),
+        ctypes.c_int(B), ctypes.c_int(T), ctypes.c_int(V), ctypes.c_int(D_max), ctypes.c_float(temperature), _p(dist))
+    _check(rc, "radar_oracle_accept_length_distribution")
+    return dist
+
+
 def accept_margins(target_logits, draft_tokens, parents, n_nodes, uniforms, temperature=1.0):
     """Distance of every sampling decision from its threshold: float64[B,2]
     (accept tests, residual inverse-CDF)."""

@@ -134,6 +134,11 @@ def test_sampling_matches_closed_form_length_distribution_and_is_lossless(oracle
     # (1) acceptance-length histogram against Eq. 11-13
     dist = accept_length_distribution(P, tokens, parents, depths)
     assert abs(dist.sum() - 1.0) < 1e-12
+    # the oracle's own Eq. 11-13 routine: same numbers as the formula written out above
+    # (and so, through the histogram below, as the sampler it describes)
+    od = oracle.accept_length_distribution(logits[None], tokens[None], parents[None], temperature=temperature)[0]
+    # (the interface carries the temperature as fp32: 0.7 arrives as 0.69999999)
+    assert np.allclose(od[:len(dist)], dist, rtol=0, atol=1e-8) and np.all(od[len(dist):] == 0)
     hist = np.bincount(alen, minlength=len(dist)) / M
     sigma = np.sqrt(dist * (1 - dist) / M)
     assert np.all(np.abs(hist - dist) <= 4 * sigma + 1e-9), (hist, dist)
@@ -231,3 +236,62 @@ def test_sampling_margins_and_bad_arguments(oracle):
     with pytest.raises(oracle.OracleError):
         oracle.verify_accept(logits[None], tokens[None], synth.chain_tree(n)[None], D_max=1,
                              uniforms=np.zeros((1, n + 1), np.float32), mode=1)            # path longer than D_max
+
+
+# ------------------------------------------------- acceptance-length distribution (Eq. 11-13)
+
+def test_length_distribution_chain_closed_form(oracle):
+    """Chain tree: length i means the first i tokens were accepted and token i+1 was not:
+    dist[i] = a_1 ... a_i (1 - a_{i+1}), a_j = p_{j-1}(token j); the leaf keeps what reaches it."""
+    rng = np.random.default_rng(21)
+    n, V, temperature = 7, 11, 0.8
+    parents = synth.chain_tree(n)
+    tokens = rng.integers(0, V, size=n).astype(np.int32)
+    logits = synth.normal_logits(rng, (n, V), 1.0)
+    P = softmax(logits.astype(np.float64) / np.float64(np.float32(temperature)), axis=1)
+    a = np.array([P[j - 1, tokens[j]] for j in range(1, n)])
+    want = np.array([np.prod(a[:i]) * (1 - a[i] if i < n - 1 else 1.0) for i in range(n)])
+    got = oracle.accept_length_distribution(logits[None], tokens[None], parents[None], temperature=temperature)[0]
+    assert np.allclose(got, want, rtol=0, atol=1e-13)
+    assert abs(got.sum() - 1) < 1e-13
+
+
+def test_length_distribution_depth_cut_folds_the_tail(oracle):
+    """Cutting the walk at D_max leaves shorter lengths alone and puts all deeper mass on D_max."""
+    rng, parents, tokens, depths, logits, P = tiny_sampling_case(8, n=12, depth=4)
+    full = oracle.accept_length_distribution(logits[None], tokens[None], parents[None])[0]
+    for d in range(0, 4):
+        cut = oracle.accept_length_distribution(logits[None], tokens[None], parents[None], D_max=d)[0]
+        assert cut.shape == (d + 1,)
+        assert np.allclose(cut[:d], full[:d], atol=1e-14) and abs(cut[d] - full[d:].sum()) < 1e-13
+
+
+def test_length_distribution_repeated_sibling_token_and_ragged_batch(oracle):
+    """A child that repeats an earlier sibling's token is never reached: the distribution equals
+    the one of the tree without that child's subtree.  Rows past n_nodes are ignored."""
+    rng = np.random.default_rng(31)
+    V = 9
+    parents = np.array([-1, 0, 0, 0, 1, 3, 3, 5], np.int32)
+    tokens = np.array([0, 4, 2, 4, 1, 6, 7, 3], np.int32)           # node 3 repeats node 1's token
+    logits = synth.normal_logits(rng, (8, V), 1.2)
+    got = oracle.accept_length_distribution(logits[None], tokens[None], parents[None])[0]
+    keep = np.array([0, 1, 2, 4])                                    # drop node 3 and everything under it
+    remap = {0: 0, 1: 1, 2: 2, 4: 3}
+    p2 = np.array([-1] + [remap[int(parents[v])] for v in keep[1:]], np.int32)
+    pad = np.zeros((8, V), np.float32); pad[:4] = logits[keep]
+    tp = np.zeros(8, np.int32); tp[:4] = tokens[keep]
+    pp = np.full(8, 5, np.int32); pp[:4] = p2                         # junk parents past n_nodes
+    want = oracle.accept_length_distribution(pad[None], tp[None], pp[None], n_nodes=np.array([4], np.int32))[0]
+    assert np.allclose(got, want, atol=1e-14)
+    indep = accept_length_distribution(softmax(pad[:4].astype(np.float64), axis=1), tp[:4], p2, np.array([0, 1, 1, 2]))
+    assert np.allclose(want[:3], indep, atol=1e-12)
+
+
+def test_length_distribution_bad_arguments(oracle):
+    from oracle import OracleError
+    z = np.zeros((1, 3, 5), np.float32)
+    t = np.zeros((1, 3), np.int32)
+    with pytest.raises(OracleError):
+        oracle.accept_length_distribution(z, t, np.array([[-1, 0, 1]], np.int32), temperature=0.0)
+    with pytest.raises(OracleError):
+        oracle.accept_length_distribution(z, t, np.array([[-1, 2, 0]], np.int32))      # parent after child
