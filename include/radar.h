@@ -224,6 +224,26 @@ radar_status radar_verify_accept(const float *target_logits, const int32_t *draf
                                  const radar_accept_desc *desc,
                                  void *workspace, size_t workspace_bytes, void *stream);
 
+/* --------------------------------------------------------------------------
+ * Acceptance-length distribution of a draft tree (Sec. 4.3, Eq. 11-13): what
+ * the walk above would return as accept_len, as a distribution over the
+ * uniforms, computed without drawing.  With P_acc(child | parent) =
+ * p_parent(token of child), p = softmax(row / temperature):
+ *   reach(root) = 1, reach(v) = reach(parent) * p_parent(tok_v);
+ *   P_stop(v) = reach(v) * (1 - sum over children c of p_v(tok_c))  (Eq. 12-13);
+ *   dist[b,i] = sum of P_stop(v) over nodes of depth i              (Eq. 11).
+ * A child that repeats an earlier sibling's token is never reached; nodes at
+ * depth D_max keep all the mass that reaches them and deeper nodes get none
+ * (the cut radar_verify_accept makes).  Every row of dist sums to 1.
+ *
+ * dist f64 [B,D_max+1] (device); the other tensors as for radar_verify_accept;
+ * desc->mode is ignored, desc->temperature must be > 0.  Workspace: what
+ * radar_verify_accept_workspace_bytes(desc) gives; one kernel is enqueued. */
+radar_status radar_accept_length_distribution(const float *target_logits, const int32_t *draft_tokens,
+                                              const int32_t *parents, const int32_t *n_nodes, double *dist,
+                                              const radar_accept_desc *desc,
+                                              void *workspace, size_t workspace_bytes, void *stream);
+
 /* Counts, per call, the nodes i < n_nodes[b] whose parent breaks the tree
  * convention; *bad_count_out (device i32) is overwritten.  parents i32
  * [B,T_max]; n_nodes i32 [B] or NULL. */
@@ -246,7 +266,8 @@ radar_status radar_debug_validate_tree(const int32_t *parents, const int32_t *n_
  * entries in *n_out and destroys the events.  These two calls are the only
  * ones that create or destroy anything and that synchronise. */
 typedef struct radar_kernel_time {
-    char name[48];      /* "expand", "rerank", "accept", "tree_attn_group_share", ... */
+    char name[48];      /* "expand", "rerank", "accept", "accept_length_distribution",
+                           "tree_attn_group_share", "tree_attn_merge", ... */
     int64_t calls;
     double total_us;
     double min_us;

@@ -60,6 +60,7 @@ EXPORTS = [
     "radar_draft_expand_workspace_bytes", "radar_draft_expand",
     "radar_draft_rerank_workspace_bytes", "radar_draft_rerank",
     "radar_verify_accept_workspace_bytes", "radar_verify_accept",
+    "radar_accept_length_distribution",
     "radar_debug_validate_tree", "radar_profile_begin", "radar_profile_end",
 ]
 
@@ -95,6 +96,8 @@ def load():
     lib.radar_verify_accept_workspace_bytes.argtypes = [ctypes.POINTER(AcceptDesc)]
     lib.radar_verify_accept.restype = i32
     lib.radar_verify_accept.argtypes = [vp] * 8 + [ctypes.POINTER(AcceptDesc), vp, sz, vp]
+    lib.radar_accept_length_distribution.restype = i32
+    lib.radar_accept_length_distribution.argtypes = [vp] * 5 + [ctypes.POINTER(AcceptDesc), vp, sz, vp]
     lib.radar_debug_validate_tree.restype = i32
     lib.radar_debug_validate_tree.argtypes = [vp, vp, i32, i32, vp, vp]
     lib.radar_profile_begin.restype = i32
@@ -346,6 +349,31 @@ def radar_verify_accept(target_logits, draft_tokens, parents, n_nodes=None, unif
         ctypes.byref(desc), wp, wn, _stream())
     keep = (target_logits, draft_tokens, parents, n_nodes, uniforms, out, desc, workspace)
     return _finish("radar_verify_accept", load().radar_verify_accept, args, keep, out, prepared)
+
+
+def radar_accept_length_distribution(target_logits, draft_tokens, parents, n_nodes=None, temperature=1.0, D_max=None,
+                                     out=None, workspace=None, prepared=False):
+    """target_logits f32 [B,T,V]; draft_tokens, parents i32 [B,T]; n_nodes i32 [B] or None.
+    Returns dist f64 [B, D_max+1]: row b is the distribution of the accepted length of tree b."""
+    B, T, V = target_logits.shape
+    if D_max is None:
+        D_max = T - 1
+    desc = accept_desc(B, T, V, D_max, RADAR_ACCEPT_SAMPLE, temperature)
+    dev = target_logits.device
+    if out is None:
+        out = torch.empty((B, D_max + 1), dtype=torch.float64, device=dev)
+    if workspace is None:
+        workspace = new_workspace(radar_verify_accept_workspace_bytes(desc), dev)
+    wp, wn = _ws_args(workspace)
+    args = (
+        _ptr(_dense(target_logits, "target_logits"), torch.float32, "target_logits"),
+        _ptr(_dense(draft_tokens, "draft_tokens"), torch.int32, "draft_tokens"),
+        _ptr(_dense(parents, "parents"), torch.int32, "parents"),
+        _ptr(None if n_nodes is None else _dense(n_nodes, "n_nodes"), torch.int32, "n_nodes"),
+        _ptr(_dense(out, "dist"), torch.float64, "dist"),
+        ctypes.byref(desc), wp, wn, _stream())
+    keep = (target_logits, draft_tokens, parents, n_nodes, out, desc, workspace)
+    return _finish("radar_accept_length_distribution", load().radar_accept_length_distribution, args, keep, out, prepared)
 
 
 def radar_debug_validate_tree(parents, n_nodes=None):

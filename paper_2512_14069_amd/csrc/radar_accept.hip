@@ -25,6 +25,7 @@ constexpr int kAccChunk = kAccThreads * kAccEPT;      // logits per workgroup
 constexpr int kAccMaxSubs = 4096;                     // V <= 4,194,304
 constexpr int kAccCounterStride = 16;   // counters 64 B apart (same-line fetch-adds serialise)
 constexpr float kAccLog2e = 1.4426950408889634f;
+constexpr int kAccDistribution = 2;     // internal mode: acceptance-length distribution instead of a walk
 
 struct AcceptArgs {
     const float *logits;
@@ -35,6 +36,7 @@ struct AcceptArgs {
     int32_t *accept_len;
     int32_t *accept_path;
     int32_t *bonus;
+    double *dist;               // mode kAccDistribution: [B][D_max+1]
     int B, T, V, D_max, mode, nwg, nsub;   // nwg workgroups and nsub 1024-logit blocks per row
     int exact_scale;            // 1/temperature is exactly representable in fp32
     float inv_temp_f;
@@ -127,7 +129,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_kernel(AcceptArgs a) {
     int nn = a.n_nodes ? a.n_nodes[b] : a.T;
     nn = max(1, min(nn, a.T));
     if (r >= nn) return;
-    const bool sampling = (a.mode == RADAR_ACCEPT_SAMPLE);
+    const bool sampling = (a.mode != RADAR_ACCEPT_GREEDY);      // row statistics are needed
     const float *row = a.logits + ((size_t)b * a.T + r) * a.V;
     const int sub = blockIdx.x * kAccWaves + w;              // this wavefront's 1024-logit block
 
@@ -186,9 +188,11 @@ __global__ __launch_bounds__(kAccThreads) void accept_kernel(AcceptArgs a) {
         if (c < nn) { p = a.parents[(size_t)b * a.T + c]; t = a.tokens[(size_t)b * a.T + c]; }
         tree_ok = (c > 0 && c < nn && p >= 0 && p < c);
         if (sampling) {
-            const float *u = a.uniforms + (size_t)b * (a.T + 1);
-            uc = u[min(c, a.T)];
-            ubonus = u[a.T];
+            if (a.uniforms) {                                // none in distribution mode
+                const float *u = a.uniforms + (size_t)b * (a.T + 1);
+                uc = u[min(c, a.T)];
+                ubonus = u[a.T];
+            }
             if (tree_ok && t >= 0 && t < a.V) xg = a.logits[((size_t)b * a.T + p) * a.V + t];
         }
         const size_t p0 = ((size_t)b * a.T + r) * a.nsub;
@@ -283,6 +287,39 @@ __global__ __launch_bounds__(kAccThreads) void accept_kernel(AcceptArgs a) {
     // probability of each node's token under its parent's row
     double pc = 0.0;
     if (tree_ok && t >= 0 && t < a.V) pc = exp((double)xg * a.inv_temp - s.row_lse[p]);
+
+    if (a.mode == kAccDistribution) {
+        // Sec. 4.3, Eq. 11-13.  Nodes are visited in index order (parents come first), one lane per
+        // node, values passed between lanes by lane reads; sums run in node order.
+        bool dup = false;                                    // same token as an earlier sibling: never reached
+        for (int o = 1; o < nn; ++o) {
+            const int po = (int)readlane_u32((uint32_t)p, o), to = (int)readlane_u32((uint32_t)t, o);
+            dup = dup || (o < c && po == p && to == t);
+        }
+        if (dup) pc = 0.0;
+        int depth = 0;
+        double reach = c == 0 ? 1.0 : 0.0, kids = 0.0;       // mass that arrives here / that goes on to children
+        for (int v = 1; v < nn; ++v) {
+            if (!readlane_u32((uint32_t)tree_ok, v)) continue;                   // wave-uniform
+            const int pv = (int)readlane_u32((uint32_t)p, v);
+            const int dv = (int)readlane_u32((uint32_t)depth, pv) + 1;
+            const double pcv = dv <= a.D_max ? readlane_f64(pc, v) : 0.0;
+            const double rv = readlane_f64(reach, pv) * pcv;
+            if (lane == v) { depth = dv; reach = rv; }
+            if (lane == pv) kids += pcv;
+        }
+        double stay = 1.0 - kids;
+        stay = stay > 0.0 ? stay : 0.0;
+        const double pstop = (c < nn && depth <= a.D_max) ? reach * stay : 0.0;
+        double acc = 0.0;
+        for (int v = 0; v < nn; ++v) {
+            const int dv = (int)readlane_u32((uint32_t)depth, v);
+            const double sv = readlane_f64(pstop, v);
+            if (lane == dv) acc += sv;
+        }
+        for (int d = lane; d <= a.D_max; d += kWave) a.dist[(size_t)b * (a.D_max + 1) + d] = d == lane ? acc : 0.0;
+        return;
+    }
     double R = 0.0;
     int nrej = 0, rejtok = -1;                               // lane j keeps the j-th rejected token
     for (;;) {
@@ -490,16 +527,12 @@ extern "C" size_t radar_verify_accept_workspace_bytes(const radar_accept_desc *d
     return accept_layout(d->B, d->T_max, nsub, nullptr, nullptr);
 }
 
-extern "C" radar_status radar_verify_accept(const float *target_logits, const int32_t *draft_tokens,
-                                            const int32_t *parents, const int32_t *n_nodes, const float *uniforms,
-                                            int32_t *accept_len, int32_t *accept_path, int32_t *bonus_token,
-                                            const radar_accept_desc *d, void *workspace, size_t workspace_bytes,
-                                            void *stream) {
-    if (!d || !target_logits || !draft_tokens || !parents || !accept_len || !accept_path || !bonus_token || !workspace)
-        return RADAR_INVALID_ARG;
+static radar_status launch_accept(const float *target_logits, const int32_t *draft_tokens, const int32_t *parents,
+                                  const int32_t *n_nodes, const float *uniforms, int32_t *accept_len,
+                                  int32_t *accept_path, int32_t *bonus_token, double *dist, int mode,
+                                  const radar_accept_desc *d, void *workspace, size_t workspace_bytes, void *stream) {
     if (d->B < 1 || d->T_max < 1 || d->V < 1 || d->D_max < 0) return RADAR_INVALID_ARG;
-    if (d->mode != RADAR_ACCEPT_GREEDY && d->mode != RADAR_ACCEPT_SAMPLE) return RADAR_INVALID_ARG;
-    if (d->mode == RADAR_ACCEPT_SAMPLE && (!(d->temperature > 0.0f) || !uniforms)) return RADAR_INVALID_ARG;
+    if (mode != RADAR_ACCEPT_GREEDY && !(d->temperature > 0.0f)) return RADAR_INVALID_ARG;
     const int64_t nsub = ((int64_t)d->V + kAccSub - 1) / kAccSub;
     const int64_t nwg = (nsub + kAccWaves - 1) / kAccWaves;
     if (d->T_max > RADAR_T_MAX || d->D_max >= RADAR_T_MAX || d->B > 65535 || nsub > kAccMaxSubs)
@@ -509,10 +542,10 @@ extern "C" radar_status radar_verify_accept(const float *target_logits, const in
 
     AcceptArgs a;
     a.logits = target_logits; a.tokens = draft_tokens; a.parents = parents; a.n_nodes = n_nodes; a.uniforms = uniforms;
-    a.accept_len = accept_len; a.accept_path = accept_path; a.bonus = bonus_token;
-    a.B = d->B; a.T = d->T_max; a.V = d->V; a.D_max = d->D_max; a.mode = d->mode;
+    a.accept_len = accept_len; a.accept_path = accept_path; a.bonus = bonus_token; a.dist = dist;
+    a.B = d->B; a.T = d->T_max; a.V = d->V; a.D_max = d->D_max; a.mode = mode;
     a.nsub = (int)nsub; a.nwg = (int)nwg;
-    a.inv_temp = d->mode == RADAR_ACCEPT_SAMPLE ? 1.0 / (double)d->temperature : 1.0;
+    a.inv_temp = mode != RADAR_ACCEPT_GREEDY ? 1.0 / (double)d->temperature : 1.0;
     a.inv_temp_f = (float)a.inv_temp;
     a.exact_scale = ((double)a.inv_temp_f == a.inv_temp) ? 1 : 0;
     accept_layout(d->B, d->T_max, (size_t)nsub, static_cast<char *>(workspace), &a);
@@ -520,9 +553,32 @@ extern "C" radar_status radar_verify_accept(const float *target_logits, const in
     const dim3 grid((unsigned)nwg, (unsigned)d->T_max, (unsigned)d->B), block(kAccThreads);
     const bool vec4 = (d->V % 4 == 0) && (((uintptr_t)target_logits & 15) == 0);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const hipError_t e = vec4 ? launch("accept", accept_kernel<true>, grid, block, 0, st, a)
-                              : launch("accept", accept_kernel<false>, grid, block, 0, st, a);
+    const char *name = mode == kAccDistribution ? "accept_length_distribution" : "accept";
+    const hipError_t e = vec4 ? launch(name, accept_kernel<true>, grid, block, 0, st, a)
+                              : launch(name, accept_kernel<false>, grid, block, 0, st, a);
     return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
+}
+
+extern "C" radar_status radar_verify_accept(const float *target_logits, const int32_t *draft_tokens,
+                                            const int32_t *parents, const int32_t *n_nodes, const float *uniforms,
+                                            int32_t *accept_len, int32_t *accept_path, int32_t *bonus_token,
+                                            const radar_accept_desc *d, void *workspace, size_t workspace_bytes,
+                                            void *stream) {
+    if (!d || !target_logits || !draft_tokens || !parents || !accept_len || !accept_path || !bonus_token || !workspace)
+        return RADAR_INVALID_ARG;
+    if (d->mode != RADAR_ACCEPT_GREEDY && d->mode != RADAR_ACCEPT_SAMPLE) return RADAR_INVALID_ARG;
+    if (d->mode == RADAR_ACCEPT_SAMPLE && !uniforms) return RADAR_INVALID_ARG;
+    return launch_accept(target_logits, draft_tokens, parents, n_nodes, uniforms, accept_len, accept_path, bonus_token,
+                         nullptr, d->mode, d, workspace, workspace_bytes, stream);
+}
+
+extern "C" radar_status radar_accept_length_distribution(const float *target_logits, const int32_t *draft_tokens,
+                                                         const int32_t *parents, const int32_t *n_nodes, double *dist,
+                                                         const radar_accept_desc *d, void *workspace,
+                                                         size_t workspace_bytes, void *stream) {
+    if (!d || !target_logits || !draft_tokens || !parents || !dist || !workspace) return RADAR_INVALID_ARG;
+    return launch_accept(target_logits, draft_tokens, parents, n_nodes, nullptr, nullptr, nullptr, nullptr, dist,
+                         kAccDistribution, d, workspace, workspace_bytes, stream);
 }
 
 extern "C" radar_status radar_debug_validate_tree(const int32_t *parents, const int32_t *n_nodes, int32_t B,
