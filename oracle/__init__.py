@@ -16,5 +16,6 @@ from .radar_oracle import (  # noqa: F401
     verify_accept,
     accept_length_distribution,
     accept_margins,
+    policy_step,
     OracleError,
 )

@@ -14,7 +14,7 @@
  * even for attention, fp32 for scores).  Order comparisons between raw logits
  * are exact fp32 comparisons.
  *
- * The paper states the three operations in words only (it prints no listing
+ * The paper states the operations in words and formulas only (it prints no listing
  * and no worked numbers), so each function below is the plain definition of
  * the sentence it cites:
  *   - tree attention: Sec. 1 and Sec. 3 (the serialized tree is checked by the
@@ -22,7 +22,10 @@
  *   - draft expansion: Sec. 2.3 (confidence scores as proxy, reordering and
  *     pruning) and App. A.1 (k tokens -> k*k candidates -> top-k confidences);
  *   - acceptance: Sec. 3, Eq. 1 (accept probability) and Eq. 2 (residual),
- *     with the tree form implied by Sec. 4.3, Eq. 11-13.
+ *     with the tree form implied by Sec. 4.3, Eq. 11-13;
+ *   - acceptance-length distribution: Sec. 4.3, Eq. 11-13 written out;
+ *   - prediction-model step: Sec. 4.2 with the architecture of App. A.3 (the
+ *     standard LSTM cell, pinned to a library LSTM in tests/test_oracle_policy.py).
  * Parity pins: tests/test_oracle_*.py (brute force, closed forms, invariants,
  * library routines).  Fidelity to the authors' unpublished code for the points
  * the paper leaves open (root is node 0, pool contents, serialized order,
@@ -557,6 +560,88 @@ int radar_oracle_accept_margins(const float *target_logits, const int32_t *draft
         free(rejected);
         margins[2 * b] = m_acc;
         margins[2 * b + 1] = m_cdf;
+    }
+    return ORACLE_OK;
+}
+
+/* ---------------------------------------------------- prediction-model step */
+
+static double sigmoid_d(double x) { return 1.0 / (1.0 + exp(-x)); }
+
+/* One call of the prediction model (Sec. 4.2; architecture per App. A.3): a
+ * single-layer LSTM cell over the k confidences, whose new hidden vector is
+ * joined with those same k inputs and passed through a two-layer perceptron
+ * (ReLU between the layers) to two logits; softmax gives the probability of
+ * action 0 (stop drafting) and action 1 (call the draft model again), Eq. 5.
+ * The state (h, c) starts at zero at the first draft step of a cycle and is
+ * handed from call to call.
+ *
+ * The paper names the parts but not the cell's equations or a parameter
+ * layout; this is the standard LSTM cell
+ *     i = sigm(Wi x + Ui h + bi + di)   f = sigm(Wf x + Uf h + bf + df)
+ *     g = tanh(Wg x + Ug h + bg + dg)   o = sigm(Wo x + Uo h + bo + do)
+ *     c' = f*c + i*g                    h' = o * tanh(c')
+ * with the four blocks stacked in the order i, f, g, o along the rows of
+ * w_ih [4H][k], w_hh [4H][H], b_ih [4H], b_hh [4H] (two bias vectors, added),
+ * then  z = relu(w1 [h'; x] + b1),  w1 [M][H+k] with the hidden part first,
+ * logits = w2 z + b2,  w2 [2][M].  Dropout (training only) is absent.
+ *
+ * action: with uniforms == NULL, 1 iff logits[1] > logits[0] (a tie stops);
+ * otherwise 1 iff uniforms[b] < probs[1] (a draw from the policy, Eq. 5).
+ * Parameters and inputs are fp32 values, all arithmetic fp64; h_out, c_out,
+ * logits, probs are fp64.  h_in / c_in NULL means the zero state.
+ */
+int radar_oracle_policy_step(const float *conf, const float *h_in, const float *c_in,
+                             const float *w_ih, const float *w_hh, const float *b_ih, const float *b_hh,
+                             const float *w1, const float *b1, const float *w2, const float *b2,
+                             const float *uniforms, int B, int k, int H, int M,
+                             double *h_out, double *c_out, double *logits, double *probs, int32_t *action)
+{
+    if (B < 0 || k < 1 || H < 1 || M < 1) return ORACLE_BAD_ARG;
+    if (!conf || !w_ih || !w_hh || !b_ih || !b_hh || !w1 || !b1 || !w2 || !b2) return ORACLE_BAD_ARG;
+    for (int b = 0; b < B; ++b) {
+        const float *x = conf + (size_t)b * k;
+        double *gate = (double *)calloc((size_t)4 * H, sizeof(double));
+        double *hn = (double *)calloc((size_t)H, sizeof(double));
+        double *z = (double *)calloc((size_t)M, sizeof(double));
+        for (int r = 0; r < 4 * H; ++r) {
+            double a = (double)b_ih[r] + (double)b_hh[r];
+            for (int j = 0; j < k; ++j) a += (double)w_ih[(size_t)r * k + j] * (double)x[j];
+            if (h_in)
+                for (int j = 0; j < H; ++j) a += (double)w_hh[(size_t)r * H + j] * (double)h_in[(size_t)b * H + j];
+            gate[r] = a;
+        }
+        for (int u = 0; u < H; ++u) {
+            const double ig = sigmoid_d(gate[u]);
+            const double fg = sigmoid_d(gate[H + u]);
+            const double gg = tanh(gate[2 * H + u]);
+            const double og = sigmoid_d(gate[3 * H + u]);
+            const double c_prev = c_in ? (double)c_in[(size_t)b * H + u] : 0.0;
+            const double cn = fg * c_prev + ig * gg;
+            hn[u] = og * tanh(cn);
+            if (c_out) c_out[(size_t)b * H + u] = cn;
+            if (h_out) h_out[(size_t)b * H + u] = hn[u];
+        }
+        for (int m = 0; m < M; ++m) {
+            double a = (double)b1[m];
+            const float *row = w1 + (size_t)m * (H + k);
+            for (int j = 0; j < H; ++j) a += (double)row[j] * hn[j];
+            for (int j = 0; j < k; ++j) a += (double)row[H + j] * (double)x[j];
+            z[m] = a > 0.0 ? a : 0.0;
+        }
+        double l[2];
+        for (int a2 = 0; a2 < 2; ++a2) {
+            double a = (double)b2[a2];
+            for (int m = 0; m < M; ++m) a += (double)w2[(size_t)a2 * M + m] * z[m];
+            l[a2] = a;
+        }
+        const double mx = l[0] > l[1] ? l[0] : l[1];
+        const double e0 = exp(l[0] - mx), e1 = exp(l[1] - mx);
+        const double p0 = e0 / (e0 + e1), p1 = e1 / (e0 + e1);
+        if (logits) { logits[2 * b] = l[0]; logits[2 * b + 1] = l[1]; }
+        if (probs) { probs[2 * b] = p0; probs[2 * b + 1] = p1; }
+        if (action) action[b] = uniforms ? ((double)uniforms[b] < p1) : (l[1] > l[0]);
+        free(gate); free(hn); free(z);
     }
     return ORACLE_OK;
 }

@@ -179,6 +179,39 @@ def accept_length_distribution(target_logits, draft_tokens, parents, n_nodes=Non
     return dist
 
 
+def policy_step(conf, params, h=None, c=None, uniforms=None):
+    """One prediction-model call (Sec. 4.2, App. A.3).  conf float32[B,k]; params a
+    dict of float32 arrays w_ih[4H,k], w_hh[4H,H], b_ih[4H], b_hh[4H], w1[M,H+k],
+    b1[M], w2[2,M], b2[2]; h, c float32[B,H] or None (zero state); uniforms
+    float32[B] or None (argmax action).  Returns a dict of h, c float64[B,H],
+    logits, probs float64[B,2], action int32[B]."""
+    conf = _arr(conf, np.float32, name="conf")
+    B, k = conf.shape
+    w_hh = _arr(params["w_hh"], np.float32, name="w_hh")
+    H = w_hh.shape[1]
+    w_hh = _arr(w_hh, np.float32, (4 * H, H), "w_hh")
+    w_ih = _arr(params["w_ih"], np.float32, (4 * H, k), "w_ih")
+    b_ih = _arr(params["b_ih"], np.float32, (4 * H,), "b_ih")
+    b_hh = _arr(params["b_hh"], np.float32, (4 * H,), "b_hh")
+    w1 = _arr(params["w1"], np.float32, name="w1")
+    M = w1.shape[0]
+    w1 = _arr(w1, np.float32, (M, H + k), "w1")
+    b1 = _arr(params["b1"], np.float32, (M,), "b1")
+    w2 = _arr(params["w2"], np.float32, (2, M), "w2")
+    b2 = _arr(params["b2"], np.float32, (2,), "b2")
+    hh = None if h is None else _arr(h, np.float32, (B, H), "h")
+    cc = None if c is None else _arr(c, np.float32, (B, H), "c")
+    un = None if uniforms is None else _arr(uniforms, np.float32, (B,), "uniforms")
+    out = {"h": np.zeros((B, H)), "c": np.zeros((B, H)), "logits": np.zeros((B, 2)),
+           "probs": np.zeros((B, 2)), "action": np.zeros(B, np.int32)}
+    rc = _load().radar_oracle_policy_step(
+        _p(conf), _p(hh), _p(cc), _p(w_ih), _p(w_hh), _p(b_ih), _p(b_hh), _p(w1), _p(b1), _p(w2), _p(b2), _p(un),
+        ctypes.c_int(B), ctypes.c_int(k), ctypes.c_int(H), ctypes.c_int(M),
+        _p(out["h"]), _p(out["c"]), _p(out["logits"]), _p(out["probs"]), _p(out["action"]))
+    _check(rc, "radar_oracle_policy_step")
+    return out
+
+
 def accept_margins(target_logits, draft_tokens, parents, n_nodes, uniforms, temperature=1.0):
     """Distance of every sampling decision from its threshold: float64[B,2]
     (accept tests, residual inverse-CDF)."""

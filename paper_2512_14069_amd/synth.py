@@ -292,3 +292,30 @@ def expand_logits(rng, F, vocab, std, normalised=True):
         from scipy.special import log_softmax
         x = log_softmax(x, axis=-1)
     return np.ascontiguousarray(x, dtype=np.float32)
+
+
+# ------------------------------------------------- prediction-model inputs
+
+POLICY_K = 10        # inputs: the k frontier confidences (Sec. 5.1: k = 10)
+POLICY_H = 128       # LSTM hidden size (App. A.3)
+POLICY_M = 128       # hidden size of the perceptron head (App. A.3)
+
+
+def policy_params(rng, k=POLICY_K, H=POLICY_H, M=POLICY_M, gain=1.0):
+    """Random parameters of the prediction model's shape (no trained weights
+    exist here): every tensor uniform in +-gain/sqrt(fan_in), float32, in the
+    row-stacked layout the library documents (gate blocks i, f, g, o)."""
+    def u(shape, fan_in):
+        b = gain / np.sqrt(fan_in)
+        return np.ascontiguousarray(rng.uniform(-b, b, size=shape), dtype=np.float32)
+    return dict(w_ih=u((4 * H, k), H), w_hh=u((4 * H, H), H), b_ih=u((4 * H,), H), b_hh=u((4 * H,), H),
+                w1=u((M, H + k), H + k), b1=u((M,), H + k), w2=u((2, M), M), b2=u((2,), M))
+
+
+def policy_conf(rng, B, k=POLICY_K, steps=1):
+    """Confidence vectors as the expansion emits them: k values in (0, 1],
+    sorted descending, shrinking from draft step to draft step (a path's
+    probability only falls as it grows).  float32 [steps, B, k]."""
+    c = np.sort(rng.random((steps, B, k)) ** 2.0, axis=-1)[..., ::-1]
+    decay = np.cumprod(rng.uniform(0.5, 1.0, size=(steps, B, 1)), axis=0)
+    return np.ascontiguousarray(c * decay, dtype=np.float32)
