@@ -15,6 +15,9 @@
  *                        Sec. 3: one parallel target pass over the tree)
  *   radar_verify_accept  after the target pass: greedy or rejection-sampling
  *                        walk down the tree (Sec. 3, Eq. 1-2; Sec. 4.3 Eq. 13)
+ * and, around them, radar_policy_step (the prediction model's continue / stop
+ * decision after each draft call, Sec. 4.2) and
+ * radar_accept_length_distribution (Sec. 4.3, Eq. 11-13).
  *
  * Conventions for every call
  *   - Tensor arguments are DEVICE pointers owned by the caller; descriptors
@@ -243,6 +246,42 @@ radar_status radar_accept_length_distribution(const float *target_logits, const 
                                               const int32_t *parents, const int32_t *n_nodes, double *dist,
                                               const radar_accept_desc *desc,
                                               void *workspace, size_t workspace_bytes, void *stream);
+
+/* --------------------------------------------------------------------------
+ * Prediction-model step (Sec. 4.2, Eq. 3-5; architecture per App. A.3): after a
+ * draft-model call, decide from the k frontier confidences whether to call the
+ * draft model again.
+ *
+ * A single-layer LSTM cell reads x = the k confidences (frontier_conf of
+ * radar_draft_expand) and the state (h, c); the new hidden vector is joined
+ * with x and passed through a two-layer perceptron with ReLU to two logits:
+ *     [i f g o] = w_ih x + b_ih + w_hh h + b_hh      (four blocks of H rows, this order)
+ *     c' = sigm(f) * c + sigm(i) * tanh(g);   h' = sigm(o) * tanh(c')
+ *     logits = w2 relu(w1 [h'; x] + b1) + b2;   probs = softmax(logits)
+ * Index 0 is "stop drafting", index 1 "call the draft model again" (Eq. 5).
+ * action[b] = 1 iff logits[b,1] > logits[b,0] (a tie stops), or, when uniforms
+ * is given, 1 iff uniforms[b] < probs[b,1] (a draw from the policy).
+ * The state starts at zero at the first draft step of a cycle (h_in = c_in =
+ * NULL) and is handed from call to call; h_out / c_out may be h_in / c_in.
+ * Training-time dropout has no counterpart here.  All arithmetic is fp32.
+ *
+ * Parameters are DEVICE arrays of fp32 in row-major [out, in] order (the
+ * layout in which the common deep-learning toolkits keep an LSTM layer and a
+ * linear layer, so trained weights can be handed over unchanged):
+ *   w_ih [4H,k]  w_hh [4H,H]  b_ih, b_hh [4H]  w1 [M,H+k]  b1 [M]  w2 [2,M]  b2 [2]
+ * Limits: H == 128; 1 <= k <= RADAR_K_MAX; 1 <= M <= 128; w_hh 16-byte aligned.
+ * conf f32 [B,k]; h_in, c_in, h_out, c_out f32 [B,H]; logits, probs f32 [B,2];
+ * action i32 [B]; uniforms f32 [B] or NULL.  One kernel, no workspace. */
+typedef struct radar_policy_params {
+    const float *w_ih, *w_hh, *b_ih, *b_hh;   /* LSTM cell   */
+    const float *w1, *b1, *w2, *b2;           /* perceptron  */
+    int32_t k, H, M;
+} radar_policy_params;
+
+radar_status radar_policy_step(const float *conf, const float *h_in, const float *c_in,
+                               const radar_policy_params *params, const float *uniforms,
+                               float *h_out, float *c_out, float *logits, float *probs, int32_t *action,
+                               int32_t B, void *stream);
 
 /* Counts, per call, the nodes i < n_nodes[b] whose parent breaks the tree
  * convention; *bad_count_out (device i32) is overwritten.  parents i32

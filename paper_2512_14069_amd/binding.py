@@ -54,13 +54,18 @@ class AcceptDesc(ctypes.Structure):
                 ("D_max", ctypes.c_int32), ("mode", ctypes.c_int32), ("temperature", ctypes.c_float)]
 
 
+class PolicyParams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("w_ih", "w_hh", "b_ih", "b_hh", "w1", "b1", "w2", "b2")] + \
+               [("k", ctypes.c_int32), ("H", ctypes.c_int32), ("M", ctypes.c_int32)]
+
+
 EXPORTS = [
     "radar_status_string", "radar_version", "radar_workspace_init",
     "radar_tree_attention_workspace_bytes", "radar_tree_attention",
     "radar_draft_expand_workspace_bytes", "radar_draft_expand",
     "radar_draft_rerank_workspace_bytes", "radar_draft_rerank",
     "radar_verify_accept_workspace_bytes", "radar_verify_accept",
-    "radar_accept_length_distribution",
+    "radar_accept_length_distribution", "radar_policy_step",
     "radar_debug_validate_tree", "radar_profile_begin", "radar_profile_end",
 ]
 
@@ -98,6 +103,8 @@ def load():
     lib.radar_verify_accept.argtypes = [vp] * 8 + [ctypes.POINTER(AcceptDesc), vp, sz, vp]
     lib.radar_accept_length_distribution.restype = i32
     lib.radar_accept_length_distribution.argtypes = [vp] * 5 + [ctypes.POINTER(AcceptDesc), vp, sz, vp]
+    lib.radar_policy_step.restype = i32
+    lib.radar_policy_step.argtypes = [vp] * 3 + [ctypes.POINTER(PolicyParams)] + [vp] * 6 + [i32, vp]
     lib.radar_debug_validate_tree.restype = i32
     lib.radar_debug_validate_tree.argtypes = [vp, vp, i32, i32, vp, vp]
     lib.radar_profile_begin.restype = i32
@@ -374,6 +381,67 @@ def radar_accept_length_distribution(target_logits, draft_tokens, parents, n_nod
         ctypes.byref(desc), wp, wn, _stream())
     keep = (target_logits, draft_tokens, parents, n_nodes, out, desc, workspace)
     return _finish("radar_accept_length_distribution", load().radar_accept_length_distribution, args, keep, out, prepared)
+
+
+class PolicyOut:
+    """Outputs of one prediction-model call: h, c f32 [B,H]; logits, probs f32 [B,2]; action i32 [B]."""
+    __slots__ = ("h", "c", "logits", "probs", "action")
+
+    def __init__(self, B, H, device):
+        self.h = torch.empty((B, H), dtype=torch.float32, device=device)
+        self.c = torch.empty((B, H), dtype=torch.float32, device=device)
+        self.logits = torch.empty((B, 2), dtype=torch.float32, device=device)
+        self.probs = torch.empty((B, 2), dtype=torch.float32, device=device)
+        self.action = torch.empty((B,), dtype=torch.int32, device=device)
+
+
+def policy_params(tensors):
+    """Parameter block from a dict of GPU float32 tensors w_ih [4H,k], w_hh [4H,H], b_ih, b_hh [4H],
+    w1 [M,H+k], b1 [M], w2 [2,M], b2 [2].  Returns (struct, tensors kept alive)."""
+    w_hh = tensors["w_hh"]
+    H = w_hh.shape[1]
+    k = tensors["w_ih"].shape[1]
+    M = tensors["w1"].shape[0]
+    want = {"w_ih": (4 * H, k), "w_hh": (4 * H, H), "b_ih": (4 * H,), "b_hh": (4 * H,),
+            "w1": (M, H + k), "b1": (M,), "w2": (2, M), "b2": (2,)}
+    pp = PolicyParams()
+    for n, shape in want.items():
+        t = tensors[n]
+        if tuple(t.shape) != shape:
+            raise ValueError(f"{n}: expected shape {shape}, got {tuple(t.shape)}")
+        setattr(pp, n, _ptr(_dense(t, n), torch.float32, n).value)
+    pp.k, pp.H, pp.M = k, H, M
+    return pp, dict(tensors)
+
+
+def radar_policy_step(conf, params, h=None, c=None, uniforms=None, out=None, prepared=False):
+    """conf f32 [B,k] (or [k]); params from policy_params(); h, c f32 [B,H] or None (zero state);
+    uniforms f32 [B] or None (argmax action).  Returns a PolicyOut."""
+    pp, held = params
+    if conf.dim() == 1:
+        conf = conf[None]
+    B, k = conf.shape
+    if k != pp.k:
+        raise ValueError(f"conf has {k} columns, the parameters expect {pp.k}")
+    if (h is None) != (c is None):
+        raise ValueError("h and c must be given together")
+    if out is None:
+        out = PolicyOut(B, pp.H, conf.device)
+    for n, t in (("h", h), ("c", c)):
+        if t is not None and tuple(t.shape) != (B, pp.H):
+            raise ValueError(f"{n}: expected shape {(B, pp.H)}, got {tuple(t.shape)}")
+    if uniforms is not None and tuple(uniforms.shape) != (B,):
+        raise ValueError(f"uniforms: expected shape {(B,)}")
+    args = (
+        _ptr(_dense(conf, "conf"), torch.float32, "conf"),
+        _ptr(None if h is None else _dense(h, "h"), torch.float32, "h"),
+        _ptr(None if c is None else _dense(c, "c"), torch.float32, "c"),
+        ctypes.byref(pp),
+        _ptr(None if uniforms is None else _dense(uniforms, "uniforms"), torch.float32, "uniforms"),
+        _ptr(out.h, torch.float32), _ptr(out.c, torch.float32), _ptr(out.logits, torch.float32),
+        _ptr(out.probs, torch.float32), _ptr(out.action, torch.int32), B, _stream())
+    keep = (conf, h, c, uniforms, pp, held, out)
+    return _finish("radar_policy_step", load().radar_policy_step, args, keep, out, prepared)
 
 
 def radar_debug_validate_tree(parents, n_nodes=None):
