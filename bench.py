@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--attn-sets", type=int, default=64, help="distinct KV caches cycled through (9.6 MB each)")
     ap.add_argument("--cycle-sets", type=int, default=8, help="distinct logits sets cycled through (72 MB each)")
     ap.add_argument("--attn-kps", type=int, default=0, help="keys_per_split override for the attention call (0 = library's choice)")
+    ap.add_argument("--policy", default="none", choices=("none", "fused", "separate"),
+                    help="also run the prediction model after every draft call but the last (Sec. 4.2): inside the "
+                         "expansion launch ('fused') or as a launch of its own ('separate'); not part of the headline workload")
     ap.add_argument("--only", default="", help="time only 'attention', 'expand' or 'accept' (for profiling)")
     ap.add_argument("--no-marks", action="store_true", help="no stream events between the phases of a step")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -129,14 +132,31 @@ def main():
 
     # Every call of a step is marshalled once (pointers, descriptors, stream) and replayed in the
     # timed region: the host then spends one foreign call per launch and the GPU stays busy.
+    pol = pol_out = None
+    if args.policy != "none":
+        prng0 = np.random.default_rng(synth.seed_for(3, 55))
+        pol = b.policy_params({n: torch.from_numpy(v).to(dev) for n, v in synth.policy_params(prng0, k).items()})
+        pol_out = b.PolicyOut(1, synth.POLICY_H, dev)
+
     def prepare_cycle(cs):
         calls = []
         pool.count = 0
         ps, ppi = ps0, ppi0
         for s in range(steps_per_cycle):
-            c = b.radar_draft_expand(cs["draft"][s], ps, ppi, k, pool, out=exp_outs[s], workspace=exp_ws, prepared=True)
-            calls.append(c)
-            ps, ppi = c.out.frontier_scores, c.out.frontier_pool_idx
+            decide = pol is not None and s + 1 < steps_per_cycle      # no decision is needed after the last draft call
+            state = (pol_out.h, pol_out.c) if decide and s > 0 else (None, None)   # zero state at a cycle's first draft step
+            if decide and args.policy == "fused":
+                c = b.radar_draft_expand_policy(cs["draft"][s], ps, ppi, k, pool, pol, state[0], state[1], out=exp_outs[s],
+                                                policy_out=pol_out, workspace=exp_ws, prepared=True)
+                calls.append(c)
+                eo = c.out[0]
+            else:
+                c = b.radar_draft_expand(cs["draft"][s], ps, ppi, k, pool, out=exp_outs[s], workspace=exp_ws, prepared=True)
+                calls.append(c)
+                eo = c.out
+                if decide:
+                    calls.append(b.radar_policy_step(eo.frontier_conf, pol, state[0], state[1], out=pol_out, prepared=True))
+            ps, ppi = eo.frontier_scores, eo.frontier_pool_idx
         calls.append(b.radar_draft_rerank(pool, N, 1, out=tree, prepared=True))
         cs["expand_calls"] = calls
         cs["accept_call"] = b.radar_verify_accept(
@@ -264,6 +284,7 @@ def main():
         "config": {"workload": "c2_8b_verify (attention) + c3_8b_expand (8 expand calls, rerank, sampled accept)",
                    "context": A.ctx_lens[0], "tree_rows": A.T, "q_heads": A.Hq, "kv_heads": A.Hkv, "head_dim": A.D,
                    "vocab": V, "k": k, "frontier_rows": F, "expand_calls": steps_per_cycle, "rerank_N": N,
+                   "prediction_model": args.policy,
                    "cache": "cold: inputs rotate through %d MB (attention) / %d MB (logits)" % (
                        attn_bytes * len(attn_sets) // 2**20, ea_bytes * len(cycle_sets) // 2**20)},
         "attention_us": round(a_us, 2),

@@ -269,7 +269,7 @@ radar_status radar_accept_length_distribution(const float *target_logits, const 
  * layout in which the common deep-learning toolkits keep an LSTM layer and a
  * linear layer, so trained weights can be handed over unchanged):
  *   w_ih [4H,k]  w_hh [4H,H]  b_ih, b_hh [4H]  w1 [M,H+k]  b1 [M]  w2 [2,M]  b2 [2]
- * Limits: H == 128; 1 <= k <= RADAR_K_MAX; 1 <= M <= 128; w_hh 16-byte aligned.
+ * Limits: H == 128; 1 <= k <= RADAR_K_MAX; 1 <= M <= 128; w_hh, h_in 16-byte aligned.
  * conf f32 [B,k]; h_in, c_in, h_out, c_out f32 [B,H]; logits, probs f32 [B,2];
  * action i32 [B]; uniforms f32 [B] or NULL.  One kernel, no workspace. */
 typedef struct radar_policy_params {
@@ -282,6 +282,30 @@ radar_status radar_policy_step(const float *conf, const float *h_in, const float
                                const radar_policy_params *params, const float *uniforms,
                                float *h_out, float *c_out, float *logits, float *probs, int32_t *action,
                                int32_t B, void *stream);
+
+/* radar_draft_expand followed, in the same launch, by radar_policy_step on the
+ * frontier_conf it has just written (batch of one: a drafting loop has one
+ * frontier and one policy state).  Results are those of the two calls made one
+ * after the other, bit for bit; the second launch and its latency are saved
+ * (the paper's T_p, Sec. 4.2 Eq. 8-9, is mostly that).  params->k must equal
+ * desc->k.  io is a HOST struct of DEVICE pointers: h_in, c_in f32 [H] or both
+ * NULL (zero state); uniform f32 [1] or NULL (argmax action); h_out, c_out f32
+ * [H] (may be h_in, c_in); logits, probs f32 [2]; action i32 [1].  Workspace and
+ * all other arguments as for radar_draft_expand. */
+typedef struct radar_policy_io {
+    const float *h_in, *c_in, *uniform;
+    float *h_out, *c_out, *logits, *probs;
+    int32_t *action;
+} radar_policy_io;
+
+radar_status radar_draft_expand_policy(const float *logits, const float *parent_scores, const int32_t *parent_pool_idx,
+                                       int32_t *cand_tokens, float *cand_scores,
+                                       int32_t *frontier_pool_idx, int32_t *frontier_tokens,
+                                       float *frontier_scores, float *frontier_conf,
+                                       int32_t *pool_tokens, float *pool_scores, int32_t *pool_parents,
+                                       const radar_expand_desc *desc,
+                                       const radar_policy_params *params, const radar_policy_io *io,
+                                       void *workspace, size_t workspace_bytes, void *stream);
 
 /* Counts, per call, the nodes i < n_nodes[b] whose parent breaks the tree
  * convention; *bad_count_out (device i32) is overwritten.  parents i32

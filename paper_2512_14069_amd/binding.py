@@ -59,10 +59,14 @@ class PolicyParams(ctypes.Structure):
                [("k", ctypes.c_int32), ("H", ctypes.c_int32), ("M", ctypes.c_int32)]
 
 
+class PolicyIO(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("h_in", "c_in", "uniform", "h_out", "c_out", "logits", "probs", "action")]
+
+
 EXPORTS = [
     "radar_status_string", "radar_version", "radar_workspace_init",
     "radar_tree_attention_workspace_bytes", "radar_tree_attention",
-    "radar_draft_expand_workspace_bytes", "radar_draft_expand",
+    "radar_draft_expand_workspace_bytes", "radar_draft_expand", "radar_draft_expand_policy",
     "radar_draft_rerank_workspace_bytes", "radar_draft_rerank",
     "radar_verify_accept_workspace_bytes", "radar_verify_accept",
     "radar_accept_length_distribution", "radar_policy_step",
@@ -93,6 +97,9 @@ def load():
     lib.radar_draft_expand_workspace_bytes.argtypes = [ctypes.POINTER(ExpandDesc)]
     lib.radar_draft_expand.restype = i32
     lib.radar_draft_expand.argtypes = [vp] * 12 + [ctypes.POINTER(ExpandDesc), vp, sz, vp]
+    lib.radar_draft_expand_policy.restype = i32
+    lib.radar_draft_expand_policy.argtypes = [vp] * 12 + [ctypes.POINTER(ExpandDesc), ctypes.POINTER(PolicyParams),
+                                              ctypes.POINTER(PolicyIO), vp, sz, vp]
     lib.radar_draft_rerank_workspace_bytes.restype = sz
     lib.radar_draft_rerank_workspace_bytes.argtypes = [i32, i32]
     lib.radar_draft_rerank.restype = i32
@@ -288,6 +295,46 @@ def radar_draft_expand(logits, parent_scores, parent_pool_idx, k, pool, out=None
     keep = (logits, parent_scores, parent_pool_idx, out, pool, desc, workspace)
     pool.count += F * k
     return _finish("radar_draft_expand", load().radar_draft_expand, args, keep, out, prepared)
+
+
+def radar_draft_expand_policy(logits, parent_scores, parent_pool_idx, k, pool, params, h=None, c=None, uniform=None,
+                              out=None, policy_out=None, workspace=None, prepared=False):
+    """radar_draft_expand and, in the same launch, radar_policy_step on its frontier_conf.
+    params from policy_params(); h, c f32 [1,H] or None; uniform f32 [1] or None.
+    Returns (ExpandOut, PolicyOut)."""
+    F, V = logits.shape
+    pp, held = params
+    desc = expand_desc(F, V, k, pool.count, pool.capacity)
+    if out is None:
+        out = ExpandOut(F, k, logits.device)
+    if policy_out is None:
+        policy_out = PolicyOut(1, pp.H, logits.device)
+    if (h is None) != (c is None):
+        raise ValueError("h and c must be given together")
+    for n, t in (("h", h), ("c", c)):
+        if t is not None and t.numel() != pp.H:
+            raise ValueError(f"{n}: expected {pp.H} elements, got {t.numel()}")
+    if workspace is None:
+        workspace = new_workspace(radar_draft_expand_workspace_bytes(desc), logits.device)
+    io = PolicyIO()
+    val = lambda t, dt, n: None if t is None else _ptr(_dense(t, n), dt, n).value
+    io.h_in, io.c_in = val(h, torch.float32, "h"), val(c, torch.float32, "c")
+    io.uniform = val(uniform, torch.float32, "uniform")
+    io.h_out, io.c_out = policy_out.h.data_ptr(), policy_out.c.data_ptr()
+    io.logits, io.probs, io.action = policy_out.logits.data_ptr(), policy_out.probs.data_ptr(), policy_out.action.data_ptr()
+    wp, wn = _ws_args(workspace)
+    args = (
+        _ptr(_dense(logits, "logits"), torch.float32, "logits"),
+        _ptr(_dense(parent_scores, "parent_scores"), torch.float32, "parent_scores"),
+        _ptr(_dense(parent_pool_idx, "parent_pool_idx"), torch.int32, "parent_pool_idx"),
+        _ptr(out.cand_tokens, torch.int32), _ptr(out.cand_scores, torch.float32),
+        _ptr(out.frontier_pool_idx, torch.int32), _ptr(out.frontier_tokens, torch.int32),
+        _ptr(out.frontier_scores, torch.float32), _ptr(out.frontier_conf, torch.float32),
+        _ptr(pool.tokens, torch.int32), _ptr(pool.scores, torch.float32), _ptr(pool.parents, torch.int32),
+        ctypes.byref(desc), ctypes.byref(pp), ctypes.byref(io), wp, wn, _stream())
+    keep = (logits, parent_scores, parent_pool_idx, out, pool, desc, workspace, pp, held, io, h, c, uniform, policy_out)
+    pool.count += F * k
+    return _finish("radar_draft_expand_policy", load().radar_draft_expand_policy, args, keep, (out, policy_out), prepared)
 
 
 class TreeOut:

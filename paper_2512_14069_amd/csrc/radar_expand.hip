@@ -9,8 +9,11 @@
 // workgroup that finishes last; it merges every row, one wavefront per row
 // (top-k of the chunk lists, log-sum-exp in fp64, cumulative scores, pool
 // append), and picks the next frontier.  There is no second launch and no
-// host round trip.
+// host round trip.  radar_draft_expand_policy lets the same workgroup go on to
+// the prediction model's step on the k confidences it has just produced
+// (Sec. 4.2), so the continue / stop decision costs no launch of its own.
 #include "radar_topk.h"
+#include "radar_policy.h"
 #include "radar_host.h"
 
 namespace radar {
@@ -42,9 +45,12 @@ struct ExpandArgs {
     uint64_t *part_keys;        // [F][nchunks][RADAR_K_MAX] best first, 0 where a chunk has fewer
     double *part_l;             // [F][nchunks] sum of exp(x - part_m) over the chunk
     float *part_m;              // [F][nchunks] chunk maximum
+    PolicyArgs pol;             // prediction model run by the last workgroup when has_policy != 0
+    float *gate_pre;            // [4H] w_hh h of that model, computed by the first workgroups of the launch
+    int has_policy, pol_has_state;
 };
 
-struct ExpandSmem {
+struct alignas(16) ExpandSmem {
     WaveTopkSmem wtk[kExpWaves];                  // one scratch per wavefront
     uint64_t wtop[kExpWaves * 16];                // the wavefront lists of a chunk
     float wave_m[kExpWaves];
@@ -93,6 +99,54 @@ __device__ __forceinline__ uint64_t row_topk(uint64_t (&kk)[9], const uint64_t *
     return top;
 }
 
+// Next frontier: top-k of the F*k candidates in s.cand_sc by cumulative score (candidate index
+// breaks ties), by one wavefront.  conf_lds, when given, also receives the k confidences.
+__device__ __forceinline__ void select_frontier(const ExpandArgs &a, ExpandSmem &s, float *conf_lds) {
+    const int lane = lane_id();
+    const int K = a.k;
+    // ---- next frontier: top-k of the candidates by cumulative score (candidate index breaks ties)
+    const int nfs = a.F * 16;
+    uint64_t top;
+    if (nfs <= 3 * kWave) {
+        uint64_t kk[9];
+#pragma unroll
+        for (int e = 0; e < 9; ++e) kk[e] = 0;
+#pragma unroll
+        for (int e = 0; e < 3; ++e) {
+            const int i = topk_slot_of(e);
+            const float sc = s.cand_sc[min(i, nfs - 1)];
+            kk[e] = (i < nfs && (i & 15) < K) ? make_key(sc, uint32_t((i >> 4) * K + (i & 15))) : 0;
+        }
+        top = wave_topk<9>(kk, K, s.wtk[0]);
+    } else {
+        top = 0;
+        for (int c0 = 0; c0 < nfs; c0 += 8 * kWave) {
+            uint64_t kk[9];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int i = c0 + topk_slot_of(e);
+                const float sc = s.cand_sc[min(i, nfs - 1)];
+                kk[e] = (i < nfs && (i & 15) < K) ? make_key(sc, uint32_t((i >> 4) * K + (i & 15))) : 0;
+            }
+            kk[8] = top;
+            top = wave_topk<9>(kk, K, s.wtk[0]);
+        }
+    }
+    if (lane < K) {
+        const int C = a.F * K;
+        int c = (int)key_index(top);
+        if (c < 0 || c >= C) c = 0;                               // only reachable with NaN scores
+        const int fr = c / K, r = c - fr * K;
+        const float sc = s.cand_sc[fr * 16 + r];
+        a.frontier_pool_idx[lane] = a.pool_count + c;
+        a.frontier_tokens[lane] = s.cand_tok[fr * 16 + r];
+        a.frontier_scores[lane] = sc;
+        const float conf = (float)exp((double)sc);
+        a.frontier_conf[lane] = conf;
+        if (conf_lds) conf_lds[lane] = conf;
+    }
+}
+
 template <bool VEC4, int EPT>
 __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
     static_assert(EPT == 4 || EPT == 8 || EPT == 16, "EPT");
@@ -119,6 +173,12 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
             raw[g].w = row[min(idx0 + 3, a.V - 1)];
         }
     }
+    // The prediction model's input-free part (w_hh h) is shared out over the workgroups of the
+    // launch: its loads travel with the logits', its results are handed to the last workgroup
+    // through the workspace like the chunk partials.
+    if (a.has_policy && a.pol_has_state)
+        policy_hidden_rows<4>(a.pol, 0, blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y,
+                              [&](int r, float v) { store_shared_result(&a.gate_pre[r], v); });
     float x[EPT];
     uint64_t keys[EPT];
 #pragma unroll
@@ -242,47 +302,18 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
         }
     }
     __syncthreads();
-    if (w != 0) return;
-
-    // ---- next frontier: top-k of the candidates by cumulative score (candidate index breaks ties)
-    const int nfs = a.F * 16;
-    uint64_t top;
-    if (nfs <= 3 * kWave) {
-        uint64_t kk[9];
-#pragma unroll
-        for (int e = 0; e < 9; ++e) kk[e] = 0;
-#pragma unroll
-        for (int e = 0; e < 3; ++e) {
-            const int i = topk_slot_of(e);
-            const float sc = s.cand_sc[min(i, nfs - 1)];
-            kk[e] = (i < nfs && (i & 15) < K) ? make_key(sc, uint32_t((i >> 4) * K + (i & 15))) : 0;
-        }
-        top = wave_topk<9>(kk, K, s.wtk[0]);
-    } else {
-        top = 0;
-        for (int c0 = 0; c0 < nfs; c0 += 8 * kWave) {
-            uint64_t kk[9];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int i = c0 + topk_slot_of(e);
-                const float sc = s.cand_sc[min(i, nfs - 1)];
-                kk[e] = (i < nfs && (i & 15) < K) ? make_key(sc, uint32_t((i >> 4) * K + (i & 15))) : 0;
-            }
-            kk[8] = top;
-            top = wave_topk<9>(kk, K, s.wtk[0]);
-        }
+    if (!a.has_policy) {
+        if (w == 0) select_frontier(a, s, nullptr);
+        return;
     }
-    if (lane < K) {
-        const int C = a.F * K;
-        int c = (int)key_index(top);
-        if (c < 0 || c >= C) c = 0;                               // only reachable with NaN scores
-        const int fr = c / K, r = c - fr * K;
-        const float sc = s.cand_sc[fr * 16 + r];
-        a.frontier_pool_idx[lane] = a.pool_count + c;
-        a.frontier_tokens[lane] = s.cand_tok[fr * 16 + r];
-        a.frontier_scores[lane] = sc;
-        a.frontier_conf[lane] = (float)exp((double)sc);
-    }
+    // ---- prediction-model step on the new frontier's confidences.  Its LDS reuses the
+    // selection scratch of wavefronts 1.., idle since the barrier above; the other wavefronts
+    // fetch the model's operands while wavefront 0 still selects the frontier.
+    static_assert(sizeof(PolicySmem) <= (kExpWaves - 1) * sizeof(WaveTopkSmem) && sizeof(WaveTopkSmem) % 16 == 0, "policy LDS overlay");
+    PolicySmem &ps = *reinterpret_cast<PolicySmem *>(&s.wtk[1]);
+    policy_step_block<true>(
+        a.pol, 0, a.pol_has_state != 0, ps, [&](int row) { return load_shared_result(&a.gate_pre[row]); },
+        [&] { select_frontier(a, s, ps.x); });
 }
 
 // ------------------------------------------------------------------ rerank
@@ -387,15 +418,18 @@ extern "C" size_t radar_draft_expand_workspace_bytes(const radar_expand_desc *d)
     size_t bytes = kCounterBytes;
     bytes += (size_t)d->F * nchunks * RADAR_K_MAX * sizeof(uint64_t);
     bytes += (size_t)d->F * nchunks * (sizeof(double) + sizeof(float));
+    bytes = ((bytes + 255) & ~size_t(255)) + 4 * kPolH * sizeof(float);      // w_hh h of the fused prediction model
     return (bytes + 255) & ~size_t(255);
 }
 
-extern "C" radar_status radar_draft_expand(const float *logits, const float *parent_scores,
-                                           const int32_t *parent_pool_idx, int32_t *cand_tokens, float *cand_scores,
-                                           int32_t *frontier_pool_idx, int32_t *frontier_tokens,
-                                           float *frontier_scores, float *frontier_conf, int32_t *pool_tokens,
-                                           float *pool_scores, int32_t *pool_parents, const radar_expand_desc *d,
-                                           void *workspace, size_t workspace_bytes, void *stream) {
+namespace radar { radar_status policy_args_from(const radar_policy_params *pp, PolicyArgs *out); }
+
+static radar_status launch_expand(const float *logits, const float *parent_scores,
+                                  const int32_t *parent_pool_idx, int32_t *cand_tokens, float *cand_scores,
+                                  int32_t *frontier_pool_idx, int32_t *frontier_tokens,
+                                  float *frontier_scores, float *frontier_conf, int32_t *pool_tokens,
+                                  float *pool_scores, int32_t *pool_parents, const radar_expand_desc *d,
+                                  const PolicyArgs *pol, void *workspace, size_t workspace_bytes, void *stream) {
     if (!d || !logits || !parent_scores || !parent_pool_idx || !cand_tokens || !cand_scores || !frontier_pool_idx ||
         !frontier_tokens || !frontier_scores || !frontier_conf || !pool_tokens || !pool_scores || !pool_parents ||
         !workspace)
@@ -423,6 +457,10 @@ extern "C" radar_status radar_draft_expand(const float *logits, const float *par
     const size_t nslots = (size_t)d->F * nchunks;
     a.part_l = reinterpret_cast<double *>(ws + kCounterBytes + nslots * RADAR_K_MAX * sizeof(uint64_t));
     a.part_m = reinterpret_cast<float *>(ws + kCounterBytes + nslots * (RADAR_K_MAX * sizeof(uint64_t) + sizeof(double)));
+    a.gate_pre = reinterpret_cast<float *>(ws + radar_draft_expand_workspace_bytes(d) - ((4 * kPolH * sizeof(float) + 255) & ~size_t(255)));
+    a.pol = pol ? *pol : PolicyArgs{};
+    a.has_policy = pol ? 1 : 0;
+    a.pol_has_state = (pol && pol->h_in) ? 1 : 0;
 
     const dim3 grid((unsigned)nchunks, (unsigned)d->F), block(kExpThreads);
     const bool vec4 = (d->V % 4 == 0) && (((uintptr_t)logits & 15) == 0);
@@ -435,6 +473,38 @@ extern "C" radar_status radar_draft_expand(const float *logits, const float *par
     else               e = vec4 ? launch("expand", expand_kernel<true, 16>, grid, block, 0, st, a)
                                 : launch("expand", expand_kernel<false, 16>, grid, block, 0, st, a);
     return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
+}
+
+extern "C" radar_status radar_draft_expand(const float *logits, const float *parent_scores,
+                                           const int32_t *parent_pool_idx, int32_t *cand_tokens, float *cand_scores,
+                                           int32_t *frontier_pool_idx, int32_t *frontier_tokens,
+                                           float *frontier_scores, float *frontier_conf, int32_t *pool_tokens,
+                                           float *pool_scores, int32_t *pool_parents, const radar_expand_desc *d,
+                                           void *workspace, size_t workspace_bytes, void *stream) {
+    return launch_expand(logits, parent_scores, parent_pool_idx, cand_tokens, cand_scores, frontier_pool_idx,
+                         frontier_tokens, frontier_scores, frontier_conf, pool_tokens, pool_scores, pool_parents, d,
+                         nullptr, workspace, workspace_bytes, stream);
+}
+
+extern "C" radar_status radar_draft_expand_policy(const float *logits, const float *parent_scores,
+                                                  const int32_t *parent_pool_idx, int32_t *cand_tokens,
+                                                  float *cand_scores, int32_t *frontier_pool_idx,
+                                                  int32_t *frontier_tokens, float *frontier_scores,
+                                                  float *frontier_conf, int32_t *pool_tokens, float *pool_scores,
+                                                  int32_t *pool_parents, const radar_expand_desc *d,
+                                                  const radar_policy_params *params, const radar_policy_io *io,
+                                                  void *workspace, size_t workspace_bytes, void *stream) {
+    PolicyArgs pa;
+    const radar_status st = policy_args_from(params, &pa);
+    if (st != RADAR_OK) return st;
+    if (!d || !io || !io->h_out || !io->c_out || !io->logits || !io->probs || !io->action) return RADAR_INVALID_ARG;
+    if ((io->h_in == nullptr) != (io->c_in == nullptr) || ((uintptr_t)io->h_in & 15) != 0) return RADAR_INVALID_ARG;
+    if (params->k != d->k) return RADAR_INVALID_ARG;               // the model reads exactly the k confidences
+    pa.h_in = io->h_in; pa.c_in = io->c_in; pa.uniforms = io->uniform;
+    pa.h_out = io->h_out; pa.c_out = io->c_out; pa.logits = io->logits; pa.probs = io->probs; pa.action = io->action;
+    return launch_expand(logits, parent_scores, parent_pool_idx, cand_tokens, cand_scores, frontier_pool_idx,
+                         frontier_tokens, frontier_scores, frontier_conf, pool_tokens, pool_scores, pool_parents, d,
+                         &pa, workspace, workspace_bytes, stream);
 }
 
 extern "C" size_t radar_draft_rerank_workspace_bytes(int32_t pool_count, int32_t N) {

@@ -118,3 +118,78 @@ def test_prepared_call_and_argument_errors(oracle):
     bad = synth.policy_params(rng, 10, 128, 200)                     # M beyond the limit
     with pytest.raises(b.RadarError):
         b.radar_policy_step(dev(conf), dev_params(b, bad))
+
+
+@pytest.mark.parametrize("F,V,k,with_state", [(1, 128256, 10, False), (10, 128256, 10, True), (10, 32000, 10, True),
+                                              (3, 5000, 4, True), (64, 4099, 16, True), (2, 300000, 10, False)])
+def test_expansion_with_policy_equals_the_two_calls(oracle, F, V, k, with_state):
+    """One launch (expansion, then the model on the confidences still on chip) gives bit for bit what
+    radar_draft_expand followed by radar_policy_step gives, and agrees with the oracle chain."""
+    from paper_2512_14069_amd import binding as b
+    rng = np.random.default_rng(synth.seed_for(23, F + V + k))
+    p = synth.policy_params(rng, k, 128, 128, 2.0)
+    pp = dev_params(b, p)
+    logits = synth.expand_logits(rng, F, V, 2.0)
+    ps = (-rng.random(F) * 3).astype(np.float32)
+    pidx = np.arange(F, dtype=np.int32) - (1 if F == 1 else 0)
+    h0 = rng.uniform(-1, 1, (1, 128)).astype(np.float32) if with_state else None
+    c0 = rng.standard_normal((1, 128)).astype(np.float32) if with_state else None
+    u = rng.random(1, dtype=np.float32)
+    dl, dps, dpi = dev(logits), dev(ps), dev(pidx)
+    dh, dc = (dev(h0), dev(c0)) if with_state else (None, None)
+    for uni in (None, u):
+        du = None if uni is None else dev(uni)
+        pool_a, pool_b = b.DraftPool(F * k + 7), b.DraftPool(F * k + 7)
+        pool_a.count = pool_b.count = 7
+        ea = b.radar_draft_expand(dl, dps, dpi, k, pool_a)
+        pa = b.radar_policy_step(ea.frontier_conf, pp, dh, dc, du)
+        eb, pb = b.radar_draft_expand_policy(dl, dps, dpi, k, pool_b, pp, dh, dc, du)
+        torch.cuda.synchronize()
+        for n in ("cand_tokens", "cand_scores", "frontier_pool_idx", "frontier_tokens", "frontier_scores", "frontier_conf"):
+            assert torch.equal(getattr(ea, n), getattr(eb, n)), n
+        for n in ("tokens", "scores", "parents"):
+            assert torch.equal(getattr(pool_a, n)[7:], getattr(pool_b, n)[7:]), n
+        for n in ("h", "c", "logits", "probs", "action"):
+            assert torch.equal(getattr(pa, n), getattr(pb, n)), n
+        # oracle chain: its own expansion, its own confidences
+        opool = dict(tokens=np.zeros(F * k + 7, np.int32), scores=np.zeros(F * k + 7, np.float32),
+                     parents=np.zeros(F * k + 7, np.int32))
+        oe = oracle.draft_expand(logits, ps, pidx, k, opool, 7)
+        assert np.array_equal(host(eb.frontier_tokens), oe["frontier_tokens"])
+        ref = oracle.policy_step(oe["frontier_conf"][None], p, h0, c0, uni)
+        compare(ref, pb, uni)
+
+
+def test_drafting_loop_with_fused_policy_on_one_workspace(oracle):
+    """Eight draft steps as the paper runs them (k = 10, F = 1 then 10): the state stays on the
+    device and is updated in place; one workspace and one pool serve every step."""
+    from paper_2512_14069_amd import binding as b
+    k, V, steps = 10, 32000, 8
+    rng = np.random.default_rng(synth.seed_for(23, 1))
+    p = synth.policy_params(rng, k, 128, 128, 2.0)
+    pp = dev_params(b, p)
+    pool = b.DraftPool(k + (steps - 1) * k * k)
+    opool = dict(tokens=np.zeros(pool.capacity, np.int32), scores=np.zeros(pool.capacity, np.float32),
+                 parents=np.zeros(pool.capacity, np.int32))
+    ws = b.new_workspace(b.radar_draft_expand_workspace_bytes(b.expand_desc(k, V, k, 0, pool.capacity)))
+    pout = b.PolicyOut(1, 128, "cuda")
+    ps, pidx = np.zeros(1, np.float32), np.full(1, -1, np.int32)
+    dps, dpi = dev(ps), dev(pidx)
+    h = c = None
+    ocount = 0
+    for t in range(steps):
+        F = 1 if t == 0 else k
+        logits = synth.expand_logits(rng, F, V, 2.0)
+        oe = oracle.draft_expand(logits, ps, pidx, k, opool, ocount)
+        ocount += F * k
+        ref = oracle.policy_step(oe["frontier_conf"][None], p, h, c)
+        eo, po = b.radar_draft_expand_policy(dev(logits), dps, dpi, k, pool, pp, None if t == 0 else pout.h,
+                                             None if t == 0 else pout.c, policy_out=pout, workspace=ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(eo.frontier_tokens), oe["frontier_tokens"])
+        assert np.array_equal(host(eo.frontier_pool_idx), oe["frontier_pool_idx"])
+        compare(ref, po)
+        ps, pidx = oe["frontier_scores"], oe["frontier_pool_idx"]
+        dps, dpi = eo.frontier_scores, eo.frontier_pool_idx
+        h, c = ref["h"].astype(np.float32), ref["c"].astype(np.float32)
+    assert pool.count == ocount
