@@ -17,5 +17,6 @@ from .radar_oracle import (  # noqa: F401
     accept_length_distribution,
     accept_margins,
     policy_step,
+    verify_accept_q,
     OracleError,
 )

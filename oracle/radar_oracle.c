@@ -645,3 +645,115 @@ int radar_oracle_policy_step(const float *conf, const float *h_in, const float *
     }
     return ORACLE_OK;
 }
+
+/* ------------------------------------- verification with draft distributions
+ *
+ * Sec. 3, Eq. 1-2 as printed: every drafted token was DRAWN from a draft
+ * distribution q, is accepted with probability min(1, p(x)/q(x)), and after a
+ * rejection the target distribution is replaced by the normalised positive part
+ * of p - q.  On a tree the rule is applied child by child to the running
+ * residual (the paper states the chain; this is the reading for several
+ * children, the one that keeps the output distributed exactly as p):
+ *
+ *   at node v:  r = p_v = softmax(target row v / temperature)
+ *   for each child c of v, ascending node index, x = tok_c,
+ *       q_c = softmax(draft row q_rows[c] / draft_temperature):
+ *       accept c  iff  uniforms[c] * q_c(x) < r(x)        (prob. min(1, r(x)/q_c(x)))
+ *       else          r = max(0, r - q_c) / sum_x max(0, r(x) - q_c(x))       (Eq. 2)
+ *   none accepted (or a leaf, or depth D_max reached): the bonus token is the
+ *   inverse CDF of r at uniforms[T], scanning token ids upwards.
+ *
+ * The code keeps the unnormalised residual u (r = u / W, W = sum u), so that
+ * the test reads uniforms[c] * W * q_c(x) < u(x) and a rejection is
+ * u = max(0, u - W q_c).  Should W reach 0 (p fully covered, possible only
+ * through rounding) the bonus is drawn from p_v itself.
+ *
+ * draft_logits f32 [B][Tq][V]; q_rows i32 [B][T] (row of draft_logits for each
+ * node; entry 0 unused) or NULL (Tq == T, row c for node c).
+ * margins f64 [B][2] or NULL: smallest |uniforms[c] * W * q - u| / (W * max(q, tiny))
+ * over the tests taken, i.e. the distance of a uniform from its threshold, and the
+ * distance of the bonus draw from the nearest CDF step, relative to W.
+ */
+int radar_oracle_verify_accept_q(const float *target_logits, const float *draft_logits, const int32_t *q_rows,
+                                 const int32_t *draft_tokens, const int32_t *parents, const int32_t *n_nodes,
+                                 const float *uniforms, int B, int T, int Tq, int V, int D_max,
+                                 float temperature, float draft_temperature,
+                                 int32_t *accept_len, int32_t *accept_path, int32_t *bonus_token, double *margins)
+{
+    if (B < 0 || T < 1 || Tq < 1 || V < 1 || D_max < 0) return ORACLE_BAD_ARG;
+    if (!(temperature > 0.0f) || !(draft_temperature > 0.0f) || !uniforms) return ORACLE_BAD_ARG;
+    if (!q_rows && Tq != T) return ORACLE_BAD_ARG;
+    int status = ORACLE_OK;
+#pragma omp parallel for schedule(dynamic)
+    for (int b = 0; b < B; ++b) {
+        const int nn = n_nodes ? n_nodes[b] : T;
+        const int32_t *par = parents + (size_t)b * T;
+        const int32_t *tok = draft_tokens + (size_t)b * T;
+        const float *un = uniforms + (size_t)b * (T + 1);
+        int32_t *path = accept_path + (size_t)b * (D_max + 1);
+        for (int d = 0; d <= D_max; ++d) path[d] = -1;
+        accept_len[b] = 0;
+        bonus_token[b] = -1;
+        double m_acc = INFINITY, m_cdf = INFINITY;
+        if (margins) { margins[2 * b] = m_acc; margins[2 * b + 1] = m_cdf; }
+        if (nn < 1 || nn > T) { status = ORACLE_BAD_ARG; continue; }
+        double *u = (double *)malloc((size_t)V * sizeof(double));
+        double *q = (double *)malloc((size_t)V * sizeof(double));
+        const double inv_t = 1.0 / (double)temperature, inv_td = 1.0 / (double)draft_temperature;
+        int cur = 0, len = 0;
+        path[0] = 0;
+        for (;;) {
+            const float *x = target_logits + ((size_t)b * T + cur) * V;
+            const double lse = row_lse(x, V, inv_t);
+            for (int t = 0; t < V; ++t) u[t] = exp((double)x[t] * inv_t - lse);
+            double W = 1.0;
+            int next = -1;
+            for (int c = cur + 1; c < nn && len < D_max; ++c) {
+                if (par[c] != cur) continue;
+                const int xr = tok[c];
+                const int row = q_rows ? q_rows[(size_t)b * T + c] : c;
+                if (xr < 0 || xr >= V || row < 0 || row >= Tq) { status = ORACLE_BAD_ARG; continue; }
+                const float *y = draft_logits + ((size_t)b * Tq + row) * V;
+                const double lse_q = row_lse(y, V, inv_td);
+                for (int t = 0; t < V; ++t) q[t] = exp((double)y[t] * inv_td - lse_q);
+                const double lhs = (double)un[c] * W * q[xr];
+                const double denom = W * (q[xr] > 1e-300 ? q[xr] : 1e-300);
+                if (fabs(lhs - u[xr]) / denom < m_acc) m_acc = fabs(lhs - u[xr]) / denom;
+                if (lhs < u[xr]) { next = c; break; }
+                double Wn = 0.0;
+                for (int t = 0; t < V; ++t) {
+                    const double r = u[t] - W * q[t];
+                    u[t] = r > 0.0 ? r : 0.0;
+                    Wn += u[t];
+                }
+                W = Wn;
+                if (!(W > 0.0)) break;
+            }
+            if (next >= 0) { cur = next; path[++len] = cur; continue; }
+            if (!(W > 0.0)) {                                  /* covered completely: fall back to p_v */
+                for (int t = 0; t < V; ++t) u[t] = exp((double)x[t] * inv_t - lse);
+                W = 1.0;
+            }
+            const double target = (double)un[T] * W;
+            double cdf = 0.0;
+            int pick = -1, last_pos = -1;
+            for (int t = 0; t < V; ++t) {
+                if (u[t] > 0.0) last_pos = t;
+                const double before = cdf;
+                cdf += u[t];
+                if (cdf > target) {
+                    pick = t;
+                    const double d1 = (cdf - target) / W, d0 = (target - before) / W;
+                    m_cdf = d1 < d0 ? d1 : d0;
+                    break;
+                }
+            }
+            bonus_token[b] = pick >= 0 ? pick : last_pos;
+            break;
+        }
+        accept_len[b] = len;
+        if (margins) { margins[2 * b] = m_acc; margins[2 * b + 1] = m_cdf; }
+        free(u); free(q);
+    }
+    return status;
+}

@@ -179,6 +179,37 @@ def accept_length_distribution(target_logits, draft_tokens, parents, n_nodes=Non
     return dist
 
 
+def verify_accept_q(target_logits, draft_logits, draft_tokens, parents, n_nodes=None, uniforms=None, q_rows=None,
+                    temperature=1.0, draft_temperature=1.0, D_max=None, want_margins=False):
+    """Sec. 3, Eq. 1-2 with draft distributions.  target_logits float32[B,T,V]; draft_logits
+    float32[B,Tq,V]; q_rows int32[B,T] or None (Tq == T); uniforms float32[B,T+1].
+    Returns (accept_len[B], accept_path[B,D_max+1], bonus_token[B]) and, with want_margins,
+    margins float64[B,2]."""
+    target_logits = _arr(target_logits, np.float32, name="target_logits")
+    B, T, V = target_logits.shape
+    draft_logits = _arr(draft_logits, np.float32, name="draft_logits")
+    Tq = draft_logits.shape[1]
+    draft_logits = _arr(draft_logits, np.float32, (B, Tq, V), "draft_logits")
+    draft_tokens = _arr(draft_tokens, np.int32, (B, T), "draft_tokens")
+    parents = _arr(parents, np.int32, (B, T), "parents")
+    nn = None if n_nodes is None else _arr(n_nodes, np.int32, (B,), "n_nodes")
+    qr = None if q_rows is None else _arr(q_rows, np.int32, (B, T), "q_rows")
+    un = _arr(uniforms, np.float32, (B, T + 1), "uniforms")
+    if D_max is None:
+        D_max = T - 1
+    accept_len = np.zeros(B, np.int32)
+    path = np.zeros((B, D_max + 1), np.int32)
+    bonus = np.zeros(B, np.int32)
+    m = np.zeros((B, 2), np.float64) if want_margins else None
+    rc = _load().radar_oracle_verify_accept_q(
+        _p(target_logits), _p(draft_logits), _p(qr), _p(draft_tokens), _p(parents), _p(nn), _p(un),
+        ctypes.c_int(B), ctypes.c_int(T), ctypes.c_int(Tq), ctypes.c_int(V), ctypes.c_int(D_max),
+        ctypes.c_float(temperature), ctypes.c_float(draft_temperature),
+        _p(accept_len), _p(path), _p(bonus), _p(m))
+    _check(rc, "radar_oracle_verify_accept_q")
+    return (accept_len, path, bonus, m) if want_margins else (accept_len, path, bonus)
+
+
 def policy_step(conf, params, h=None, c=None, uniforms=None):
     """One prediction-model call (Sec. 4.2, App. A.3).  conf float32[B,k]; params a
     dict of float32 arrays w_ih[4H,k], w_hh[4H,H], b_ih[4H], b_hh[4H], w1[M,H+k],

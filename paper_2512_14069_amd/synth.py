@@ -319,3 +319,43 @@ def policy_conf(rng, B, k=POLICY_K, steps=1):
     c = np.sort(rng.random((steps, B, k)) ** 2.0, axis=-1)[..., ::-1]
     decay = np.cumprod(rng.uniform(0.5, 1.0, size=(steps, B, 1)), axis=0)
     return np.ascontiguousarray(c * decay, dtype=np.float32)
+
+
+# ------------------------------------------- sampled drafts (general-q verify)
+
+def sampled_draft_inputs(rng, parents_list, vocab, T, std=2.0, noise=1.0, shared_rows=True):
+    """Inputs for verification with draft distributions (Sec. 3, Eq. 1-2): a batch of trees whose
+    tokens were DRAWN from draft distributions.  Target rows are N(0, std) logits; the draft
+    distribution under a node is the target row of that node plus N(0, noise) (a draft model that
+    tracks the target loosely).  shared_rows: the children of a node share one draft row (they
+    are i.i.d. draws from it; q_rows maps each child to its parent's row), else every child has
+    a row of its own.  Token draws use scipy's softmax and numpy's choice: input preparation,
+    the draft stage itself is outside the path.
+
+    parents_list: one int32 parent array per sequence (length <= T).
+    Returns dict(target_logits [B,T,V], draft_logits [B,T,V], q_rows [B,T], draft_tokens [B,T],
+    parents [B,T], n_nodes [B], uniforms [B,T+1])."""
+    from scipy.special import softmax
+    B = len(parents_list)
+    tl = normal_logits(rng, (B, T, vocab), std)
+    dl = np.zeros((B, T, vocab), np.float32)
+    q_rows = np.zeros((B, T), np.int32)
+    tokens = np.zeros((B, T), np.int32)
+    parents = np.full((B, T), -1, np.int32)
+    n_nodes = np.zeros(B, np.int32)
+    for b, par in enumerate(parents_list):
+        n = len(par)
+        n_nodes[b] = n
+        parents[b, :n] = par
+        tokens[b, 0] = int(rng.integers(0, vocab))
+        for c in range(1, n):
+            p = int(par[c])
+            row = p if shared_rows else c
+            q_rows[b, c] = row
+            if not dl[b, row].any():
+                dl[b, row] = tl[b, p] + normal_logits(rng, (vocab,), noise)
+            q = softmax(dl[b, row].astype(np.float64))
+            tokens[b, c] = int(rng.choice(vocab, p=q))
+    uniforms = rng.random((B, T + 1), dtype=np.float32)
+    return dict(target_logits=tl, draft_logits=dl, q_rows=q_rows, draft_tokens=tokens, parents=parents,
+                n_nodes=n_nodes, uniforms=uniforms)
