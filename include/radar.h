@@ -248,6 +248,45 @@ radar_status radar_accept_length_distribution(const float *target_logits, const 
                                               void *workspace, size_t workspace_bytes, void *stream);
 
 /* --------------------------------------------------------------------------
+ * Verification with draft distributions (Sec. 3, Eq. 1-2 as printed): for
+ * trees whose tokens were DRAWN from the draft model's distributions rather
+ * than picked as its top-k.  With p_v = softmax(target row v / temperature),
+ * q_c = softmax(draft row q_rows[c] / draft_temperature) the distribution node
+ * c's token was drawn from, and r the running residual at node v (r = p_v at
+ * first):
+ *   for each child c of v in ascending node index, x = its token:
+ *     accept c  iff  uniforms[b,c] * q_c(x) < r(x)          (probability min(1, r(x)/q_c(x)), Eq. 1)
+ *     otherwise     r <- max(0, r - q_c), renormalised       (Eq. 2)
+ *   when no child is accepted (or v is a leaf, or the walk is D_max deep) the
+ *   bonus token is the inverse CDF of r at uniforms[b,T_max], scanning token ids
+ *   upwards.  Should the residual vanish (p_v <= the rejected proposals
+ *   everywhere, possible only through rounding) the bonus is drawn from p_v.
+ * On a chain this is exactly the paper's procedure; for several children it is
+ * the recursive form that keeps the emitted tokens distributed as the target's.
+ * Children may repeat a token.  Outputs as for radar_verify_accept.
+ *
+ * target_logits f32 [B,T_max,V]; draft_logits f32 [B,Tq,V]; q_rows i32 [B,T_max]
+ * (row of draft_logits per node, entry 0 unused; siblings drawn from one
+ * distribution may share a row) or NULL (Tq == T_max, node c uses row c);
+ * draft_tokens, parents i32 [B,T_max]; n_nodes i32 [B] or NULL; uniforms f32
+ * [B,T_max+1].  Nodes whose token or draft row is out of range are skipped.
+ * Limits: T_max <= RADAR_T_MAX; V <= 1048576; B * (T_max + Tq) <= 65535;
+ *         both temperatures > 0.  Two kernels are enqueued. */
+typedef struct radar_accept_q_desc {
+    int32_t B, T_max, Tq, V, D_max;
+    float   temperature, draft_temperature;
+} radar_accept_q_desc;
+
+size_t radar_verify_accept_q_workspace_bytes(const radar_accept_q_desc *desc);
+
+radar_status radar_verify_accept_q(const float *target_logits, const float *draft_logits, const int32_t *q_rows,
+                                   const int32_t *draft_tokens, const int32_t *parents, const int32_t *n_nodes,
+                                   const float *uniforms,
+                                   int32_t *accept_len, int32_t *accept_path, int32_t *bonus_token,
+                                   const radar_accept_q_desc *desc,
+                                   void *workspace, size_t workspace_bytes, void *stream);
+
+/* --------------------------------------------------------------------------
  * Prediction-model step (Sec. 4.2, Eq. 3-5; architecture per App. A.3): after a
  * draft-model call, decide from the k frontier confidences whether to call the
  * draft model again.

@@ -54,6 +54,11 @@ class AcceptDesc(ctypes.Structure):
                 ("D_max", ctypes.c_int32), ("mode", ctypes.c_int32), ("temperature", ctypes.c_float)]
 
 
+class AcceptQDesc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("T_max", ctypes.c_int32), ("Tq", ctypes.c_int32), ("V", ctypes.c_int32),
+                ("D_max", ctypes.c_int32), ("temperature", ctypes.c_float), ("draft_temperature", ctypes.c_float)]
+
+
 class PolicyParams(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in ("w_ih", "w_hh", "b_ih", "b_hh", "w1", "b1", "w2", "b2")] + \
                [("k", ctypes.c_int32), ("H", ctypes.c_int32), ("M", ctypes.c_int32)]
@@ -70,6 +75,7 @@ EXPORTS = [
     "radar_draft_rerank_workspace_bytes", "radar_draft_rerank",
     "radar_verify_accept_workspace_bytes", "radar_verify_accept",
     "radar_accept_length_distribution", "radar_policy_step",
+    "radar_verify_accept_q_workspace_bytes", "radar_verify_accept_q",
     "radar_debug_validate_tree", "radar_profile_begin", "radar_profile_end",
 ]
 
@@ -110,6 +116,10 @@ def load():
     lib.radar_verify_accept.argtypes = [vp] * 8 + [ctypes.POINTER(AcceptDesc), vp, sz, vp]
     lib.radar_accept_length_distribution.restype = i32
     lib.radar_accept_length_distribution.argtypes = [vp] * 5 + [ctypes.POINTER(AcceptDesc), vp, sz, vp]
+    lib.radar_verify_accept_q_workspace_bytes.restype = sz
+    lib.radar_verify_accept_q_workspace_bytes.argtypes = [ctypes.POINTER(AcceptQDesc)]
+    lib.radar_verify_accept_q.restype = i32
+    lib.radar_verify_accept_q.argtypes = [vp] * 10 + [ctypes.POINTER(AcceptQDesc), vp, sz, vp]
     lib.radar_policy_step.restype = i32
     lib.radar_policy_step.argtypes = [vp] * 3 + [ctypes.POINTER(PolicyParams)] + [vp] * 6 + [i32, vp]
     lib.radar_debug_validate_tree.restype = i32
@@ -403,6 +413,52 @@ def radar_verify_accept(target_logits, draft_tokens, parents, n_nodes=None, unif
         ctypes.byref(desc), wp, wn, _stream())
     keep = (target_logits, draft_tokens, parents, n_nodes, uniforms, out, desc, workspace)
     return _finish("radar_verify_accept", load().radar_verify_accept, args, keep, out, prepared)
+
+
+def accept_q_desc(B, T, Tq, V, D_max, temperature=1.0, draft_temperature=1.0):
+    d = AcceptQDesc()
+    d.B, d.T_max, d.Tq, d.V, d.D_max, d.temperature, d.draft_temperature = B, T, Tq, V, D_max, temperature, draft_temperature
+    return d
+
+
+def radar_verify_accept_q_workspace_bytes(desc):
+    return int(load().radar_verify_accept_q_workspace_bytes(ctypes.byref(desc)))
+
+
+def radar_verify_accept_q(target_logits, draft_logits, draft_tokens, parents, n_nodes=None, uniforms=None, q_rows=None,
+                          temperature=1.0, draft_temperature=1.0, D_max=None, out=None, workspace=None, prepared=False):
+    """target_logits f32 [B,T,V]; draft_logits f32 [B,Tq,V]; q_rows i32 [B,T] or None (Tq == T);
+    draft_tokens, parents i32 [B,T]; n_nodes i32 [B] or None; uniforms f32 [B,T+1].
+    Returns (accept_len [B], accept_path [B,D_max+1], bonus_token [B])."""
+    B, T, V = target_logits.shape
+    Tq = draft_logits.shape[1]
+    if tuple(draft_logits.shape) != (B, Tq, V):
+        raise ValueError(f"draft_logits: expected shape {(B, Tq, V)}, got {tuple(draft_logits.shape)}")
+    if uniforms is None or tuple(uniforms.shape) != (B, T + 1):
+        raise ValueError(f"uniforms: expected shape {(B, T + 1)}")
+    if D_max is None:
+        D_max = T - 1
+    desc = accept_q_desc(B, T, Tq, V, D_max, temperature, draft_temperature)
+    dev = target_logits.device
+    if out is None:
+        out = (torch.empty(B, dtype=torch.int32, device=dev),
+               torch.empty((B, D_max + 1), dtype=torch.int32, device=dev),
+               torch.empty(B, dtype=torch.int32, device=dev))
+    if workspace is None:
+        workspace = new_workspace(radar_verify_accept_q_workspace_bytes(desc), dev)
+    wp, wn = _ws_args(workspace)
+    args = (
+        _ptr(_dense(target_logits, "target_logits"), torch.float32, "target_logits"),
+        _ptr(_dense(draft_logits, "draft_logits"), torch.float32, "draft_logits"),
+        _ptr(None if q_rows is None else _dense(q_rows, "q_rows"), torch.int32, "q_rows"),
+        _ptr(_dense(draft_tokens, "draft_tokens"), torch.int32, "draft_tokens"),
+        _ptr(_dense(parents, "parents"), torch.int32, "parents"),
+        _ptr(None if n_nodes is None else _dense(n_nodes, "n_nodes"), torch.int32, "n_nodes"),
+        _ptr(_dense(uniforms, "uniforms"), torch.float32, "uniforms"),
+        _ptr(out[0], torch.int32), _ptr(out[1], torch.int32), _ptr(out[2], torch.int32),
+        ctypes.byref(desc), wp, wn, _stream())
+    keep = (target_logits, draft_logits, q_rows, draft_tokens, parents, n_nodes, uniforms, out, desc, workspace)
+    return _finish("radar_verify_accept_q", load().radar_verify_accept_q, args, keep, out, prepared)
 
 
 def radar_accept_length_distribution(target_logits, draft_tokens, parents, n_nodes=None, temperature=1.0, D_max=None,

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libradar.so")
-SOURCES = ["radar_common.hip", "radar_expand.hip", "radar_accept.hip", "radar_attention.hip", "radar_policy.hip"]
+SOURCES = ["radar_common.hip", "radar_expand.hip", "radar_accept.hip", "radar_attention.hip", "radar_policy.hip", "radar_accept_q.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed fp32 arithmetic is kept off for device code

@@ -69,30 +69,6 @@ __device__ __forceinline__ double scaled_exp(float x, const AcceptArgs &a, float
     return (double)expf((float)((double)x * a.inv_temp - (double)ref));
 }
 
-__device__ __forceinline__ double readlane_f64(double v, int lane) {
-    return __longlong_as_double((long long)readlane_u64((uint64_t)__double_as_longlong(v), lane));
-}
-
-// Inclusive prefix sum over the lanes of a wavefront by DPP moves (shift by 1, 2, 4, 8 inside each
-// 16-lane row, then the row totals are carried into the following rows); fixed association order.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ double dpp_take_f64(double v) {
-    const uint64_t b = (uint64_t)__double_as_longlong(v);
-    // lanes without a source lane, and rows outside ROW_MASK, receive 0
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)b, CTRL, ROW_MASK, 0xF, true);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(b >> 32), CTRL, ROW_MASK, 0xF, true);
-    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
-}
-__device__ __forceinline__ double wave_scan_f64(double v) {
-    v += dpp_take_f64<0x111, 0xF>(v);             // row_shr:1
-    v += dpp_take_f64<0x112, 0xF>(v);             // row_shr:2
-    v += dpp_take_f64<0x114, 0xF>(v);             // row_shr:4
-    v += dpp_take_f64<0x118, 0xF>(v);             // row_shr:8
-    v += dpp_take_f64<0x142, 0xA>(v);             // row_bcast:15 -> rows 1 and 3
-    v += dpp_take_f64<0x143, 0xC>(v);             // row_bcast:31 -> rows 2 and 3
-    return v;
-}
-
 // 16 logits per lane of one 1024-logit block: lane l takes [16 * l, 16 * l + 16) when CONTIG (pass
 // (b) needs token order inside a lane), else 4 x (64 lanes x 16 B) interleaved (widest requests).
 template <bool VEC4, bool CONTIG>
