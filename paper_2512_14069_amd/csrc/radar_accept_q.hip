@@ -47,6 +47,9 @@ __device__ __forceinline__ double exp_rel(float x, float m, double inv_temp) {
     return (double)__expf((float)(((double)x - (double)m) * inv_temp));
 }
 
+// the same in fp32 throughout (relative error about 1e-7 per unit of |x - m| * inv_temp)
+__device__ __forceinline__ float exp_rel_f32(float x, float m, float inv_temp) { return __expf((x - m) * inv_temp); }
+
 // sum over the workgroup of one double per thread, fixed order; every thread gets it
 __device__ __forceinline__ double block_sum_f64(double v, double *wred) {
     const double ws = wave_sum_f64(v);
@@ -156,6 +159,7 @@ __device__ __forceinline__ double residual_pass(const AqArgs &a, AqSmem &s, int 
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     float *ub = a.ubuf + (size_t)b * a.V;
     const int ngran = (hi - lo + kAqGran - 1) / kAqGran;
+    const float it_f = (float)a.inv_t, itd_f = (float)a.inv_td, pinv_l_f = (float)pinv_l, qinv_l_f = (float)qinv_l, W_f = (float)W;
     constexpr int U = 4;                                             // 4096-token steps whose loads are in flight together
     for (int base0 = lo + tid * 4; base0 - lane * 4 < hi; base0 += U * kAqThreads * 4) {
         float u4[U][4], q4[U][4];
@@ -183,15 +187,15 @@ __device__ __forceinline__ double residual_pass(const AqArgs &a, AqSmem &s, int 
         for (int k = 0; k < U; ++k) {
             const int base = base0 + k * kAqThreads * 4;
             if (base - lane * 4 >= hi) break;                        // wave-uniform
-            double sum = 0.0;
+            // fp32 per token (one workgroup's vector ALUs, not its memory path, bound this loop), fp64 sums
             float out[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                double u = prow ? exp_rel(u4[k][j], pm, a.inv_t) * pinv_l : (double)u4[k][j];
-                if (qrow) u = fmax(0.0, u - W * (exp_rel(q4[k][j], qm, a.inv_td) * qinv_l));
-                out[j] = (base + j < hi) ? (float)u : 0.f;
-                sum += (double)out[j];
+                float u = prow ? exp_rel_f32(u4[k][j], pm, it_f) * pinv_l_f : u4[k][j];
+                if (qrow) u = fmaxf(0.f, fmaf(-W_f, exp_rel_f32(q4[k][j], qm, itd_f) * qinv_l_f, u));
+                out[j] = (base + j < hi) ? u : 0.f;
             }
+            double sum = ((double)out[0] + (double)out[1]) + ((double)out[2] + (double)out[3]);
             if (VEC4) {
                 if (base < hi) *reinterpret_cast<float4 *>(ub + base) = make_float4(out[0], out[1], out[2], out[3]);
             } else {
