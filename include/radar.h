@@ -346,6 +346,59 @@ radar_status radar_draft_expand_policy(const float *logits, const float *parent_
                                        const radar_policy_params *params, const radar_policy_io *io,
                                        void *workspace, size_t workspace_bytes, void *stream);
 
+/* --------------------------------------------------------------------------
+ * A whole drafting cycle without the host in the loop (Sec. 4.1-4.2: after
+ * every draft call the prediction model decides whether another one follows;
+ * App. latency table: the decision and its round trip are what T_p pays for).
+ *
+ * The decision stays on the device: a radar_cycle_state in DEVICE memory holds
+ * "stopped", the number of pooled candidates and the number of draft calls
+ * made.  The host enqueues the longest cycle it allows (t_max draft calls,
+ * Sec. 4.2) once -- directly or captured in a HIP graph -- and never reads a
+ * result in between:
+ *   radar_cycle_begin          resets the state (one small kernel, no memset)
+ *   radar_draft_expand_cycle   one draft call's expansion; does NOTHING (every
+ *       workgroup leaves at once, no output is touched) when the state says
+ *       stopped; otherwise radar_draft_expand with the pool count taken from
+ *       the state, followed, when params != NULL, by radar_policy_step on the
+ *       new confidences as in radar_draft_expand_policy; then the state's pool
+ *       count grows by F*k, steps_done by one, and action 0 sets stopped.
+ *       Pass params = io = NULL for the last allowed draft call (no decision
+ *       is needed after it).  desc->pool_count is the LARGEST count the state
+ *       can hold when this call runs (what it would be had every earlier call
+ *       run): the capacity check uses it, and a state outside [0, that] makes
+ *       the call a no-op.
+ *   radar_draft_rerank_cycle   radar_draft_rerank over the candidates the state
+ *       counts (at most pool_count_max).
+ * Because a skipped call leaves its outputs alone, the frontier arrays chained
+ * from call to call still hold the last executed call's values.  All other
+ * arguments, limits and the workspace are those of the plain calls. */
+typedef struct radar_cycle_state {
+    int32_t stopped;        /* 1 once a decision said "stop" */
+    int32_t pool_count;     /* candidates pooled so far */
+    int32_t steps_done;     /* draft calls whose expansion ran */
+    int32_t last_action;    /* last decision (0 stop, 1 continue), -1 before the first */
+} radar_cycle_state;
+
+radar_status radar_cycle_begin(radar_cycle_state *state, void *stream);
+
+radar_status radar_draft_expand_cycle(const float *logits, const float *parent_scores, const int32_t *parent_pool_idx,
+                                      int32_t *cand_tokens, float *cand_scores,
+                                      int32_t *frontier_pool_idx, int32_t *frontier_tokens,
+                                      float *frontier_scores, float *frontier_conf,
+                                      int32_t *pool_tokens, float *pool_scores, int32_t *pool_parents,
+                                      const radar_expand_desc *desc,
+                                      const radar_policy_params *params, const radar_policy_io *io,
+                                      radar_cycle_state *state,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+
+radar_status radar_draft_rerank_cycle(const int32_t *pool_tokens, const float *pool_scores, const int32_t *pool_parents,
+                                      const radar_cycle_state *state, int32_t pool_count_max, int32_t N,
+                                      int32_t root_token,
+                                      int32_t *tree_tokens, int32_t *tree_parents, float *tree_scores,
+                                      int32_t *tree_depth, int32_t *tree_pool_idx, int32_t *n_nodes_out,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+
 /* Counts, per call, the nodes i < n_nodes[b] whose parent breaks the tree
  * convention; *bad_count_out (device i32) is overwritten.  parents i32
  * [B,T_max]; n_nodes i32 [B] or NULL. */

@@ -73,6 +73,7 @@ EXPORTS = [
     "radar_tree_attention_workspace_bytes", "radar_tree_attention",
     "radar_draft_expand_workspace_bytes", "radar_draft_expand", "radar_draft_expand_policy",
     "radar_draft_rerank_workspace_bytes", "radar_draft_rerank",
+    "radar_cycle_begin", "radar_draft_expand_cycle", "radar_draft_rerank_cycle",
     "radar_verify_accept_workspace_bytes", "radar_verify_accept",
     "radar_accept_length_distribution", "radar_policy_step",
     "radar_verify_accept_q_workspace_bytes", "radar_verify_accept_q",
@@ -106,6 +107,13 @@ def load():
     lib.radar_draft_expand_policy.restype = i32
     lib.radar_draft_expand_policy.argtypes = [vp] * 12 + [ctypes.POINTER(ExpandDesc), ctypes.POINTER(PolicyParams),
                                               ctypes.POINTER(PolicyIO), vp, sz, vp]
+    lib.radar_cycle_begin.restype = i32
+    lib.radar_cycle_begin.argtypes = [vp, vp]
+    lib.radar_draft_expand_cycle.restype = i32
+    lib.radar_draft_expand_cycle.argtypes = [vp] * 12 + [ctypes.POINTER(ExpandDesc), ctypes.POINTER(PolicyParams),
+                                             ctypes.POINTER(PolicyIO), vp, vp, sz, vp]
+    lib.radar_draft_rerank_cycle.restype = i32
+    lib.radar_draft_rerank_cycle.argtypes = [vp] * 4 + [i32, i32, i32] + [vp] * 6 + [vp, sz, vp]
     lib.radar_draft_rerank_workspace_bytes.restype = sz
     lib.radar_draft_rerank_workspace_bytes.argtypes = [i32, i32]
     lib.radar_draft_rerank.restype = i32
@@ -373,6 +381,72 @@ def radar_draft_rerank(pool, N, root_token, out=None, workspace=None, prepared=F
         _ptr(out.depth, torch.int32), _ptr(out.pool_idx, torch.int32), _ptr(out.n_nodes, torch.int32),
         wp, wn, _stream())
     return _finish("radar_draft_rerank", load().radar_draft_rerank, args, (pool, out, workspace), out, prepared)
+
+
+# ------------------------------------------------- cycle with device-side stop
+
+def new_cycle_state(device="cuda"):
+    """Device-side state of a drafting cycle: int32 [stopped, pool_count, steps_done, last_action]."""
+    return torch.zeros(4, dtype=torch.int32, device=device)
+
+
+def radar_cycle_begin(state, prepared=False):
+    args = (_ptr(state, torch.int32, "state"), _stream())
+    return _finish("radar_cycle_begin", load().radar_cycle_begin, args, (state,), state, prepared)
+
+
+def radar_draft_expand_cycle(logits, parent_scores, parent_pool_idx, k, pool, pool_count_max, state, params=None,
+                             h=None, c=None, uniform=None, out=None, policy_out=None, workspace=None, prepared=False):
+    """One draft call of a cycle whose stop decision stays on the device.  pool_count_max: the pool count
+    had every earlier call of the cycle run (host arithmetic); the actual count lives in `state`.
+    params None: no decision after this call.  pool.count is not touched.
+    Returns (ExpandOut, PolicyOut or None)."""
+    F, V = logits.shape
+    desc = expand_desc(F, V, k, int(pool_count_max), pool.capacity)
+    if out is None:
+        out = ExpandOut(F, k, logits.device)
+    if workspace is None:
+        workspace = new_workspace(radar_draft_expand_workspace_bytes(desc), logits.device)
+    pp = held = io = None
+    if params is not None:
+        pp, held = params
+        if policy_out is None:
+            policy_out = PolicyOut(1, pp.H, logits.device)
+        if (h is None) != (c is None):
+            raise ValueError("h and c must be given together")
+        io = PolicyIO()
+        val = lambda t, dt, n: None if t is None else _ptr(_dense(t, n), dt, n).value
+        io.h_in, io.c_in = val(h, torch.float32, "h"), val(c, torch.float32, "c")
+        io.uniform = val(uniform, torch.float32, "uniform")
+        io.h_out, io.c_out = policy_out.h.data_ptr(), policy_out.c.data_ptr()
+        io.logits, io.probs, io.action = policy_out.logits.data_ptr(), policy_out.probs.data_ptr(), policy_out.action.data_ptr()
+    wp, wn = _ws_args(workspace)
+    args = (
+        _ptr(_dense(logits, "logits"), torch.float32, "logits"),
+        _ptr(_dense(parent_scores, "parent_scores"), torch.float32, "parent_scores"),
+        _ptr(_dense(parent_pool_idx, "parent_pool_idx"), torch.int32, "parent_pool_idx"),
+        _ptr(out.cand_tokens, torch.int32), _ptr(out.cand_scores, torch.float32),
+        _ptr(out.frontier_pool_idx, torch.int32), _ptr(out.frontier_tokens, torch.int32),
+        _ptr(out.frontier_scores, torch.float32), _ptr(out.frontier_conf, torch.float32),
+        _ptr(pool.tokens, torch.int32), _ptr(pool.scores, torch.float32), _ptr(pool.parents, torch.int32),
+        ctypes.byref(desc), None if pp is None else ctypes.byref(pp), None if io is None else ctypes.byref(io),
+        _ptr(state, torch.int32, "state"), wp, wn, _stream())
+    keep = (logits, parent_scores, parent_pool_idx, out, pool, desc, workspace, pp, held, io, h, c, uniform, policy_out, state)
+    return _finish("radar_draft_expand_cycle", load().radar_draft_expand_cycle, args, keep, (out, policy_out), prepared)
+
+
+def radar_draft_rerank_cycle(pool, state, pool_count_max, N, root_token, out=None, workspace=None, prepared=False):
+    """radar_draft_rerank over the candidates `state` counts (at most pool_count_max)."""
+    if out is None:
+        out = TreeOut(N, pool.tokens.device)
+    wp, wn = _ws_args(workspace)
+    args = (
+        _ptr(pool.tokens, torch.int32), _ptr(pool.scores, torch.float32), _ptr(pool.parents, torch.int32),
+        _ptr(state, torch.int32, "state"), int(pool_count_max), int(N), int(root_token),
+        _ptr(out.tokens, torch.int32), _ptr(out.parents, torch.int32), _ptr(out.scores, torch.float32),
+        _ptr(out.depth, torch.int32), _ptr(out.pool_idx, torch.int32), _ptr(out.n_nodes, torch.int32),
+        wp, wn, _stream())
+    return _finish("radar_draft_rerank_cycle", load().radar_draft_rerank_cycle, args, (pool, state, out, workspace), out, prepared)
 
 
 # ------------------------------------------------------------ verification

@@ -47,6 +47,8 @@ struct ExpandArgs {
     float *part_m;              // [F][nchunks] chunk maximum
     PolicyArgs pol;             // prediction model run by the last workgroup when has_policy != 0
     float *gate_pre;            // [4H] w_hh h of that model, computed by the first workgroups of the launch
+    radar_cycle_state *cycle;   // device-side state of the drafting cycle, or null: when set, pool_count above is
+                                // only the largest value the state's own count may have
     int has_policy, pol_has_state;
 };
 
@@ -154,6 +156,14 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
     __shared__ ExpandSmem s;
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int f = blockIdx.y, chunk = blockIdx.x;
+    if (a.cycle) {
+        // A drafting cycle that has stopped skips its remaining draft calls: every workgroup leaves
+        // before touching anything.  (The state is only written by the last workgroup of a launch,
+        // after every other workgroup has handed over its results, i.e. long after this read.)
+        const int pc = a.cycle->pool_count;
+        if (a.cycle->stopped != 0 || pc < 0 || pc > a.pool_count) return;
+        a.pool_count = pc;
+    }
     const float *row = a.logits + (size_t)f * a.V;
     const int base = chunk * kChunk;
     const int K = a.k;
@@ -303,7 +313,13 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
     }
     __syncthreads();
     if (!a.has_policy) {
-        if (w == 0) select_frontier(a, s, nullptr);
+        if (w == 0) {
+            select_frontier(a, s, nullptr);
+            if (a.cycle && lane == 0) {
+                a.cycle->pool_count = a.pool_count + a.F * a.k;
+                a.cycle->steps_done += 1;
+            }
+        }
         return;
     }
     // ---- prediction-model step on the new frontier's confidences.  Its LDS reuses the
@@ -313,7 +329,15 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
     PolicySmem &ps = *reinterpret_cast<PolicySmem *>(&s.wtk[1]);
     policy_step_block<true>(
         a.pol, 0, a.pol_has_state != 0, ps, [&](int row) { return load_shared_result(&a.gate_pre[row]); },
-        [&] { select_frontier(a, s, ps.x); });
+        [&] { select_frontier(a, s, ps.x); },
+        [&](int action) {
+            if (a.cycle) {
+                a.cycle->pool_count = a.pool_count + a.F * a.k;
+                a.cycle->steps_done += 1;
+                a.cycle->last_action = action;
+                if (action == 0) a.cycle->stopped = 1;
+            }
+        });
 }
 
 // ------------------------------------------------------------------ rerank
@@ -322,6 +346,7 @@ struct RerankArgs {
     const float *pool_scores;
     const int32_t *pool_parents;
     int pool_count, N, root_token;
+    const radar_cycle_state *cycle;   // or null; when set, pool_count is the state's, clamped to the value above
     int32_t *tree_tokens;
     int32_t *tree_parents;
     float *tree_scores;
@@ -340,6 +365,7 @@ template <int EPT>                       // pool entries per lane: 4 (pools up t
 __global__ __launch_bounds__(kTopkThreads) void rerank_kernel(RerankArgs a) {
     __shared__ RerankSmem s;
     const int tid = threadIdx.x;
+    if (a.cycle) a.pool_count = min(max(a.cycle->pool_count, 0), a.pool_count);
     const int keep = min(a.N, a.pool_count);
 
     uint64_t keys[EPT];
@@ -429,7 +455,8 @@ static radar_status launch_expand(const float *logits, const float *parent_score
                                   int32_t *frontier_pool_idx, int32_t *frontier_tokens,
                                   float *frontier_scores, float *frontier_conf, int32_t *pool_tokens,
                                   float *pool_scores, int32_t *pool_parents, const radar_expand_desc *d,
-                                  const PolicyArgs *pol, void *workspace, size_t workspace_bytes, void *stream) {
+                                  const PolicyArgs *pol, radar_cycle_state *cycle, void *workspace,
+                                  size_t workspace_bytes, void *stream) {
     if (!d || !logits || !parent_scores || !parent_pool_idx || !cand_tokens || !cand_scores || !frontier_pool_idx ||
         !frontier_tokens || !frontier_scores || !frontier_conf || !pool_tokens || !pool_scores || !pool_parents ||
         !workspace)
@@ -458,6 +485,7 @@ static radar_status launch_expand(const float *logits, const float *parent_score
     a.part_l = reinterpret_cast<double *>(ws + kCounterBytes + nslots * RADAR_K_MAX * sizeof(uint64_t));
     a.part_m = reinterpret_cast<float *>(ws + kCounterBytes + nslots * (RADAR_K_MAX * sizeof(uint64_t) + sizeof(double)));
     a.gate_pre = reinterpret_cast<float *>(ws + radar_draft_expand_workspace_bytes(d) - ((4 * kPolH * sizeof(float) + 255) & ~size_t(255)));
+    a.cycle = cycle;
     a.pol = pol ? *pol : PolicyArgs{};
     a.has_policy = pol ? 1 : 0;
     a.pol_has_state = (pol && pol->h_in) ? 1 : 0;
@@ -483,7 +511,7 @@ extern "C" radar_status radar_draft_expand(const float *logits, const float *par
                                            void *workspace, size_t workspace_bytes, void *stream) {
     return launch_expand(logits, parent_scores, parent_pool_idx, cand_tokens, cand_scores, frontier_pool_idx,
                          frontier_tokens, frontier_scores, frontier_conf, pool_tokens, pool_scores, pool_parents, d,
-                         nullptr, workspace, workspace_bytes, stream);
+                         nullptr, nullptr, workspace, workspace_bytes, stream);
 }
 
 extern "C" radar_status radar_draft_expand_policy(const float *logits, const float *parent_scores,
@@ -504,12 +532,72 @@ extern "C" radar_status radar_draft_expand_policy(const float *logits, const flo
     pa.h_out = io->h_out; pa.c_out = io->c_out; pa.logits = io->logits; pa.probs = io->probs; pa.action = io->action;
     return launch_expand(logits, parent_scores, parent_pool_idx, cand_tokens, cand_scores, frontier_pool_idx,
                          frontier_tokens, frontier_scores, frontier_conf, pool_tokens, pool_scores, pool_parents, d,
-                         &pa, workspace, workspace_bytes, stream);
+                         &pa, nullptr, workspace, workspace_bytes, stream);
+}
+
+// fill kernel for the cycle state (a graph may not hold a memset node)
+__global__ void cycle_begin_kernel(radar_cycle_state *st) {
+    if (threadIdx.x == 0) { st->stopped = 0; st->pool_count = 0; st->steps_done = 0; st->last_action = -1; }
+}
+
+extern "C" radar_status radar_cycle_begin(radar_cycle_state *state, void *stream) {
+    if (!state) return RADAR_INVALID_ARG;
+    const hipError_t e = launch("cycle_begin", cycle_begin_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), state);
+    return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
+}
+
+extern "C" radar_status radar_draft_expand_cycle(const float *logits, const float *parent_scores,
+                                                 const int32_t *parent_pool_idx, int32_t *cand_tokens,
+                                                 float *cand_scores, int32_t *frontier_pool_idx,
+                                                 int32_t *frontier_tokens, float *frontier_scores,
+                                                 float *frontier_conf, int32_t *pool_tokens, float *pool_scores,
+                                                 int32_t *pool_parents, const radar_expand_desc *d,
+                                                 const radar_policy_params *params, const radar_policy_io *io,
+                                                 radar_cycle_state *state, void *workspace, size_t workspace_bytes,
+                                                 void *stream) {
+    if (!state || !d) return RADAR_INVALID_ARG;
+    if (!params) {
+        if (io) return RADAR_INVALID_ARG;
+        return launch_expand(logits, parent_scores, parent_pool_idx, cand_tokens, cand_scores, frontier_pool_idx,
+                             frontier_tokens, frontier_scores, frontier_conf, pool_tokens, pool_scores, pool_parents, d,
+                             nullptr, state, workspace, workspace_bytes, stream);
+    }
+    PolicyArgs pa;
+    const radar_status st = policy_args_from(params, &pa);
+    if (st != RADAR_OK) return st;
+    if (!io || !io->h_out || !io->c_out || !io->logits || !io->probs || !io->action) return RADAR_INVALID_ARG;
+    if ((io->h_in == nullptr) != (io->c_in == nullptr) || ((uintptr_t)io->h_in & 15) != 0) return RADAR_INVALID_ARG;
+    if (params->k != d->k) return RADAR_INVALID_ARG;
+    pa.h_in = io->h_in; pa.c_in = io->c_in; pa.uniforms = io->uniform;
+    pa.h_out = io->h_out; pa.c_out = io->c_out; pa.logits = io->logits; pa.probs = io->probs; pa.action = io->action;
+    return launch_expand(logits, parent_scores, parent_pool_idx, cand_tokens, cand_scores, frontier_pool_idx,
+                         frontier_tokens, frontier_scores, frontier_conf, pool_tokens, pool_scores, pool_parents, d,
+                         &pa, state, workspace, workspace_bytes, stream);
 }
 
 extern "C" size_t radar_draft_rerank_workspace_bytes(int32_t pool_count, int32_t N) {
     (void)pool_count; (void)N;
     return 256;   // rerank keeps everything in LDS; a minimal workspace keeps the calling convention uniform
+}
+
+static radar_status launch_rerank(const int32_t *pool_tokens, const float *pool_scores, const int32_t *pool_parents,
+                                  int32_t pool_count, const radar_cycle_state *cycle, int32_t N, int32_t root_token,
+                                  int32_t *tree_tokens, int32_t *tree_parents, float *tree_scores,
+                                  int32_t *tree_depth, int32_t *tree_pool_idx, int32_t *n_nodes_out, void *stream) {
+    if (!pool_tokens || !pool_scores || !pool_parents || !tree_tokens || !tree_parents || !tree_scores ||
+        !tree_depth || !tree_pool_idx || !n_nodes_out)
+        return RADAR_INVALID_ARG;
+    if (pool_count < 0 || N < 0) return RADAR_INVALID_ARG;
+    if (pool_count > RADAR_POOL_MAX || N >= RADAR_T_MAX) return RADAR_UNSUPPORTED_SHAPE;
+    RerankArgs a;
+    a.pool_tokens = pool_tokens; a.pool_scores = pool_scores; a.pool_parents = pool_parents;
+    a.pool_count = pool_count; a.N = N; a.root_token = root_token; a.cycle = cycle;
+    a.tree_tokens = tree_tokens; a.tree_parents = tree_parents; a.tree_scores = tree_scores;
+    a.tree_depth = tree_depth; a.tree_pool_idx = tree_pool_idx; a.n_nodes_out = n_nodes_out;
+    const hipError_t e = pool_count <= 4 * kTopkThreads
+        ? launch("rerank", rerank_kernel<4>, dim3(1), dim3(kTopkThreads), 0, static_cast<hipStream_t>(stream), a)
+        : launch("rerank", rerank_kernel<16>, dim3(1), dim3(kTopkThreads), 0, static_cast<hipStream_t>(stream), a);
+    return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
 }
 
 extern "C" radar_status radar_draft_rerank(const int32_t *pool_tokens, const float *pool_scores,
@@ -519,18 +607,18 @@ extern "C" radar_status radar_draft_rerank(const int32_t *pool_tokens, const flo
                                            int32_t *n_nodes_out, void *workspace, size_t workspace_bytes,
                                            void *stream) {
     (void)workspace; (void)workspace_bytes;
-    if (!pool_tokens || !pool_scores || !pool_parents || !tree_tokens || !tree_parents || !tree_scores ||
-        !tree_depth || !tree_pool_idx || !n_nodes_out)
-        return RADAR_INVALID_ARG;
-    if (pool_count < 0 || N < 0) return RADAR_INVALID_ARG;
-    if (pool_count > RADAR_POOL_MAX || N >= RADAR_T_MAX) return RADAR_UNSUPPORTED_SHAPE;
-    RerankArgs a;
-    a.pool_tokens = pool_tokens; a.pool_scores = pool_scores; a.pool_parents = pool_parents;
-    a.pool_count = pool_count; a.N = N; a.root_token = root_token;
-    a.tree_tokens = tree_tokens; a.tree_parents = tree_parents; a.tree_scores = tree_scores;
-    a.tree_depth = tree_depth; a.tree_pool_idx = tree_pool_idx; a.n_nodes_out = n_nodes_out;
-    const hipError_t e = pool_count <= 4 * kTopkThreads
-        ? launch("rerank", rerank_kernel<4>, dim3(1), dim3(kTopkThreads), 0, static_cast<hipStream_t>(stream), a)
-        : launch("rerank", rerank_kernel<16>, dim3(1), dim3(kTopkThreads), 0, static_cast<hipStream_t>(stream), a);
-    return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
+    return launch_rerank(pool_tokens, pool_scores, pool_parents, pool_count, nullptr, N, root_token, tree_tokens,
+                         tree_parents, tree_scores, tree_depth, tree_pool_idx, n_nodes_out, stream);
+}
+
+extern "C" radar_status radar_draft_rerank_cycle(const int32_t *pool_tokens, const float *pool_scores,
+                                                 const int32_t *pool_parents, const radar_cycle_state *state,
+                                                 int32_t pool_count_max, int32_t N, int32_t root_token,
+                                                 int32_t *tree_tokens, int32_t *tree_parents, float *tree_scores,
+                                                 int32_t *tree_depth, int32_t *tree_pool_idx, int32_t *n_nodes_out,
+                                                 void *workspace, size_t workspace_bytes, void *stream) {
+    (void)workspace; (void)workspace_bytes;
+    if (!state) return RADAR_INVALID_ARG;
+    return launch_rerank(pool_tokens, pool_scores, pool_parents, pool_count_max, state, N, root_token, tree_tokens,
+                         tree_parents, tree_scores, tree_depth, tree_pool_idx, n_nodes_out, stream);
 }

@@ -20,8 +20,10 @@ template <typename... Params, typename... Args>
 inline hipError_t launch(const char *name, void (*kernel)(Params...), dim3 grid, dim3 block, unsigned smem,
                          hipStream_t stream, Args... args) {
     hipEvent_t e0 = nullptr, e1 = nullptr;
-    profile_slot(name, &e0, &e1);
-    hipExtLaunchKernelGGL(kernel, grid, block, smem, stream, e0, e1, 0u, static_cast<Params>(args)...);
+    if (profile_slot(name, &e0, &e1))
+        hipExtLaunchKernelGGL(kernel, grid, block, smem, stream, e0, e1, 0u, static_cast<Params>(args)...);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, smem, stream, static_cast<Params>(args)...);   // the form a stream capture records
     return hipGetLastError();
 }
 

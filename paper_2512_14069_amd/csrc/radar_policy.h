@@ -116,9 +116,10 @@ __device__ __forceinline__ void policy_hidden_rows(const PolicyArgs &p, int b, i
 // loads (a value in global memory, complete before the call), otherwise after the first barrier
 // (a value this workgroup wrote to LDS just before the call).
 // h_out / c_out may be the arrays h_in / c_in.
-template <bool EARLY, typename Hidden, typename Inputs>
+// decided(action) is called by the one lane that has just written the outputs.
+template <bool EARLY, typename Hidden, typename Inputs, typename Decided>
 __device__ __forceinline__ void policy_step_block(const PolicyArgs &p, int b, bool has_state, PolicySmem &s,
-                                                  Hidden &&hidden, Inputs &&wave0_inputs) {
+                                                  Hidden &&hidden, Inputs &&wave0_inputs, Decided &&decided) {
     const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave;
     const int wk = w - 1;                                            // worker index, -1 for wavefront 0
     // cell update: wavefronts 8..15, 16 units each; lane = 16 * gate + unit within the wavefront
@@ -247,7 +248,9 @@ __device__ __forceinline__ void policy_step_block(const PolicyArgs &p, int b, bo
             p.logits[2 * b + 1] = l1;
             p.probs[2 * b] = p0;
             p.probs[2 * b + 1] = p1;
-            p.action[b] = p.uniforms ? (uni < p1 ? 1 : 0) : (l1 > l0 ? 1 : 0);
+            const int act = p.uniforms ? (uni < p1 ? 1 : 0) : (l1 > l0 ? 1 : 0);
+            p.action[b] = act;
+            decided(act);
         }
     }
 }

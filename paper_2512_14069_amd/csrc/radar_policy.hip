@@ -15,7 +15,8 @@ __global__ __launch_bounds__(kPolThreads) void policy_kernel(PolicyArgs p, const
         p, b, has_state != 0, s, [&](int row) { return s.gate[row]; },
         [&] {
             if ((int)threadIdx.x < p.k) s.x[threadIdx.x] = conf[(size_t)b * p.k + threadIdx.x];
-        });
+        },
+        [](int) {});
 }
 
 // Host-side check of a parameter block; fills the kernel's argument struct.
