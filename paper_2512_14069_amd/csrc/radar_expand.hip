@@ -149,19 +149,23 @@ __device__ __forceinline__ void select_frontier(const ExpandArgs &a, ExpandSmem 
     }
 }
 
-template <bool VEC4, int EPT>
+// EXT: the launch may carry a prediction model and / or a device-side cycle state; the plain
+// expansion is compiled without any of that code.
+template <bool VEC4, int EPT, bool EXT>
 __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
+    const bool has_policy = EXT && a.has_policy != 0;
+    radar_cycle_state *const cycle = EXT ? a.cycle : nullptr;
     static_assert(EPT == 4 || EPT == 8 || EPT == 16, "EPT");
     constexpr int kChunk = kExpThreads * EPT;
     __shared__ ExpandSmem s;
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int f = blockIdx.y, chunk = blockIdx.x;
-    if (a.cycle) {
+    if (cycle) {
         // A drafting cycle that has stopped skips its remaining draft calls: every workgroup leaves
         // before touching anything.  (The state is only written by the last workgroup of a launch,
         // after every other workgroup has handed over its results, i.e. long after this read.)
-        const int pc = a.cycle->pool_count;
-        if (a.cycle->stopped != 0 || pc < 0 || pc > a.pool_count) return;
+        const int pc = cycle->pool_count;
+        if (cycle->stopped != 0 || pc < 0 || pc > a.pool_count) return;
         a.pool_count = pc;
     }
     const float *row = a.logits + (size_t)f * a.V;
@@ -186,7 +190,7 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
     // The prediction model's input-free part (w_hh h) is shared out over the workgroups of the
     // launch: its loads travel with the logits', its results are handed to the last workgroup
     // through the workspace like the chunk partials.
-    if (a.has_policy && a.pol_has_state)
+    if (has_policy && a.pol_has_state)
         policy_hidden_rows<4>(a.pol, 0, blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y,
                               [&](int r, float v) { store_shared_result(&a.gate_pre[r], v); });
     float x[EPT];
@@ -312,12 +316,12 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
         }
     }
     __syncthreads();
-    if (!a.has_policy) {
+    if (!has_policy) {
         if (w == 0) {
             select_frontier(a, s, nullptr);
-            if (a.cycle && lane == 0) {
-                a.cycle->pool_count = a.pool_count + a.F * a.k;
-                a.cycle->steps_done += 1;
+            if (cycle && lane == 0) {
+                cycle->pool_count = a.pool_count + a.F * a.k;
+                cycle->steps_done += 1;
             }
         }
         return;
@@ -331,11 +335,11 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
         a.pol, 0, a.pol_has_state != 0, ps, [&](int row) { return load_shared_result(&a.gate_pre[row]); },
         [&] { select_frontier(a, s, ps.x); },
         [&](int action) {
-            if (a.cycle) {
-                a.cycle->pool_count = a.pool_count + a.F * a.k;
-                a.cycle->steps_done += 1;
-                a.cycle->last_action = action;
-                if (action == 0) a.cycle->stopped = 1;
+            if (cycle) {
+                cycle->pool_count = a.pool_count + a.F * a.k;
+                cycle->steps_done += 1;
+                cycle->last_action = action;
+                if (action == 0) cycle->stopped = 1;
             }
         });
 }
@@ -494,12 +498,14 @@ static radar_status launch_expand(const float *logits, const float *parent_score
     const bool vec4 = (d->V % 4 == 0) && (((uintptr_t)logits & 15) == 0);
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
-    if (ept == 4)      e = vec4 ? launch("expand", expand_kernel<true, 4>, grid, block, 0, st, a)
-                                : launch("expand", expand_kernel<false, 4>, grid, block, 0, st, a);
-    else if (ept == 8) e = vec4 ? launch("expand", expand_kernel<true, 8>, grid, block, 0, st, a)
-                                : launch("expand", expand_kernel<false, 8>, grid, block, 0, st, a);
-    else               e = vec4 ? launch("expand", expand_kernel<true, 16>, grid, block, 0, st, a)
-                                : launch("expand", expand_kernel<false, 16>, grid, block, 0, st, a);
+    const bool ext = pol != nullptr || cycle != nullptr;
+#define RADAR_EXPAND_LAUNCH(V4, E)                                                                   \
+    (ext ? launch("expand", expand_kernel<V4, E, true>, grid, block, 0, st, a)                        \
+         : launch("expand", expand_kernel<V4, E, false>, grid, block, 0, st, a))
+    if (ept == 4)      e = vec4 ? RADAR_EXPAND_LAUNCH(true, 4) : RADAR_EXPAND_LAUNCH(false, 4);
+    else if (ept == 8) e = vec4 ? RADAR_EXPAND_LAUNCH(true, 8) : RADAR_EXPAND_LAUNCH(false, 8);
+    else               e = vec4 ? RADAR_EXPAND_LAUNCH(true, 16) : RADAR_EXPAND_LAUNCH(false, 16);
+#undef RADAR_EXPAND_LAUNCH
     return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
 }
 
