@@ -51,7 +51,7 @@ struct AttnArgs {
     int B, T, Hq, Hkv, G, S, kps, max_splits, n_ublk, nqb;   // nqb 32-row blocks per head, n_ublk workgroups per KV range
     int64_t q_sb, q_st, q_sh, kv_sb, kv_sh, kv_ss, o_sb, o_st, o_sh;
     float scale_log2;                      // softmax scale * log2(e), > 0
-    float *part_o;                         // [B][Hq][max_splits][D][64]: transposed partial outputs
+    uint32_t *part_o;                      // [B][Hq][max_splits][D/2][64]: partial outputs, fp16 pairs (d, d+1), scaled per row
     float *part_ml;                        // [B][Hq][max_splits][2][64]: running maximum (log2 units) and sum
 };
 
@@ -268,7 +268,7 @@ __device__ __forceinline__ void gs_store_tile(const GsTileRegs<D> &g, unsigned c
     }
 }
 
-template <int D>
+template <int D, bool DEEP>
 __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
     constexpr int DB = D / 32;              // 32-row blocks of O^T
 
@@ -301,8 +301,12 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
     const int kv_ss = (int)a.kv_ss;          // 32-bit offsets inside one head's cache (checked on the host)
 
     const int ntiles = (kend - kbeg + kKT - 1) / kKT;
-    GsTileRegs<D> regs;                                   // staging by the whole workgroup
-    gs_load_tile<D>(regs, kbase, vbase, kv_ss, kbeg, kend, tid);
+    // DEEP (ranges of many tiles): staging runs two tiles ahead through two register sets, which hides
+    // HBM latency better but doubles the loop's code; short ranges keep the compact one-ahead loop
+    // (their time goes into a cold start, where code size counts).
+    GsTileRegs<D> regs0, regs1;
+    gs_load_tile<D>(regs0, kbase, vbase, kv_ss, kbeg, kend, tid);
+    if (DEEP && ntiles > 1) gs_load_tile<D>(regs1, kbase, vbase, kv_ss, kbeg + kKT, kend, tid);
     // this lane's query operands, kept in registers for the whole kernel: row i, d = 16*st + 8*g2 .. +8
     bf16x8 qop[D / 16];
     {
@@ -315,9 +319,10 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
         }
     }
     if (tid < RADAR_T_MAX) s_par[tid] = a.parents[(size_t)b * a.T + min(tid, nn - 1)];
-    gs_store_tile<D>(regs, smem, smem + TILE / 2, tid);
+    gs_store_tile<D>(regs0, smem, smem + TILE / 2, tid);
     __syncthreads();
-    if (ntiles > 1) gs_load_tile<D>(regs, kbase, vbase, kv_ss, kbeg + kKT, kend, tid);
+    if (DEEP) { if (ntiles > 2) gs_load_tile<D>(regs0, kbase, vbase, kv_ss, kbeg + 2 * kKT, kend, tid); }
+    else if (ntiles > 1) gs_load_tile<D>(regs0, kbase, vbase, kv_ss, kbeg + kKT, kend, tid);
     uint64_t anc[1];
     anc[0] = (kend > L && i < nn) ? ancestor_word(s_par, i) : 0ull;
 
@@ -328,17 +333,25 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
         for (int r = 0; r < 16; ++r) oacc[db][0][r] = 0.f;
     float m_run[1] = {kNegBig}, l_run[1] = {0.f};
 
-    // Two tile buffers: while tile t is consumed from one, every wavefront drops its share of tile
-    // t+1 (in registers since the previous iteration) into the other as soon as it is done with t.
-    // One barrier per tile: it publishes tile t+1 and tells that nobody reads tile t any more.
-    for (int t = 0; t < ntiles; ++t) {
+    // Two tile buffers in LDS: while tile t is consumed from one, every wavefront drops its share of
+    // tile t+1 into the other as soon as it is done with t.  One barrier per tile: it publishes tile
+    // t+1 and tells that nobody reads tile t any more.
+    auto step = [&](int t, GsTileRegs<D> &next_regs, int ahead) {
         unsigned char *cur = smem + (t & 1) * TILE, *nxt = smem + ((t + 1) & 1) * TILE;
         if (active) wave_tile<D, 1>(cur, cur + TILE / 2, qop, oacc, m_run, l_run, anc, kbeg + t * kKT, L, kend, t == 0, a.scale_log2);
         if (t + 1 < ntiles) {
-            gs_store_tile<D>(regs, nxt, nxt + TILE / 2, tid);
+            gs_store_tile<D>(next_regs, nxt, nxt + TILE / 2, tid);
             __syncthreads();
-            if (t + 2 < ntiles) gs_load_tile<D>(regs, kbase, vbase, kv_ss, kbeg + (t + 2) * kKT, kend, tid);
+            if (t + ahead < ntiles) gs_load_tile<D>(next_regs, kbase, vbase, kv_ss, kbeg + (t + ahead) * kKT, kend, tid);
         }
+    };
+    if (DEEP) {                                           // unrolled by two: odd tiles travel through regs1, even ones through regs0
+        for (int t = 0; t < ntiles; t += 2) {
+            step(t, regs1, 3);
+            if (t + 1 < ntiles) step(t + 1, regs0, 3);
+        }
+    } else {
+        for (int t = 0; t < ntiles; ++t) step(t, regs0, 2);
     }
     if (!active) return;
 
@@ -360,17 +373,39 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
         if (a.lse && g2 == 0)
             a.lse[((size_t)b * a.T + i) * a.Hq + h] = (i < nn) ? (m_run[0] + __builtin_amdgcn_logf(l_tot)) * kLn2 : 0.f;
     } else {
+        // Partial result of this key range: the row's output normalised by its own l and by the row's
+        // largest magnitude, as fp16 pairs (d, d+1) -- [D/2][64 rows] words, so that 32 lanes still write
+        // 128 contiguous bytes -- plus (m, l, magnitude) in fp32.  The partials of all ranges together
+        // outweigh the K/V bytes, and writing them is what the tail of this kernel waits for; halving
+        // them costs 2^-11 of the row's largest element in precision, an eighth of the bf16 rounding of
+        // the final output.  Written through: nothing is left dirty in L2 for the end of the kernel.
         const size_t unit = ((size_t)b * a.Hq + h) * a.max_splits + sp;
-        float *po = a.part_o + unit * (size_t)(D * 64);
-        float *pml = a.part_ml + unit * 128;
+        uint32_t *po = a.part_o + unit * (size_t)(D / 2 * 64);
+        float *pml = a.part_ml + unit * 192;
+        const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+        float amax = 0.f;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
+            for (int r = 0; r < 16; ++r) amax = fmaxf(amax, fabsf(oacc[db][0][r]));
+        amax = fmaxf(amax, __shfl_xor(amax, 32)) * inv;          // both halves of the row's d range
+        const float mag = amax > 0.f && amax < 3.0e38f ? amax : 1.f;
+        const float scl = inv / mag;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int rp = 0; rp < 8; ++rp) {
+                const int r = 2 * rp;
                 const int d = 32 * db + 8 * (r >> 2) + 4 * g2 + (r & 3);
-                store_shared_result(&po[d * 64 + i], oacc[db][0][r]);     // written through: nothing is left
-            }                                                              // dirty in L2 for the end of the kernel
-        if (g2 == 0) { store_shared_result(&pml[i], m_run[0]); store_shared_result(&pml[64 + i], l_tot); }
+                const _Float16 lo = (_Float16)(oacc[db][0][r] * scl), hi = (_Float16)(oacc[db][0][r + 1] * scl);
+                const uint32_t word = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+                store_shared_result(&po[(d >> 1) * 64 + i], word);
+            }
+        if (g2 == 0) {
+            store_shared_result(&pml[i], m_run[0]);
+            store_shared_result(&pml[64 + i], l_tot);
+            store_shared_result(&pml[128 + i], mag);
+        }
     }
 }
 
@@ -408,15 +443,16 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_merge_kernel(AttnArgs 
 #pragma unroll
     for (int d = 0; d < DQ; ++d) acc[d] = 0.f;
     for (int s0 = 0; s0 < nsplit; s0 += 4) {
-        float ms[4], ls[4], ov[4][DQ];
+        float ms[4], ls[4];
+        uint32_t ow[4][DQ / 2];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int sc = min(s0 + j, nsplit - 1);
-            ms[j] = a.part_ml[(unit0 + sc) * 128 + i];
-            ls[j] = a.part_ml[(unit0 + sc) * 128 + 64 + i];
-            const float *po = a.part_o + (unit0 + sc) * (size_t)(D * 64);
+            ms[j] = a.part_ml[(unit0 + sc) * 192 + i];
+            ls[j] = a.part_ml[(unit0 + sc) * 192 + 64 + i] * a.part_ml[(unit0 + sc) * 192 + 128 + i];   // l x magnitude
+            const uint32_t *po = a.part_o + (unit0 + sc) * (size_t)(D / 2 * 64);
 #pragma unroll
-            for (int d = 0; d < DQ; ++d) ov[j][d] = po[(d0 + d) * 64 + i];
+            for (int d = 0; d < DQ / 2; ++d) ow[j][d] = po[((d0 >> 1) + d) * 64 + i];
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -425,9 +461,16 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_merge_kernel(AttnArgs 
             const float Mn = fmaxf(M, m);
             const float aold = __builtin_amdgcn_exp2f(M - Mn);
             const float wnew = valid ? __builtin_amdgcn_exp2f(m - Mn) : 0.f;
-            lsum = lsum * aold + wnew * ls[j];
+            const float lj = a.part_ml[(unit0 + min(s0 + j, nsplit - 1)) * 192 + 64 + i];
+            lsum = lsum * aold + wnew * lj;
+            const float wo = wnew * ls[j];                        // the stored rows are o / (l x magnitude)
 #pragma unroll
-            for (int d = 0; d < DQ; ++d) acc[d] = acc[d] * aold + wnew * ov[j][d];
+            for (int d = 0; d < DQ / 2; ++d) {
+                const float lo = (float)__builtin_bit_cast(_Float16, (uint16_t)(ow[j][d] & 0xffffu));
+                const float hi = (float)__builtin_bit_cast(_Float16, (uint16_t)(ow[j][d] >> 16));
+                acc[2 * d] = acc[2 * d] * aold + wo * lo;
+                acc[2 * d + 1] = acc[2 * d + 1] * aold + wo * hi;
+            }
             M = Mn;
         }
     }
@@ -475,8 +518,8 @@ static AttnPlan plan_attention(const radar_attn_desc *d) {
     auto take = [&](size_t bytes) { const size_t o = off; off += (bytes + 255) & ~size_t(255); return o; };
     take(256);                                             // never empty: callers always pass a workspace
     const size_t units = p.max_splits > 1 ? (size_t)d->B * d->Hq * p.max_splits : 0;
-    p.off_part_o = take(units * 64 * d->D * sizeof(float));
-    p.off_part_ml = take(units * 128 * sizeof(float));
+    p.off_part_o = take(units * 64 * (d->D / 2) * sizeof(uint32_t));
+    p.off_part_ml = take(units * 192 * sizeof(float));
     p.bytes = off;
     return p;
 }
@@ -504,16 +547,16 @@ extern "C" size_t radar_tree_attention_workspace_bytes(const radar_attn_desc *d)
 template <int D>
 constexpr int gs_smem_bytes() { return 2 * (2 * kKT * D * 2) + RADAR_T_MAX * 4; }
 
-template <int D>
+template <int D, bool DEEP>
 static hipError_t launch_gs(const AttnArgs &a, dim3 grid, hipStream_t s) {
     static bool configured = false;                        // raise the dynamic LDS limit once per instantiation
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_gs_kernel<D>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_gs_kernel<D, DEEP>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, gs_smem_bytes<D>());
         if (e != hipSuccess) return e;
         configured = true;
     }
-    return launch("tree_attn_group_share", tree_attn_gs_kernel<D>, grid, dim3(kGsThreads), gs_smem_bytes<D>(), s, a);
+    return launch("tree_attn_group_share", tree_attn_gs_kernel<D, DEEP>, grid, dim3(kGsThreads), gs_smem_bytes<D>(), s, a);
 }
 
 extern "C" radar_status radar_tree_attention(const void *q, const void *k_cache, const void *v_cache,
@@ -555,7 +598,7 @@ extern "C" radar_status radar_tree_attention(const void *q, const void *k_cache,
     const float scale = d->softmax_scale != 0.f ? d->softmax_scale : 1.0f / sqrtf((float)d->D);
     a.scale_log2 = scale * kLog2e;
     char *ws = static_cast<char *>(workspace);
-    a.part_o = reinterpret_cast<float *>(ws + p.off_part_o);
+    a.part_o = reinterpret_cast<uint32_t *>(ws + p.off_part_o);
     a.part_ml = reinterpret_cast<float *>(ws + p.off_part_ml);
 
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -564,7 +607,8 @@ extern "C" radar_status radar_tree_attention(const void *q, const void *k_cache,
     const dim3 grid((unsigned)a.max_splits, (unsigned)(a.Hkv * a.n_ublk), (unsigned)a.B);
     {
         hipError_t e;
-        e = d->D == 128 ? launch_gs<128>(a, grid, s) : launch_gs<64>(a, grid, s);
+        if (p.kps >= 8 * kKT) e = d->D == 128 ? launch_gs<128, true>(a, grid, s) : launch_gs<64, true>(a, grid, s);
+        else                  e = d->D == 128 ? launch_gs<128, false>(a, grid, s) : launch_gs<64, false>(a, grid, s);
         if (e != hipSuccess) return RADAR_HIP_ERROR;
     }
     if (a.max_splits > 1) {
