@@ -56,7 +56,8 @@ class AcceptDesc(ctypes.Structure):
 
 class AcceptQDesc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("T_max", ctypes.c_int32), ("Tq", ctypes.c_int32), ("V", ctypes.c_int32),
-                ("D_max", ctypes.c_int32), ("temperature", ctypes.c_float), ("draft_temperature", ctypes.c_float)]
+                ("D_max", ctypes.c_int32), ("temperature", ctypes.c_float), ("draft_temperature", ctypes.c_float),
+                ("walk_spin_limit", ctypes.c_int32)]
 
 
 class PolicyParams(ctypes.Structure):
@@ -489,9 +490,10 @@ def radar_verify_accept(target_logits, draft_tokens, parents, n_nodes=None, unif
     return _finish("radar_verify_accept", load().radar_verify_accept, args, keep, out, prepared)
 
 
-def accept_q_desc(B, T, Tq, V, D_max, temperature=1.0, draft_temperature=1.0):
+def accept_q_desc(B, T, Tq, V, D_max, temperature=1.0, draft_temperature=1.0, walk_spin_limit=0):
     d = AcceptQDesc()
     d.B, d.T_max, d.Tq, d.V, d.D_max, d.temperature, d.draft_temperature = B, T, Tq, V, D_max, temperature, draft_temperature
+    d.walk_spin_limit = walk_spin_limit
     return d
 
 
@@ -500,7 +502,8 @@ def radar_verify_accept_q_workspace_bytes(desc):
 
 
 def radar_verify_accept_q(target_logits, draft_logits, draft_tokens, parents, n_nodes=None, uniforms=None, q_rows=None,
-                          temperature=1.0, draft_temperature=1.0, D_max=None, out=None, workspace=None, prepared=False):
+                          temperature=1.0, draft_temperature=1.0, D_max=None, out=None, workspace=None, prepared=False,
+                          walk_spin_limit=0):
     """target_logits f32 [B,T,V]; draft_logits f32 [B,Tq,V]; q_rows i32 [B,T] or None (Tq == T);
     draft_tokens, parents i32 [B,T]; n_nodes i32 [B] or None; uniforms f32 [B,T+1].
     Returns (accept_len [B], accept_path [B,D_max+1], bonus_token [B])."""
@@ -512,7 +515,7 @@ def radar_verify_accept_q(target_logits, draft_logits, draft_tokens, parents, n_
         raise ValueError(f"uniforms: expected shape {(B, T + 1)}")
     if D_max is None:
         D_max = T - 1
-    desc = accept_q_desc(B, T, Tq, V, D_max, temperature, draft_temperature)
+    desc = accept_q_desc(B, T, Tq, V, D_max, temperature, draft_temperature, walk_spin_limit)
     dev = target_logits.device
     if out is None:
         out = (torch.empty(B, dtype=torch.int32, device=dev),

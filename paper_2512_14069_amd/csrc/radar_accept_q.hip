@@ -39,6 +39,12 @@ struct AqArgs {
     float *row_m;               // [rows]
     double *row_l;              // [rows]
     float *ubuf;                // [B][V] unnormalised residual of the node being verified
+    // walk by several workgroups per sequence
+    unsigned int *co_ctl;       // [B][32]: arrival counter, leave counter, abort flag (each on its own 32 bytes)
+    double *co_psum;            // [B][2][32] slice sums of the last two meetings
+    float *co_sib;              // [B][2][64] residual at the tokens of untried children
+    int co_R;                   // float4 per lane
+    unsigned int co_spin_limit; // polls of the arrival counter before a workgroup gives up
 };
 
 // exp((x - m) * inv_temp) with the difference formed in fp64, rounded to fp32 once, and the fp32
@@ -297,11 +303,10 @@ __device__ __forceinline__ int pick_token(const AqArgs &a, AqSmem &s, int b, dou
     return __shfl(pick, owner2);
 }
 
+// The whole walk of sequence b by one workgroup (every thread calls it).
 template <bool VEC4>
-__global__ __launch_bounds__(kAqThreads) void accept_q_walk_kernel(AqArgs a) {
-    __shared__ AqSmem s;
+__device__ __forceinline__ void walk_single(const AqArgs &a, AqSmem &s, int b) {
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
-    const int b = blockIdx.x;
     const int rows_per_seq = a.T + a.Tq;
     const int nn = a.n_nodes ? min(max(a.n_nodes[b], 0), a.T) : a.T;
     int32_t *path = a.accept_path + (size_t)b * (a.D_max + 1);
@@ -410,11 +415,322 @@ __global__ __launch_bounds__(kAqThreads) void accept_q_walk_kernel(AqArgs a) {
     }
 }
 
+// only_marked: the launch that follows the shared walk; it redoes the sequences that walk marked
+// (and clears the mark), and leaves the others alone.
+template <bool VEC4>
+__global__ __launch_bounds__(kAqThreads) void accept_q_walk_kernel(AqArgs a, int only_marked) {
+    __shared__ AqSmem s;
+    if (only_marked) {
+        unsigned int *mark = &a.co_ctl[(size_t)blockIdx.x * 32 + 24];
+        const unsigned int m = *mark;                     // written by the previous launch
+        __syncthreads();                                  // everyone has read it
+        if (m == 0u) return;
+        if (threadIdx.x == 0) *mark = 0u;
+    }
+    walk_single<VEC4>(a, s, blockIdx.x);
+}
+
+// ------------------------------------------------------------------- walk by several workgroups
+// G workgroups per sequence; workgroup g keeps the residual of tokens [g * slice, (g + 1) * slice) in
+// registers (R float4 per lane) for as long as the walk stays at a node, so a rejection costs each
+// of them one 16-byte load per float4 (its part of the draft row) instead of a vocabulary-wide pass
+// by a single CU.  Every workgroup takes the same decisions from the same numbers: after a
+// rejection each publishes the sum of its slice and the residual at the tokens of the children
+// still to be tried, all meet at an arrival counter, and all add the G sums in the same order.
+// The wait at the counter is bounded: a workgroup that gives up (the workgroups of a sequence
+// were not all resident, which the host avoids by keeping G * B within the chip) raises the
+// sequence's abort flag, everyone leaves, and the last one to leave redoes the sequence alone.
+constexpr int kCoG = 32;                     // most workgroups per sequence
+constexpr int kCoR = 4;                      // most float4 per lane (V <= 32 * 4 * 4096; larger vocabularies walk with one workgroup)
+constexpr int kCoCtl = 32;                   // uints per sequence in the control block: arrive, leave, abort, redo mark at 0, 8, 16, 24
+
+struct CoSmem {
+    double wred[kAqWaves];
+    double psum[kCoG];
+    double px[kWave], qx[kWave];
+    int par[kWave], tok[kWave], qrow[kWave];
+    float uni[kWave + 1];
+    double W;
+    unsigned long long kids;
+    int wlast[kAqWaves];
+    int cur, len, next, aborted, pick;
+};
+
+template <bool VEC4>
+__global__ __launch_bounds__(kAqThreads) void accept_q_coop_kernel(AqArgs a) {
+    __shared__ CoSmem s;
+    const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
+    const int g = blockIdx.x, G = gridDim.x, b = blockIdx.y;
+    const int R = a.co_R, slice = R * kAqThreads * 4, lo = g * slice;
+    const int rows_per_seq = a.T + a.Tq;
+    const int nn = a.n_nodes ? min(max(a.n_nodes[b], 0), a.T) : a.T;
+    unsigned int *ctl = a.co_ctl + (size_t)b * kCoCtl;
+    double *psum_g = a.co_psum + (size_t)b * 2 * kCoG;    // [2][kCoG]
+    float *sib_g = a.co_sib + (size_t)b * 2 * kWave;      // [2][64]
+    int32_t *path = a.accept_path + (size_t)b * (a.D_max + 1);
+    unsigned int nsync = 0;
+
+    // leave: every workgroup of the sequence ends here.  The last one to arrive clears the control
+    // block for the next call and learns whether anybody gave up on the way (all their stores are
+    // complete by then); if so it marks the sequence for the launch that follows, in which a single
+    // workgroup redoes it.  (Calling that code from here would give this kernel a stack, which
+    // costs every launch 8 us.)
+    auto leave = [&]() {
+        __syncthreads();
+        if (tid == 0) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            const unsigned int before = __hip_atomic_fetch_add(&ctl[8], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (before == (unsigned int)(G - 1)) {
+                store_shared_result(&ctl[24], load_shared_result(&ctl[16]));
+                store_shared_result(&ctl[0], 0u);
+                store_shared_result(&ctl[8], 0u);
+                store_shared_result(&ctl[16], 0u);
+            }
+        }
+    };
+    // meet: publish this workgroup's sum (and whatever the caller stored before), wait for all G,
+    // return the total.  Sets s.aborted when the wait gave up or somebody else did.
+    auto meet = [&](double mine) -> double {
+        const int par = nsync & 1;
+        ++nsync;
+        if (tid == 0) store_shared_result(&psum_g[par * kCoG + g], mine);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) {
+            __hip_atomic_fetch_add(&ctl[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned int want = nsync * (unsigned int)G;
+            unsigned int spins = 0;
+            int bad = 0;
+            while (__hip_atomic_load(&ctl[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < want) {
+                if (++spins > a.co_spin_limit || load_shared_result(&ctl[16]) != 0u) { bad = 1; break; }
+                __builtin_amdgcn_s_sleep(4);
+            }
+            if (bad) store_shared_result(&ctl[16], 1u);
+            s.aborted = bad;
+        }
+        __syncthreads();
+        if (s.aborted) return 0.0;
+        if (tid < G) s.psum[tid] = load_shared_result(&psum_g[par * kCoG + tid]);
+        __syncthreads();
+        double t = 0.0;
+        for (int i = 0; i < G; ++i) t += s.psum[i];
+        return t;
+    };
+
+    if (tid == 0) s.aborted = load_shared_result(&ctl[16]) != 0u;   // somebody gave up before this workgroup even started
+    if (tid < kWave) {
+        const bool live = tid < nn;
+        s.par[tid] = live ? a.parents[(size_t)b * a.T + tid] : -2;
+        s.tok[tid] = live ? a.tokens[(size_t)b * a.T + tid] : -1;
+        s.qrow[tid] = !live ? -1 : a.q_rows ? a.q_rows[(size_t)b * a.T + tid] : tid;
+        s.uni[tid] = tid <= a.T ? a.uniforms[(size_t)b * (a.T + 1) + tid] : 0.f;
+        if (tid == 0) { s.uni[kWave] = a.T == kWave ? a.uniforms[(size_t)b * (a.T + 1) + kWave] : 0.f; s.cur = 0; s.len = 0; }
+    }
+    // Outputs are written through (agent-scope stores): should the sequence be redone by another
+    // workgroup, on another die, no older copy of them may linger in this die's L2 to be written back later.
+    if (g == 0) for (int d = tid; d <= a.D_max; d += kAqThreads) store_shared_result(&path[d], d == 0 && nn >= 1 ? 0 : -1);
+    __syncthreads();
+    bool fall_back = s.aborted != 0;
+    if (nn < 1) {
+        if (g == 0 && tid == 0) { store_shared_result(&a.accept_len[b], 0); store_shared_result(&a.bonus[b], -1); }
+        leave();                                          // nobody meets on this path, so nobody can have given up
+        return;
+    }
+
+    const float it_f = (float)a.inv_t, itd_f = (float)a.inv_td;
+    float u4[kCoR][4];
+    // this lane's tokens: float4 r covers lo + (r * 1024 + tid) * 4 .. + 3
+    auto load_row = [&](const float *row, float m, float inv_l, float inv_temp, float (&out)[kCoR][4]) {
+#pragma unroll
+        for (int r = 0; r < kCoR; ++r) {
+            if (r < R) {
+                const int i0 = lo + (r * kAqThreads + tid) * 4;
+                float x[4];
+                if (VEC4) {
+                    const float4 v = *reinterpret_cast<const float4 *>(row + (i0 < a.V ? i0 : 0));
+                    x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) x[j] = row[min(i0 + j, a.V - 1)];
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) out[r][j] = (i0 + j < a.V) ? exp_rel_f32(x[j], m, inv_temp) * inv_l : 0.f;
+            }
+        }
+    };
+    auto my_sum = [&]() -> double {
+        double t = 0.0;
+#pragma unroll
+        for (int r = 0; r < kCoR; ++r)
+            if (r < R) t += ((double)u4[r][0] + (double)u4[r][1]) + ((double)u4[r][2] + (double)u4[r][3]);
+        return block_sum_f64(t, s.wred);
+    };
+
+    while (!fall_back) {                                  // one iteration per visited node
+        const int cur = s.cur, len = s.len;
+        const int prow_id = b * rows_per_seq + cur;
+        const float *prow = a.target + ((size_t)b * a.T + cur) * a.V;
+        const float pm = a.row_m[prow_id];
+        const double pinv_l = 1.0 / a.row_l[prow_id];
+        if (w == 0) {
+            const int x = s.tok[lane], qr = s.qrow[lane];
+            const bool kid = lane > cur && lane < nn && s.par[lane] == cur && len < a.D_max && x >= 0 && x < a.V && qr >= 0 && qr < a.Tq;
+            if (kid) {
+                const int qid = b * rows_per_seq + a.T + qr;
+                s.px[lane] = exp_rel(prow[x], pm, a.inv_t) * pinv_l;
+                s.qx[lane] = exp_rel(a.draft[((size_t)b * a.Tq + qr) * a.V + x], a.row_m[qid], a.inv_td) / a.row_l[qid];
+            }
+            const unsigned long long kids = __ballot(kid);
+            if (lane == 0) { s.kids = kids; s.W = 1.0; s.next = -1; }
+        }
+        load_row(prow, pm, (float)pinv_l, it_f, u4);      // u = p_cur on this workgroup's slice
+        __syncthreads();
+        bool rejected_here = false;
+        while (s.kids != 0 && s.next < 0 && s.W > 0.0) {
+            const int c = __ffsll((long long)s.kids) - 1;
+            const double W = s.W;
+            const bool accept = (double)s.uni[c] * W * s.qx[c] < s.px[c];
+            __syncthreads();
+            if (accept) {
+                if (tid == 0) s.next = c;
+            } else {
+                const int qr = s.qrow[c], qid = b * rows_per_seq + a.T + qr;
+                float q4[kCoR][4];
+                load_row(a.draft + ((size_t)b * a.Tq + qr) * a.V, a.row_m[qid], (float)(1.0 / a.row_l[qid]), itd_f, q4);
+                const float W_f = (float)W;
+#pragma unroll
+                for (int r = 0; r < kCoR; ++r)
+                    if (r < R) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) u4[r][j] = fmaxf(0.f, fmaf(-W_f, q4[r][j], u4[r][j]));
+                    }
+                // the residual at the tokens of the children still to be tried: their owners publish it
+                const unsigned long long rest = s.kids & ~(1ull << c);
+                const int par = nsync & 1;
+                for (unsigned long long m = rest; m != 0; m &= m - 1) {
+                    const int c2 = __ffsll((long long)m) - 1;
+                    const int off = s.tok[c2] - lo;
+                    if (off >= 0 && off < slice && ((off >> 2) & (kAqThreads - 1)) == tid) {
+                        const int r2 = off >> 12, j2 = off & 3;                 // float4 index, element
+                        float val = 0.f;
+#pragma unroll
+                        for (int r = 0; r < kCoR; ++r)
+#pragma unroll
+                            for (int j = 0; j < 4; ++j)
+                                if (r == r2 && j == j2) val = u4[r][j];
+                        store_shared_result(&sib_g[par * kWave + c2], val);
+                    }
+                }
+                const double total = meet(my_sum());
+                if (s.aborted) break;
+                if (w == 0 && ((rest >> lane) & 1)) s.px[lane] = (double)load_shared_result(&sib_g[par * kWave + lane]);
+                if (tid == 0) { s.kids = rest; s.W = total; }
+                rejected_here = true;
+            }
+            __syncthreads();
+        }
+        if (s.aborted) { fall_back = true; break; }
+        if (s.next >= 0) {
+            if (tid == 0) {
+                const int c = s.next;
+                s.cur = c;
+                s.len = len + 1;
+                if (g == 0) store_shared_result(&path[len + 1], c);
+            }
+            __syncthreads();
+            continue;
+        }
+        // ---- bonus token.  Everybody needs the G slice sums of what the bonus is drawn from.
+        double W = s.W;
+        __syncthreads();
+        if (!rejected_here || !(W > 0.0)) {               // nothing rejected here, or the residual vanished: draw from p_cur
+            if (rejected_here) load_row(prow, pm, (float)pinv_l, it_f, u4);
+            W = meet(my_sum());
+            if (s.aborted) { fall_back = true; break; }
+        }
+        // (after a rejection s.psum still holds the sums of the last meeting)
+        const double target = (double)s.uni[a.T] * W;
+        int owner = -1, last_pos = -1;
+        double before = 0.0, acc = 0.0;
+        for (int i = 0; i < G; ++i) {
+            if (s.psum[i] > 0.0) last_pos = i;
+            if (owner < 0 && acc + s.psum[i] > target) { owner = i; before = acc; }
+            acc += s.psum[i];
+        }
+        const bool take_last = owner < 0;                 // rounding: the sums never exceed the target
+        if (take_last) owner = last_pos;
+        if (g == 0 && tid == 0) store_shared_result(&a.accept_len[b], len);
+        if (owner < 0) { if (g == 0 && tid == 0) store_shared_result(&a.bonus[b], -1); break; }
+        if (g == owner) {
+            // token order inside the slice: float4 row r, then thread, then element
+            if (tid == 0) s.pick = 0x7fffffff;
+            __syncthreads();
+            double run = before;
+            int lastp = -1;
+            for (int r = 0; r < R; ++r) {                 // uniform; the row is picked by comparison (r is not a constant here)
+                float v[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int rr = 0; rr < kCoR; ++rr)
+                    if (rr == r) { v[0] = u4[rr][0]; v[1] = u4[rr][1]; v[2] = u4[rr][2]; v[3] = u4[rr][3]; }
+                const double lsum = ((double)v[0] + (double)v[1]) + ((double)v[2] + (double)v[3]);
+                const double linc = wave_scan_f64(lsum);
+                if (lane == kWave - 1) s.wred[w] = linc;
+                __syncthreads();
+                double wbefore = run, rtot = 0.0;
+                for (int i = 0; i < kAqWaves; ++i) {
+                    if (i < w) wbefore += s.wred[i];
+                    rtot += s.wred[i];
+                }
+                const int i0 = lo + (r * kAqThreads + tid) * 4;
+                double accl = wbefore + linc - lsum;
+                int pick = -1;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (v[j] > 0.f) lastp = i0 + j;
+                    accl += (double)v[j];
+                    if (pick < 0 && accl > target) pick = i0 + j;
+                }
+                if (pick >= 0 && !take_last) atomicMin(&s.pick, pick);
+                run += rtot;
+                __syncthreads();
+            }
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) lastp = max(lastp, __shfl_xor(lastp, off));
+            if (lane == 0) s.wlast[w] = lastp;
+            __syncthreads();
+            if (tid == 0) {
+                int lp = -1;
+                for (int i = 0; i < kAqWaves; ++i) lp = max(lp, s.wlast[i]);
+                store_shared_result(&a.bonus[b], s.pick != 0x7fffffff ? s.pick : lp);
+            }
+        }
+        break;
+    }
+    (void)fall_back;
+    leave();
+}
+
 }  // namespace radar
 
 using namespace radar;
 
 static int aq_chunks(int V) { return (V + kAqChunk - 1) / kAqChunk; }
+
+// Workgroups per sequence (G) and float4 per lane (R) of the walk; G = 1 means the single-workgroup
+// walk.  All G * B workgroups must be resident together for the arrival counters to make progress,
+// so their number stays within the 256 CUs (one 1024-lane workgroup each).
+static void aq_coop_plan(const radar_accept_q_desc *d, int *G, int *R) {
+    *G = 1; *R = 1;
+    if (d->walk_spin_limit < 0 || d->B > 128) return;
+    const int gcap = 256 / d->B < kCoG ? 256 / d->B : kCoG;
+    const int per_wg = kAqThreads * 4;
+    int r = ((d->V + per_wg - 1) / per_wg + gcap - 1) / gcap;              // float4 per lane needed with gcap workgroups
+    if (r > kCoR) return;
+    if (r < 1) r = 1;
+    const int g = (d->V + per_wg * r - 1) / (per_wg * r);
+    if (g < 2) return;                                                    // one workgroup would cover it anyway
+    *G = g; *R = r;
+}
 
 extern "C" size_t radar_verify_accept_q_workspace_bytes(const radar_accept_q_desc *d) {
     if (!d || d->B < 1 || d->T_max < 1 || d->Tq < 1 || d->V < 1) return 0;
@@ -425,6 +741,9 @@ extern "C" size_t radar_verify_accept_q_workspace_bytes(const radar_accept_q_des
     bytes += (rows * sizeof(double) + 255) & ~size_t(255);
     bytes += (rows * sizeof(float) + 255) & ~size_t(255);
     bytes += ((size_t)d->B * d->V * sizeof(float) + 255) & ~size_t(255);
+    bytes += ((size_t)d->B * kCoCtl * sizeof(unsigned int) + 255) & ~size_t(255);
+    bytes += ((size_t)d->B * 2 * kCoG * sizeof(double) + 255) & ~size_t(255);
+    bytes += ((size_t)d->B * 2 * kWave * sizeof(float) + 255) & ~size_t(255);
     return bytes;
 }
 
@@ -460,6 +779,13 @@ extern "C" radar_status radar_verify_accept_q(const float *target_logits, const 
     a.row_l = reinterpret_cast<double *>(take(rows * sizeof(double)));
     a.row_m = reinterpret_cast<float *>(take(rows * sizeof(float)));
     a.ubuf = reinterpret_cast<float *>(take((size_t)d->B * d->V * sizeof(float)));
+    a.co_ctl = reinterpret_cast<unsigned int *>(take((size_t)d->B * kCoCtl * sizeof(unsigned int)));
+    a.co_psum = reinterpret_cast<double *>(take((size_t)d->B * 2 * kCoG * sizeof(double)));
+    a.co_sib = reinterpret_cast<float *>(take((size_t)d->B * 2 * kWave * sizeof(float)));
+    int G = 1, R = 1;
+    aq_coop_plan(d, &G, &R);
+    a.co_R = R;
+    a.co_spin_limit = d->walk_spin_limit > 0 ? (unsigned int)d->walk_spin_limit : 1000000u;   // roughly a second of polling
 
     const bool vec4 = (d->V % 4 == 0) && (((uintptr_t)target_logits & 15) == 0) && (((uintptr_t)draft_logits & 15) == 0);
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -467,7 +793,16 @@ extern "C" radar_status radar_verify_accept_q(const float *target_logits, const 
     hipError_t e = vec4 ? launch("accept_q_stats", accept_q_stats_kernel<true>, g1, block, 0, st, a)
                         : launch("accept_q_stats", accept_q_stats_kernel<false>, g1, block, 0, st, a);
     if (e != hipSuccess) return RADAR_HIP_ERROR;
-    e = vec4 ? launch("accept_q_walk", accept_q_walk_kernel<true>, g2, block, 0, st, a)
-             : launch("accept_q_walk", accept_q_walk_kernel<false>, g2, block, 0, st, a);
+    if (G > 1) {
+        const dim3 g3((unsigned)G, (unsigned)d->B);
+        e = vec4 ? launch("accept_q_walk_shared", accept_q_coop_kernel<true>, g3, block, 0, st, a)
+                 : launch("accept_q_walk_shared", accept_q_coop_kernel<false>, g3, block, 0, st, a);
+        if (e != hipSuccess) return RADAR_HIP_ERROR;
+        e = vec4 ? launch("accept_q_walk_redo", accept_q_walk_kernel<true>, g2, block, 0, st, a, 1)
+                 : launch("accept_q_walk_redo", accept_q_walk_kernel<false>, g2, block, 0, st, a, 1);
+    } else {
+        e = vec4 ? launch("accept_q_walk", accept_q_walk_kernel<true>, g2, block, 0, st, a, 0)
+                 : launch("accept_q_walk", accept_q_walk_kernel<false>, g2, block, 0, st, a, 0);
+    }
     return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
 }

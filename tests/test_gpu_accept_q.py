@@ -26,10 +26,17 @@ def run_both(oracle, b, x, q_rows=True, **kw):
     qr = x["q_rows"] if q_rows else None
     ref = oracle.verify_accept_q(x["target_logits"], x["draft_logits"], x["draft_tokens"], x["parents"], x["n_nodes"],
                                  x["uniforms"], qr, want_margins=True, **kw)
-    got = b.radar_verify_accept_q(dev(x["target_logits"]), dev(x["draft_logits"]), dev(x["draft_tokens"]), dev(x["parents"]),
-                                  dev(x["n_nodes"]), dev(x["uniforms"]), None if qr is None else dev(qr), **kw)
+    args = (dev(x["target_logits"]), dev(x["draft_logits"]), dev(x["draft_tokens"]), dev(x["parents"]),
+            dev(x["n_nodes"]), dev(x["uniforms"]), None if qr is None else dev(qr))
+    got = [host(t) for t in b.radar_verify_accept_q(*args, **kw)]
+    # the same call with the walk kept to one workgroup per sequence (-1) and with the shared walk's
+    # wait cut to one poll (1: its workgroups give up and the sequence is redone by one): same answers
+    for limit in (-1, 1):
+        alt = [host(t) for t in b.radar_verify_accept_q(*args, walk_spin_limit=limit, **kw)]
+        for u, v in zip(got, alt):
+            assert np.array_equal(u, v), ("walk_spin_limit", limit)
     torch.cuda.synchronize()
-    return ref, [host(t) for t in got]
+    return ref, got
 
 
 def compare(ref, got, min_sure):
