@@ -273,15 +273,28 @@ __global__ __launch_bounds__(kAccThreads) void accept_kernel(AcceptArgs a) {
             dup = dup || (o < c && po == p && to == t);
         }
         if (dup) pc = 0.0;
+        // depth and reach level by level: a lane whose parent is settled takes depth(parent) + 1 and
+        // reach(parent) * its own probability (two lane gathers); as many rounds as the tree is deep.
+        // Nodes with a broken parent count as settled with depth 0 and reach 0.
         int depth = 0;
         double reach = c == 0 ? 1.0 : 0.0, kids = 0.0;       // mass that arrives here / that goes on to children
-        for (int v = 1; v < nn; ++v) {
-            if (!readlane_u32((uint32_t)tree_ok, v)) continue;                   // wave-uniform
+        bool settled = !tree_ok;                             // the root and everything outside the tree
+        for (int round = 0; round < nn; ++round) {
+            if (__ballot(!settled) == 0ull) break;
+            const int src = max(p, 0);
+            const int pd = __shfl(depth, src);
+            const bool ps = __shfl((int)settled, src) != 0;
+            const double pr = __longlong_as_double(__shfl((long long)__double_as_longlong(reach), src));
+            if (!settled && ps) {
+                depth = pd + 1;
+                if (depth > a.D_max) pc = 0.0;               // cut: nothing is handed below D_max
+                reach = pr * pc;
+                settled = true;
+            }
+        }
+        for (int v = 1; v < nn; ++v) {                       // children's mass per parent, summed in node order
             const int pv = (int)readlane_u32((uint32_t)p, v);
-            const int dv = (int)readlane_u32((uint32_t)depth, pv) + 1;
-            const double pcv = dv <= a.D_max ? readlane_f64(pc, v) : 0.0;
-            const double rv = readlane_f64(reach, pv) * pcv;
-            if (lane == v) { depth = dv; reach = rv; }
+            const double pcv = readlane_f64(pc, v);
             if (lane == pv) kids += pcv;
         }
         double stay = 1.0 - kids;
