@@ -332,7 +332,7 @@ int radar_oracle_draft_rerank(const int32_t *pool_tokens, const float *pool_scor
         tree_pool_idx[1 + r] = best;
         int pp = pool_parents[best];
         int pn = (pp < 0) ? 0 : ((pp < pool_count) ? node_of[pp] : -1);
-        if (pn < 0) { status = ORACLE_BAD_TREE; break; }
+        if (pn < 0 || pn >= 1 + r) { status = ORACLE_BAD_TREE; break; }   /* parent missing, itself, or ranked later */
         tree_parents[1 + r] = pn;
         tree_depth[1 + r] = tree_depth[pn] + 1;
     }

@@ -198,3 +198,16 @@ def test_bad_arguments(oracle):
              parents=np.array([-1, 0], np.int32))
     with pytest.raises(oracle.OracleError):
         oracle.draft_rerank(p, 2, 1, 0)
+
+
+def test_rerank_rejects_a_pool_entry_that_is_its_own_parent():
+    """Scores never grow from parent to child, so a kept candidate's parent is kept and ranked earlier; an
+    entry that names itself (or nothing valid) as parent is a malformed pool, not a tree."""
+    import oracle
+    pool = dict(tokens=np.arange(4, dtype=np.int32), scores=np.array([0.0, -1.0, -2.0, -3.0], np.float32),
+                parents=np.array([-1, 0, 2, 1], np.int32))          # entry 2 is its own parent
+    with pytest.raises(oracle.OracleError):
+        oracle.draft_rerank(pool, 4, 4, 7)
+    pool["parents"][2] = 1
+    t = oracle.draft_rerank(pool, 4, 4, 7)
+    assert t["parents"].tolist() == [-1, 0, 1, 2, 2] and t["depth"].tolist() == [0, 1, 2, 3, 3]
