@@ -30,7 +30,7 @@ def build_library(force=True, verbose=False):
     for src in SOURCES:
         sp = os.path.join(CSRC, src)
         if not os.path.exists(sp):
-            continue
+            raise RuntimeError(f"kernel source {sp} is missing")
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
         if force or _stale(obj, [sp] + headers):
             cmd = [HIPCC] + FLAGS + ["-c", sp, "-o", obj]
