@@ -109,17 +109,15 @@ __device__ __forceinline__ void select_frontier(const ExpandArgs &a, ExpandSmem 
     // ---- next frontier: top-k of the candidates by cumulative score (candidate index breaks ties)
     const int nfs = a.F * 16;
     uint64_t top;
-    if (nfs <= 3 * kWave) {
-        uint64_t kk[9];
+    if (nfs <= 4 * kWave) {                                    // F <= 16 rows: four slots per lane
+        uint64_t kk[4];
 #pragma unroll
-        for (int e = 0; e < 9; ++e) kk[e] = 0;
-#pragma unroll
-        for (int e = 0; e < 3; ++e) {
+        for (int e = 0; e < 4; ++e) {
             const int i = topk_slot_of(e);
             const float sc = s.cand_sc[min(i, nfs - 1)];
             kk[e] = (i < nfs && (i & 15) < K) ? make_key(sc, uint32_t((i >> 4) * K + (i & 15))) : 0;
         }
-        top = wave_topk<9>(kk, K, s.wtk[0]);
+        top = wave_topk<4>(kk, K, s.wtk[0]);
     } else {
         top = 0;
         for (int c0 = 0; c0 < nfs; c0 += 8 * kWave) {
@@ -277,8 +275,18 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
     const int nslot = a.nchunks * RADAR_K_MAX;
     for (int fr = w; fr < a.F; fr += kExpWaves) {
         const uint64_t *pk = a.part_keys + (size_t)fr * nslot;
+        const bool few = nslot <= 4 * kWave;                       // up to 16 chunks per row (V <= 131072 at 8 per lane)
         uint64_t kk[9];
-        load_key_block(pk, nslot, 0, K, kk);
+        if (few) {                                                 // four slots per lane: half the loads, a shorter selection
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int i = topk_slot_of(e);
+                const uint64_t key = load_shared_result(pk + min(i, nslot - 1));
+                kk[e] = (i < nslot && (i & 15) < K) ? key : 0;
+            }
+        } else {
+            load_key_block(pk, nslot, 0, K, kk);
+        }
         float ml;
         double ll;
         {                                                          // chunk partials, one chunk per lane first
@@ -289,7 +297,13 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
         }
         const float pscore = a.parent_scores[fr];
         const int ppool = a.parent_pool_idx[fr];
-        const uint64_t top = row_topk(kk, pk, nslot, K, s.wtk[w]);
+        uint64_t top;
+        if (few) {
+            const uint64_t k4[4] = {kk[0], kk[1], kk[2], kk[3]};
+            top = wave_topk<4>(k4, K, s.wtk[w]);
+        } else {
+            top = row_topk(kk, pk, nslot, K, s.wtk[w]);
+        }
         for (int c = lane + kWave; c < a.nchunks; c += kWave) {        // V > 262144 only
             const float m2 = load_shared_result(&a.part_m[(size_t)fr * a.nchunks + c]);
             const double l2 = load_shared_result(&a.part_l[(size_t)fr * a.nchunks + c]);
