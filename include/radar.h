@@ -30,8 +30,12 @@
  *     device workspace whose size the matching *_workspace_bytes query gives.
  *     A workspace must be passed once through radar_workspace_init before its
  *     first use (it holds arrival counters that the kernels leave zeroed
- *     again); it may then be reused by any sequence of calls on ONE
- *     stream.  Calls that share a workspace on different streams race.
+ *     again); it may then be reused by any number of calls of the SAME entry
+ *     point with the SAME descriptor on ONE stream.  Where the counters sit
+ *     depends on the entry point and on the shape, so a workspace that goes
+ *     over to another entry point or another descriptor is passed through
+ *     radar_workspace_init again first.  Calls that share a workspace on
+ *     different streams race.
  *   - Return value: RADAR_OK or a negative radar_status.  Nothing is printed,
  *     thrown or aborted.  On an error no kernel has been launched.
  *   - Device data is not validated (that would need a synchronisation).  The

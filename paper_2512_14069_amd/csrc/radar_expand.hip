@@ -1,9 +1,9 @@
 // Draft-tree expansion and rerank for RADAR's drafting loop (App. A.1, Sec. 2.3,
 // Sec. 4.2 Eq. 3), as single-launch HIP kernels for gfx950.
 //
-// radar_draft_expand: grid (chunks of 4096 logits, frontier rows).  Every
-// workgroup streams its chunk once from HBM with 16-byte loads (the whole
-// step is one read of F*V*4 bytes), keeps its 16 values per lane in registers,
+// radar_draft_expand: grid (chunks of 4096, 8192 or 16384 logits, frontier rows).
+// Every workgroup streams its chunk once from HBM with 16-byte loads (the whole
+// step is one read of F*V*4 bytes), keeps its 4, 8 or 16 values per lane in registers,
 // and leaves (chunk top-k keys, chunk max, chunk sum of exp) in the workspace.
 // Arrival tickets (one counter per row, then one per call) single out the
 // workgroup that finishes last; it merges every row, one wavefront per row
@@ -218,7 +218,7 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
     const double wl = wave_sum_f64(tl);
     if (lane == 0) { s.wave_m[w] = wm; s.wave_l[w] = wl; }
 
-    // ---- top-k of each wavefront's logits, then of the eight lists
+    // ---- top-k of each wavefront's logits, then of the 16 lists
     uint64_t wt;
     {
         constexpr int E1 = EPT < 8 ? EPT : 8;
