@@ -89,11 +89,17 @@ __device__ __forceinline__ void load_block(const float *row, int i_block, int V,
             raw[g].w = row[min(i + 3, V - 1)];
         }
     }
+    const bool tail = i_block + kAccSub > V;                  // wave-uniform: only a row's last block needs masking
 #pragma unroll
     for (int g = 0; g < kAccEPT / 4; ++g) {
         const float v[4] = {raw[g].x, raw[g].y, raw[g].z, raw[g].w};
+        if (tail) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) x[4 * g + j] = (first[g] + j < V) ? v[j] : -INFINITY;
+            for (int j = 0; j < 4; ++j) x[4 * g + j] = (first[g] + j < V) ? v[j] : -INFINITY;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) x[4 * g + j] = v[j];
+        }
     }
 }
 
@@ -114,24 +120,23 @@ __global__ __launch_bounds__(kAccThreads) void accept_kernel(AcceptArgs a) {
         float x[kAccEPT];
         int first[kAccEPT / 4];
         load_block<VEC4, false>(row, sub * kAccSub, a.V, x, first);
-        // the lane's elements come in ascending index order, so "strictly greater" keeps the lowest
-        // index among equal values (and -0.0 ties with +0.0, as the key order has it)
-        float bx = -INFINITY;
-        int bi = first[0];
+        // Largest logit of the block first (lane, then wavefront); only the lanes that hold it look for
+        // its position, lowest index first (-0.0 equals +0.0 here, as in the key order).
+        float tmx = x[0];
 #pragma unroll
-        for (int e = 0; e < kAccEPT; ++e) {
-            const bool better = x[e] > bx;
-            bx = better ? x[e] : bx;
-            bi = better ? first[e / 4] + (e & 3) : bi;
+        for (int e = 1; e < kAccEPT; ++e) tmx = fmaxf(tmx, x[e]);
+        const float wmx = wave_max_f32(tmx);
+        uint32_t bi = 0xffffffffu;
+        if (tmx == wmx) {
+#pragma unroll
+            for (int e = kAccEPT - 1; e >= 0; --e) bi = (x[e] == wmx) ? uint32_t(first[e / 4] + (e & 3)) : bi;
         }
-        uint64_t best = bi < a.V ? make_key(bx, uint32_t(bi)) : 0;
-        best = wave_max_u64(best);
+        bi = ~wave_max_u32(~bi);                                  // lowest index over the wavefront
+        const uint64_t best = bi < (uint32_t)a.V ? make_key(wmx, bi) : 0;
         const size_t pslot = ((size_t)b * a.T + r) * a.nsub + sub;
         if (sampling) {
-            float tm = -INFINITY;
-#pragma unroll
-            for (int e = 0; e < kAccEPT; ++e) tm = fmaxf(tm, x[e] * a.inv_temp_f);
-            const float wm = wave_max_f32(tm);
+            // 1 / temperature > 0 and rounding is monotone, so the largest scaled logit is the scaled largest
+            const float wm = wmx * a.inv_temp_f;
             double tl = 0.0;
             if (wm > -INFINITY) {
 #pragma unroll
