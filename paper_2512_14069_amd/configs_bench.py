@@ -23,7 +23,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--reps", type=int, default=30)
     ap.add_argument("--configs", default="2,4,5")
-    ap.add_argument("--modes", default="greedy,sampling", help="verify-accept modes to time")
+    ap.add_argument("--modes", default="greedy,sampling", help="verify-accept modes to time (none: attention only)")
     args = ap.parse_args()
     import numpy as np
     import torch
@@ -107,6 +107,8 @@ def main():
         torch.cuda.empty_cache()
 
         # ------------------------------------------------------------ verify-accept
+        if not [m for m in args.modes.split(",") if m in ("greedy", "sampling")]:
+            continue
         set_bytes = B * T * V * 4
         nsets = max(2, int(COLD_BYTES // set_bytes) + 1)
         logit_sets = []

@@ -230,41 +230,115 @@ struct GsTileRegs {
 };
 
 template <int D>
+__device__ __forceinline__ void gs_load_k(GsTileRegs<D> &g, const __bf16 *kbase, int kv_ss, int t0, int kend, int tid) {
+    constexpr int CH = GsTileRegs<D>::CH;
+#pragma unroll
+    for (int i = 0; i < GsTileRegs<D>::KL; ++i) {
+        const int c = i * 256 + tid;
+        const int kpos = min(t0 + c / CH, kend - 1);
+        g.r[i] = *reinterpret_cast<const u32x4 *>(kbase + (uint32_t)(kpos * kv_ss + (c % CH) * 8));
+    }
+}
+template <int D>
+__device__ __forceinline__ void gs_load_v(GsTileRegs<D> &g, const __bf16 *vbase, int kv_ss, int t0, int kend, int tid) {
+    constexpr int CH = GsTileRegs<D>::CH;
+    const int item = min(tid - 256, GsTileRegs<D>::VITEMS - 1);
+    const int ch = item % CH, kg = item / CH;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int kpos = t0 + kg * 4 + i;
+        u32x4 v = *reinterpret_cast<const u32x4 *>(vbase + (uint32_t)(min(kpos, kend - 1) * kv_ss + ch * 8));
+        and_mask(v, kpos < kend);
+        g.r[i] = v;
+    }
+}
+template <int D>
 __device__ __forceinline__ void gs_load_tile(GsTileRegs<D> &g, const __bf16 *kbase, const __bf16 *vbase, int kv_ss,
                                              int t0, int kend, int tid) {
-    constexpr int CH = GsTileRegs<D>::CH;
-    if (tid < 256) {                                                       // wave-uniform
-#pragma unroll
-        for (int i = 0; i < GsTileRegs<D>::KL; ++i) {
-            const int c = i * 256 + tid;
-            const int kpos = min(t0 + c / CH, kend - 1);
-            g.r[i] = *reinterpret_cast<const u32x4 *>(kbase + (uint32_t)(kpos * kv_ss + (c % CH) * 8));
-        }
-    } else {
-        const int item = min(tid - 256, GsTileRegs<D>::VITEMS - 1);
-        const int ch = item % CH, kg = item / CH;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int kpos = t0 + kg * 4 + i;
-            u32x4 v = *reinterpret_cast<const u32x4 *>(vbase + (uint32_t)(min(kpos, kend - 1) * kv_ss + ch * 8));
-            and_mask(v, kpos < kend);
-            g.r[i] = v;
-        }
-    }
+    if (tid < 256) gs_load_k<D>(g, kbase, kv_ss, t0, kend, tid);           // wave-uniform
+    else gs_load_v<D>(g, vbase, kv_ss, t0, kend, tid);
 }
 
 template <int D>
-__device__ __forceinline__ void gs_store_tile(const GsTileRegs<D> &g, unsigned char *Ks, unsigned char *Vt, int tid) {
+__device__ __forceinline__ void gs_store_k(const GsTileRegs<D> &g, unsigned char *Ks, int tid) {
     constexpr int CH = GsTileRegs<D>::CH;
-    if (tid < 256) {
 #pragma unroll
-        for (int i = 0; i < GsTileRegs<D>::KL; ++i) {
-            const int c = i * 256 + tid;
-            *reinterpret_cast<u32x4 *>(Ks + ks_off<D>(c / CH, c % CH)) = g.r[i];
-        }
-    } else if (tid - 256 < GsTileRegs<D>::VITEMS) {
+    for (int i = 0; i < GsTileRegs<D>::KL; ++i) {
+        const int c = i * 256 + tid;
+        *reinterpret_cast<u32x4 *>(Ks + ks_off<D>(c / CH, c % CH)) = g.r[i];
+    }
+}
+template <int D>
+__device__ __forceinline__ void gs_store_v(const GsTileRegs<D> &g, unsigned char *Vt, int tid) {
+    constexpr int CH = GsTileRegs<D>::CH;
+    if (tid - 256 < GsTileRegs<D>::VITEMS) {
         const int item = tid - 256;
         store_vt4(Vt, item % CH, item / CH, g.r);
+    }
+}
+template <int D>
+__device__ __forceinline__ void gs_store_tile(const GsTileRegs<D> &g, unsigned char *Ks, unsigned char *Vt, int tid) {
+    if (tid < 256) gs_store_k<D>(g, Ks, tid);
+    else gs_store_v<D>(g, Vt, tid);
+}
+
+// End of a group-share kernel: a lane owns query i; its accumulator registers O(db, r) hold
+// d = 32*db + 8*(r/4) + 4*g2 + r%4 of the transposed output.
+template <int D, typename Acc>
+__device__ __forceinline__ void gs_finish(const AttnArgs &a, Acc O, float m_run, float l_run, int b, int h, int i, int nn,
+                                          int sp, int nsplit) {
+    constexpr int DB = D / 32;
+    const int g2 = lane_id() >> 5;
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (nsplit == 1) {
+        if (i >= a.T) return;
+        __bf16 *orow = a.out + (size_t)b * a.o_sb + (size_t)i * a.o_st + (size_t)h * a.o_sh;
+        const float inv = (i < nn && l_tot > 0.f) ? 1.0f / l_tot : 0.f;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                bf16x4 o4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(i < nn ? O(db, 4 * r4 + e) * inv : 0.f);
+                *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * r4 + 4 * g2) = o4;
+            }
+        if (a.lse && g2 == 0)
+            a.lse[((size_t)b * a.T + i) * a.Hq + h] = (i < nn) ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : 0.f;
+    } else {
+        // Partial result of this key range: the row's output normalised by its own l and by the row's
+        // largest magnitude, as fp16 pairs (d, d+1) -- [D/2][64 rows] words, so that 32 lanes still write
+        // 128 contiguous bytes -- plus (m, l, magnitude) in fp32.  The partials of all ranges together
+        // outweigh the K/V bytes, and writing them is what the tail of this kernel waits for; halving
+        // them costs 2^-11 of the row's largest element in precision, an eighth of the bf16 rounding of
+        // the final output.  Written through: nothing is left dirty in L2 for the end of the kernel.
+        const size_t unit = ((size_t)b * a.Hq + h) * a.max_splits + sp;
+        uint32_t *po = a.part_o + unit * (size_t)(D / 2 * 64);
+        float *pml = a.part_ml + unit * 192;
+        const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+        float amax = 0.f;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) amax = fmaxf(amax, fabsf(O(db, r)));
+        amax = fmaxf(amax, __shfl_xor(amax, 32)) * inv;          // both halves of the row's d range
+        const float mag = amax > 0.f && amax < 3.0e38f ? amax : 1.f;
+        const float scl = inv / mag;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int rp = 0; rp < 8; ++rp) {
+                const int r = 2 * rp;
+                const int d = 32 * db + 8 * (r >> 2) + 4 * g2 + (r & 3);
+                const _Float16 lo = (_Float16)(O(db, r) * scl), hi = (_Float16)(O(db, r + 1) * scl);
+                const uint32_t word = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+                store_shared_result(&po[(d >> 1) * 64 + i], word);
+            }
+        if (g2 == 0) {
+            store_shared_result(&pml[i], m_run);
+            store_shared_result(&pml[64 + i], l_tot);
+            store_shared_result(&pml[128 + i], mag);
+        }
     }
 }
 
@@ -354,59 +428,7 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
         for (int t = 0; t < ntiles; ++t) step(t, regs0, 2);
     }
     if (!active) return;
-
-    // ---- epilogue: a lane owns query i; its registers hold d = 32*db + 8*(r/4) + 4*g2 + r%4
-    const float l_tot = l_run[0] + __shfl_xor(l_run[0], 32);
-    if (nsplit == 1) {
-        if (i >= a.T) return;
-        __bf16 *orow = a.out + (size_t)b * a.o_sb + (size_t)i * a.o_st + (size_t)h * a.o_sh;
-        const float inv = (i < nn && l_tot > 0.f) ? 1.0f / l_tot : 0.f;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                bf16x4 o4;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(i < nn ? oacc[db][0][4 * r4 + e] * inv : 0.f);
-                *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * r4 + 4 * g2) = o4;
-            }
-        if (a.lse && g2 == 0)
-            a.lse[((size_t)b * a.T + i) * a.Hq + h] = (i < nn) ? (m_run[0] + __builtin_amdgcn_logf(l_tot)) * kLn2 : 0.f;
-    } else {
-        // Partial result of this key range: the row's output normalised by its own l and by the row's
-        // largest magnitude, as fp16 pairs (d, d+1) -- [D/2][64 rows] words, so that 32 lanes still write
-        // 128 contiguous bytes -- plus (m, l, magnitude) in fp32.  The partials of all ranges together
-        // outweigh the K/V bytes, and writing them is what the tail of this kernel waits for; halving
-        // them costs 2^-11 of the row's largest element in precision, an eighth of the bf16 rounding of
-        // the final output.  Written through: nothing is left dirty in L2 for the end of the kernel.
-        const size_t unit = ((size_t)b * a.Hq + h) * a.max_splits + sp;
-        uint32_t *po = a.part_o + unit * (size_t)(D / 2 * 64);
-        float *pml = a.part_ml + unit * 192;
-        const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-        float amax = 0.f;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) amax = fmaxf(amax, fabsf(oacc[db][0][r]));
-        amax = fmaxf(amax, __shfl_xor(amax, 32)) * inv;          // both halves of the row's d range
-        const float mag = amax > 0.f && amax < 3.0e38f ? amax : 1.f;
-        const float scl = inv / mag;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int rp = 0; rp < 8; ++rp) {
-                const int r = 2 * rp;
-                const int d = 32 * db + 8 * (r >> 2) + 4 * g2 + (r & 3);
-                const _Float16 lo = (_Float16)(oacc[db][0][r] * scl), hi = (_Float16)(oacc[db][0][r + 1] * scl);
-                const uint32_t word = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
-                store_shared_result(&po[(d >> 1) * 64 + i], word);
-            }
-        if (g2 == 0) {
-            store_shared_result(&pml[i], m_run[0]);
-            store_shared_result(&pml[64 + i], l_tot);
-            store_shared_result(&pml[128 + i], mag);
-        }
-    }
+    gs_finish<D>(a, [&](int db, int r) { return oacc[db][0][r]; }, m_run[0], l_run[0], b, h, i, nn, sp, nsplit);
 }
 
 // Merges the group-share kernel's per-split partials.  A workgroup takes one (sequence, query

@@ -74,6 +74,32 @@ def test_small_cases_match_oracle(oracle, name, kps):
         assert np.all(got[bb, n:] == 0) and np.all(lse[bb, n:] == 0)     # unused rows are zeroed
 
 
+LONG_CASES = {
+    "d128_ragged": shape(2, 8, 2, 128, 40, [1100, 530], [40, 17], [5, 3]),
+    "d64_two_query_blocks": shape(1, 8, 2, 64, 64, [700], [64], [8], k=10),
+    "one_tile_and_root_only": shape(2, 4, 2, 128, 30, [0, 600], [30, 1], [4, 1]),
+    "group_of_3_tail_of_33": shape(1, 6, 2, 128, 20, [1037], [20], [4]),
+}
+
+
+@pytest.mark.parametrize("kps", [512, 1024, 2048])
+@pytest.mark.parametrize("name", list(LONG_CASES))
+def test_long_ranges_match_oracle(oracle, name, kps):
+    """Ranges of eight tiles or more run the software-pipelined kernel: ranges that end after one, two
+    or several tiles, tree rows that straddle a tile or a range boundary, a single range (no merge)."""
+    from paper_2512_14069_amd import binding as b
+    a = LONG_CASES[name]
+    x = synth.attention_inputs(a, seed=synth.seed_for(1, 7 * len(name) + kps // 512), shuffle=True)
+    ref, ref_lse = oracle.tree_attention(x["q"], x["k_cache"], x["v_cache"], x["parents"], x["ctx_lens"],
+                                         x["n_nodes"], want_lse=True)
+    got, lse = run_gpu(b, x, keys_per_split=kps, want_lse=True)
+    for bb in range(a.B):
+        n = a.n_nodes[bb]
+        check_close(got[bb, :n], ref[bb, :n], f"{name} b={bb} kps={kps}")
+        assert np.max(np.abs(lse[bb, :n] - ref_lse[bb, :n])) < 2e-2
+        assert np.all(got[bb, n:] == 0) and np.all(lse[bb, n:] == 0)
+
+
 def test_chain_and_star_trees_depth_63(oracle):
     from paper_2512_14069_amd import binding as b
     a = shape(2, 4, 1, 128, 64, [100, 31], [64, 64], [8, 8], k=10)
