@@ -55,10 +55,14 @@ struct AttnArgs {
     float *part_ml;                        // [B][Hq][max_splits][2][64]: running maximum (log2 units) and sum
 };
 
-// byte offset of the 16-byte chunk `chunk` of cache row `key` in a K tile
+// Byte offset of the 16-byte chunk `chunk` of cache row `key` in a K tile.  The chunks of a row are
+// XOR-swizzled with the row number so that the sixteen lanes of one pass of a 16-byte operand read
+// (sixteen consecutive rows, the same chunk) cover all 64 banks: 16 distinct chunk slots at D = 128
+// (256-byte rows), 8 slots times the two rows of a 256-byte bank period at D = 64.
 template <int D>
 __device__ __forceinline__ int ks_off(int key, int chunk) {
-    return key * (D * 2) + ((chunk ^ (key & 7)) << 4);
+    constexpr int CH = D / 8;
+    return key * (D * 2) + ((chunk ^ ((key >> (CH == 16 ? 0 : 1)) & (CH - 1))) << 4);
 }
 // byte offset of element (d, pos) of a transposed V tile; pos = permuted key slot.
 // 16-byte groups of a row are XOR-swizzled so that both the transposing writes
