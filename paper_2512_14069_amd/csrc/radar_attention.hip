@@ -242,6 +242,8 @@ __device__ __forceinline__ void gs_load_k(GsTileRegs<D> &g, const __bf16 *kbase,
         const int kpos = min(t0 + c / CH, kend - 1);
         g.r[i] = *reinterpret_cast<const u32x4 *>(kbase + (uint32_t)(kpos * kv_ss + (c % CH) * 8));
     }
+#pragma unroll
+    for (int i = GsTileRegs<D>::KL; i < 4; ++i) g.r[i] = g.r[0];           // D = 64 fills two of the four; none stays undefined
 }
 template <int D>
 __device__ __forceinline__ void gs_load_v(GsTileRegs<D> &g, const __bf16 *vbase, int kv_ss, int t0, int kend, int tid) {
