@@ -54,7 +54,7 @@ struct ExpandArgs {
 
 struct alignas(16) ExpandSmem {
     WaveTopkSmem wtk[kExpWaves];                  // one scratch per wavefront
-    uint64_t wtop[kExpWaves * 16];                // the wavefront lists of a chunk
+    uint64_t wlist[kExpWaves * kWaveListSlots];   // the wavefronts' candidates of a chunk (0 = none)
     float wave_m[kExpWaves];
     double wave_l[kExpWaves];
     // last workgroup only: candidate (row f, rank r) at f * 16 + r
@@ -192,60 +192,66 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
         policy_hidden_rows<4>(a.pol, 0, blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y,
                               [&](int r, float v) { store_shared_result(&a.gate_pre[r], v); });
     float x[EPT];
-    uint64_t keys[EPT];
 #pragma unroll
     for (int g = 0; g < EPT / 4; ++g) {
         const int idx0 = base + g * (kExpThreads * 4) + tid * 4;
         const float v[4] = {raw[g].x, raw[g].y, raw[g].z, raw[g].w};
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bool valid = idx0 + j < a.V;
-            x[4 * g + j] = valid ? v[j] : -INFINITY;
-            keys[4 * g + j] = make_key(v[j], uint32_t(idx0 + j)) & (0ull - (uint64_t)valid);   // no branch
-        }
+        for (int j = 0; j < 4; ++j) x[4 * g + j] = (idx0 + j < a.V) ? v[j] : -INFINITY;
     }
 
-    // ---- log-sum-exp partial per wavefront (exp2 of fp32 differences, sums in fp64)
+    // ---- log-sum-exp partial per wavefront (exp2 of fp32 differences; a lane's few terms are added in
+    // fp32, everything after that in fp64)
     float tm = x[0];
 #pragma unroll
     for (int e = 1; e < EPT; ++e) tm = fmaxf(tm, x[e]);
     const float wm = wave_max_f32(tm);
-    double tl = 0.0;
+    float tl = 0.f;
     if (wm > -INFINITY) {
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) tl += (double)__builtin_amdgcn_exp2f((x[e] - wm) * kLog2eF);
+        for (int e = 0; e < EPT; ++e) tl += __builtin_amdgcn_exp2f((x[e] - wm) * kLog2eF);
     }
-    const double wl = wave_sum_f64(tl);
+    const double wl = wave_sum_f64((double)tl);
     if (lane == 0) { s.wave_m[w] = wm; s.wave_l[w] = wl; }
 
-    // ---- top-k of each wavefront's logits, then of the 16 lists
-    uint64_t wt;
+    // ---- candidates of each wavefront (everything that reaches the K-th largest quad maximum; no
+    // ranking yet), then the top-k of the 16 candidate lists
     {
-        constexpr int E1 = EPT < 8 ? EPT : 8;
-        uint64_t kk[E1];
+        uint64_t *list = &s.wlist[w * kWaveListSlots];
+        bool listed = false;
+        if constexpr (EPT <= 8)
+            listed = wave_candidates<EPT>(x, tm, uint32_t(base + tid * 4), uint32_t(kExpThreads * 4), uint32_t(a.V), K, s.wtk[w], list);
+        if (!listed) {                                             // 16 logits per lane, or more than 32 candidates: rank
+            uint64_t keys[EPT];
 #pragma unroll
-        for (int e = 0; e < E1; ++e) kk[e] = keys[e];
-        wt = wave_topk<E1>(kk, K, s.wtk[w]);
-        if (EPT > 8) {                                             // the rest, with the selection so far
-            uint64_t k2[EPT - E1 + 1];
+            for (int e = 0; e < EPT; ++e) {
+                const int idx = base + (e >> 2) * (kExpThreads * 4) + tid * 4 + (e & 3);
+                keys[e] = idx < a.V ? make_key(x[e], uint32_t(idx)) : 0;
+            }
+            constexpr int E1 = EPT < 8 ? EPT : 8;
+            uint64_t kk[E1];
 #pragma unroll
-            for (int e = E1; e < EPT; ++e) k2[e - E1] = keys[e];
-            k2[EPT - E1] = wt;
-            wt = wave_topk<EPT - E1 + 1>(k2, K, s.wtk[w]);
+            for (int e = 0; e < E1; ++e) kk[e] = keys[e];
+            uint64_t wt = wave_topk<E1>(kk, K, s.wtk[w]);
+            if (EPT > 8) {                                         // the rest, with the selection so far
+                uint64_t k2[EPT - E1 + 1];
+#pragma unroll
+                for (int e = E1; e < EPT; ++e) k2[e - E1] = keys[e];
+                k2[EPT - E1] = wt;
+                wt = wave_topk<EPT - E1 + 1>(k2, K, s.wtk[w]);
+            }
+            if (lane < kWaveListSlots) list[lane] = wt;            // lanes 16.. hold 0
         }
     }
-    if (lane < 16) s.wtop[w * 16 + lane] = wt;
     __syncthreads();
 
     const size_t pslot = (size_t)f * a.nchunks + chunk;
     if (w == 0) {
-        uint64_t kk[kExpWaves / 4];                               // 16 lists of 16 slots
+        constexpr int NS = kExpWaves * kWaveListSlots / kWave;    // 16 lists of 32 slots, eight slots per lane
+        uint64_t kk[NS];
 #pragma unroll
-        for (int e = 0; e < kExpWaves / 4; ++e) {
-            const int i = topk_slot_of(e);
-            kk[e] = (i & 15) < K ? s.wtop[i] : 0;
-        }
-        const uint64_t top = wave_topk<kExpWaves / 4>(kk, K, s.wtk[0]);
+        for (int e = 0; e < NS; ++e) kk[e] = s.wlist[topk_slot_of(e)];   // rotated: the used slots lead each list
+        const uint64_t top = wave_topk<NS>(kk, K, s.wtk[0]);
         if (lane < K) store_shared_result(a.part_keys + pslot * RADAR_K_MAX + lane, top);
     } else if (w == 1) {
         float m = s.wave_m[0];

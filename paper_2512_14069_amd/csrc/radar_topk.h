@@ -176,6 +176,43 @@ __device__ __forceinline__ uint64_t wave_topk(const uint64_t (&keys)[EPL], int K
     return lane < 16 ? r : 0;
 }
 
+// Candidates for a later selection, without ranking them: every element of the wavefront whose value
+// reaches tau = the K-th largest quad maximum (so the wavefront's K largest are among them), as
+// proper keys in list[0..32), 0 where there are fewer.  x[e] is element e of the lane (-inf where it
+// lies past the row), its index is idx0 + (e / 4) * gstride + e % 4, indices of a lane ascend with
+// e.  Keys are only built for the survivors (about K + 4 of them on random data).  Returns false,
+// with list untouched, when more than 32 survive (long runs of equal values): the caller then
+// ranks with wave_topk.  All 64 lanes must call; list is wavefront-private LDS.
+constexpr int kWaveListSlots = 32;
+
+template <int EPL>
+__device__ __forceinline__ bool wave_candidates(const float (&x)[EPL], float lane_max, uint32_t idx0, uint32_t gstride,
+                                                uint32_t V, int K, WaveTopkSmem &s, uint64_t *list) {
+    static_assert(EPL <= kWaveTopkMaxEPL, "scratch too small");
+    const int lane = lane_id();
+    // a lane with no element inside the row counts as empty (0), not as a lane holding -inf
+    const uint32_t tau = quad_threshold(idx0 < V ? ord_of(lane_max) : 0u, K);
+    // as a float; thresholds at or below the image of -inf let every element of the row pass
+    const float tau_f = tau < 0x00800000u ? -INFINITY : float_of_ord(tau);
+    int n = 0;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        const uint32_t idx = idx0 + (uint32_t)(e >> 2) * gstride + (uint32_t)(e & 3);
+        const bool keep = x[e] >= tau_f && idx < V;
+        const uint64_t m = __ballot(keep);
+        if (keep) s.surv[n + lanes_below(m)] = (uint64_t(__float_as_uint(x[e])) << 32) | idx;
+        n += __popcll(m);
+    }
+    if (n > kWaveListSlots) return false;
+    wave_lds_sync();
+    if (lane < kWaveListSlots) {
+        const uint64_t raw = s.surv[min(lane, max(n - 1, 0))];
+        list[lane] = lane < n ? make_key(__uint_as_float(uint32_t(raw >> 32)), uint32_t(raw)) : 0;
+    }
+    wave_lds_sync();                              // scratch may be reused right after the return
+    return true;
+}
+
 // Lists of 16 slots of which the first K are used (slot i: list i / 16, rank i % 16), taken 64
 // slots per step: which slot a lane takes at step e.  Lanes rotate by 4 per step, so a lane
 // meets slots of different ranks and every quad of lanes holds used slots.
