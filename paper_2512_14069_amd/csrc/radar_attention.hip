@@ -223,8 +223,8 @@ constexpr int kGsWaves = kGsThreads / kWave;
 // Staging of one 64-row K/V tile by the 512 lanes of the workgroup, four 16-byte loads per lane and
 // no request made twice: lanes 0..255 fetch K (row-major chunks), lanes 256..511 fetch V, one
 // (chunk, four-key group) item each, which they transpose on the way into LDS.  Branch-free loads:
-// rows past the range re-read the last valid row; V is zeroed afterwards (0 * anything must stay
-// 0), K is masked by the softmax.
+// rows past the range re-read the last valid row; V is zeroed on its way into LDS (0 * anything
+// must stay 0), K is masked by the softmax.
 template <int D>
 struct GsTileRegs {
     static constexpr int CH = D / 8;
@@ -253,9 +253,9 @@ __device__ __forceinline__ void gs_load_v(GsTileRegs<D> &g, const __bf16 *vbase,
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int kpos = t0 + kg * 4 + i;
-        u32x4 v = *reinterpret_cast<const u32x4 *>(vbase + (uint32_t)(min(kpos, kend - 1) * kv_ss + ch * 8));
-        and_mask(v, kpos < kend);
-        g.r[i] = v;
+        // rows past the range re-read the last valid row; gs_store_v zeroes them.  (Masking here would make
+        // the wavefront wait for its own loads as soon as it has issued them.)
+        g.r[i] = *reinterpret_cast<const u32x4 *>(vbase + (uint32_t)(min(kpos, kend - 1) * kv_ss + ch * 8));
     }
 }
 template <int D>
@@ -274,18 +274,26 @@ __device__ __forceinline__ void gs_store_k(const GsTileRegs<D> &g, unsigned char
         *reinterpret_cast<u32x4 *>(Ks + ks_off<D>(c / CH, c % CH)) = g.r[i];
     }
 }
+// t0, kend: the tile's first cache row and the end of the range, as given to gs_load_v
 template <int D>
-__device__ __forceinline__ void gs_store_v(const GsTileRegs<D> &g, unsigned char *Vt, int tid) {
+__device__ __forceinline__ void gs_store_v(const GsTileRegs<D> &g, unsigned char *Vt, int t0, int kend, int tid) {
     constexpr int CH = GsTileRegs<D>::CH;
     if (tid - 256 < GsTileRegs<D>::VITEMS) {
-        const int item = tid - 256;
-        store_vt4(Vt, item % CH, item / CH, g.r);
+        const int item = tid - 256, kg = item / CH;
+        u32x4 v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[i] = g.r[i];
+            and_mask(v[i], t0 + kg * 4 + i < kend);                        // 0 * anything must stay 0
+        }
+        store_vt4(Vt, item % CH, kg, v);
     }
 }
 template <int D>
-__device__ __forceinline__ void gs_store_tile(const GsTileRegs<D> &g, unsigned char *Ks, unsigned char *Vt, int tid) {
+__device__ __forceinline__ void gs_store_tile(const GsTileRegs<D> &g, unsigned char *Ks, unsigned char *Vt, int t0, int kend,
+                                              int tid) {
     if (tid < 256) gs_store_k<D>(g, Ks, tid);
-    else gs_store_v<D>(g, Vt, tid);
+    else gs_store_v<D>(g, Vt, t0, kend, tid);
 }
 
 // End of a group-share kernel: a lane owns query i; its accumulator registers O(db, r) hold
@@ -399,7 +407,7 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
         }
     }
     if (tid < RADAR_T_MAX) s_par[tid] = a.parents[(size_t)b * a.T + min(tid, nn - 1)];
-    gs_store_tile<D>(regs0, smem, smem + TILE / 2, tid);
+    gs_store_tile<D>(regs0, smem, smem + TILE / 2, kbeg, kend, tid);
     __syncthreads();
     if (DEEP) { if (ntiles > 2) gs_load_tile<D>(regs0, kbase, vbase, kv_ss, kbeg + 2 * kKT, kend, tid); }
     else if (ntiles > 1) gs_load_tile<D>(regs0, kbase, vbase, kv_ss, kbeg + kKT, kend, tid);
@@ -420,7 +428,7 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
         unsigned char *cur = smem + (t & 1) * TILE, *nxt = smem + ((t + 1) & 1) * TILE;
         if (active) wave_tile<D, 1>(cur, cur + TILE / 2, qop, oacc, m_run, l_run, anc, kbeg + t * kKT, L, kend, t == 0, a.scale_log2);
         if (t + 1 < ntiles) {
-            gs_store_tile<D>(next_regs, nxt, nxt + TILE / 2, tid);
+            gs_store_tile<D>(next_regs, nxt, nxt + TILE / 2, kbeg + (t + 1) * kKT, kend, tid);
             __syncthreads();
             if (t + ahead < ntiles) gs_load_tile<D>(next_regs, kbase, vbase, kv_ss, kbeg + (t + ahead) * kKT, kend, tid);
         }
