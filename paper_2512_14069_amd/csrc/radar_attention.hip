@@ -34,7 +34,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));     // a 16-byte load/store unit kept in registers
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kAttnThreads = 256;
 constexpr int kAttnWaves = 4;
@@ -91,22 +90,6 @@ __device__ __forceinline__ uint64_t ancestor_word(const int *par, int i) {
     int guard = i, p = par[i];
     while (p >= 0 && p < guard) { m |= 1ull << p; guard = p; p = par[p];}
     return m;
-}
-
-// Packs four 16-byte V rows (keys 4*kg .. 4*kg+3, elements 8*ch .. 8*ch+7) into the transposed tile.
-__device__ __forceinline__ void store_vt4(unsigned char *Vt, int ch, int kg, const u32x4 (&v)[4]) {
-    const int pos0 = key_slot(kg * 4);
-#pragma unroll
-    for (int e2 = 0; e2 < 4; ++e2) {
-        // elements 2*e2 (low halves) and 2*e2+1 (high halves) of the four keys
-        u32x2 lo, hi;
-        lo[0] = (v[0][e2] & 0xffffu) | (v[1][e2] << 16);
-        lo[1] = (v[2][e2] & 0xffffu) | (v[3][e2] << 16);
-        hi[0] = (v[0][e2] >> 16) | (v[1][e2] & 0xffff0000u);
-        hi[1] = (v[2][e2] >> 16) | (v[3][e2] & 0xffff0000u);
-        *reinterpret_cast<u32x2 *>(Vt + vt_off(ch * 8 + 2 * e2, pos0)) = lo;
-        *reinterpret_cast<u32x2 *>(Vt + vt_off(ch * 8 + 2 * e2 + 1, pos0)) = hi;
-    }
 }
 
 // One wavefront, one 64-row tile that sits in LDS (Ks row-major swizzled, Vt transposed):
@@ -220,80 +203,65 @@ __device__ __forceinline__ void wave_tile(const unsigned char *Ks, const unsigne
 constexpr int kGsThreads = 512;
 constexpr int kGsWaves = kGsThreads / kWave;
 
-// Staging of one 64-row K/V tile by the 512 lanes of the workgroup, four 16-byte loads per lane and
-// no request made twice: lanes 0..255 fetch K (row-major chunks), lanes 256..511 fetch V, one
-// (chunk, four-key group) item each, which they transpose on the way into LDS.  Branch-free loads:
-// rows past the range re-read the last valid row; V is zeroed on its way into LDS (0 * anything
-// must stay 0), K is masked by the softmax.
+// Staging of one 64-row K/V tile by the 512 lanes of the workgroup, no request made twice and the
+// same work for every wavefront (a wavefront that staged more than the others would reach the tile's
+// barrier after them, and everybody would wait for it): every lane fetches 16-byte chunks of K rows
+// (two at D = 128) and one V item = one chunk of two consecutive cache rows, which it interleaves
+// into the transposed tile with 4-byte LDS writes.  Branch-free loads: rows past the range re-read
+// the last valid row; V is zeroed on its way into LDS (0 * anything must stay 0; masking right
+// after the load would make the wavefront wait for its own loads), K is masked by the softmax.
 template <int D>
 struct GsTileRegs {
-    static constexpr int CH = D / 8;
-    static constexpr int KL = kKT * CH / 256;                              // K loads per K lane (4 at D = 128)
-    static constexpr int VITEMS = CH * (kKT / 4);                          // 256 at D = 128
-    u32x4 r[4];
+    static constexpr int CH = D / 8;                                       // 16-byte chunks per row
+    static constexpr int KL = kKT * CH / 512;                              // K chunks per lane: 2 at D = 128, 1 at D = 64
+    static constexpr int VITEMS = CH * (kKT / 2);                          // (chunk, row pair) items: 512 at D = 128, 256 at D = 64
+    u32x4 k[KL], v[2];
 };
 
 template <int D>
-__device__ __forceinline__ void gs_load_k(GsTileRegs<D> &g, const __bf16 *kbase, int kv_ss, int t0, int kend, int tid) {
-    constexpr int CH = GsTileRegs<D>::CH;
-#pragma unroll
-    for (int i = 0; i < GsTileRegs<D>::KL; ++i) {
-        const int c = i * 256 + tid;
-        const int kpos = min(t0 + c / CH, kend - 1);
-        g.r[i] = *reinterpret_cast<const u32x4 *>(kbase + (uint32_t)(kpos * kv_ss + (c % CH) * 8));
-    }
-#pragma unroll
-    for (int i = GsTileRegs<D>::KL; i < 4; ++i) g.r[i] = g.r[0];           // D = 64 fills two of the four; none stays undefined
-}
-template <int D>
-__device__ __forceinline__ void gs_load_v(GsTileRegs<D> &g, const __bf16 *vbase, int kv_ss, int t0, int kend, int tid) {
-    constexpr int CH = GsTileRegs<D>::CH;
-    const int item = min(tid - 256, GsTileRegs<D>::VITEMS - 1);
-    const int ch = item % CH, kg = item / CH;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int kpos = t0 + kg * 4 + i;
-        // rows past the range re-read the last valid row; gs_store_v zeroes them.  (Masking here would make
-        // the wavefront wait for its own loads as soon as it has issued them.)
-        g.r[i] = *reinterpret_cast<const u32x4 *>(vbase + (uint32_t)(min(kpos, kend - 1) * kv_ss + ch * 8));
-    }
-}
-template <int D>
 __device__ __forceinline__ void gs_load_tile(GsTileRegs<D> &g, const __bf16 *kbase, const __bf16 *vbase, int kv_ss,
                                              int t0, int kend, int tid) {
-    if (tid < 256) gs_load_k<D>(g, kbase, kv_ss, t0, kend, tid);           // wave-uniform
-    else gs_load_v<D>(g, vbase, kv_ss, t0, kend, tid);
-}
-
-template <int D>
-__device__ __forceinline__ void gs_store_k(const GsTileRegs<D> &g, unsigned char *Ks, int tid) {
     constexpr int CH = GsTileRegs<D>::CH;
 #pragma unroll
     for (int i = 0; i < GsTileRegs<D>::KL; ++i) {
-        const int c = i * 256 + tid;
-        *reinterpret_cast<u32x4 *>(Ks + ks_off<D>(c / CH, c % CH)) = g.r[i];
+        const int c = i * 512 + tid;
+        const int kpos = min(t0 + c / CH, kend - 1);
+        g.k[i] = *reinterpret_cast<const u32x4 *>(kbase + (uint32_t)(kpos * kv_ss + (c % CH) * 8));
     }
-}
-// t0, kend: the tile's first cache row and the end of the range, as given to gs_load_v
-template <int D>
-__device__ __forceinline__ void gs_store_v(const GsTileRegs<D> &g, unsigned char *Vt, int t0, int kend, int tid) {
-    constexpr int CH = GsTileRegs<D>::CH;
-    if (tid - 256 < GsTileRegs<D>::VITEMS) {
-        const int item = tid - 256, kg = item / CH;
-        u32x4 v[4];
+    const int item = min(tid, GsTileRegs<D>::VITEMS - 1);
+    const int ch = item % CH, kp = item / CH;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            v[i] = g.r[i];
-            and_mask(v[i], t0 + kg * 4 + i < kend);                        // 0 * anything must stay 0
-        }
-        store_vt4(Vt, item % CH, kg, v);
+    for (int i = 0; i < 2; ++i) {
+        const int kpos = min(t0 + 2 * kp + i, kend - 1);
+        g.v[i] = *reinterpret_cast<const u32x4 *>(vbase + (uint32_t)(kpos * kv_ss + ch * 8));
     }
 }
+
+// t0, kend: the tile's first cache row and the end of the range, as given to gs_load_tile
 template <int D>
 __device__ __forceinline__ void gs_store_tile(const GsTileRegs<D> &g, unsigned char *Ks, unsigned char *Vt, int t0, int kend,
                                               int tid) {
-    if (tid < 256) gs_store_k<D>(g, Ks, tid);
-    else gs_store_v<D>(g, Vt, t0, kend, tid);
+    constexpr int CH = GsTileRegs<D>::CH;
+#pragma unroll
+    for (int i = 0; i < GsTileRegs<D>::KL; ++i) {
+        const int c = i * 512 + tid;
+        *reinterpret_cast<u32x4 *>(Ks + ks_off<D>(c / CH, c % CH)) = g.k[i];
+    }
+    if (tid < GsTileRegs<D>::VITEMS) {
+        const int ch = tid % CH, kp = tid / CH;
+        u32x4 v0 = g.v[0], v1 = g.v[1];
+        and_mask(v0, t0 + 2 * kp < kend);
+        and_mask(v1, t0 + 2 * kp + 1 < kend);
+        const int pos0 = key_slot(2 * kp);                                 // even; the pair's second row sits next to it
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+            // elements 2*e2 (low halves) and 2*e2+1 (high halves) of the two rows
+            const uint32_t lo = (v0[e2] & 0xffffu) | (v1[e2] << 16);
+            const uint32_t hi = (v0[e2] >> 16) | (v1[e2] & 0xffff0000u);
+            *reinterpret_cast<uint32_t *>(Vt + vt_off(ch * 8 + 2 * e2, pos0)) = lo;
+            *reinterpret_cast<uint32_t *>(Vt + vt_off(ch * 8 + 2 * e2 + 1, pos0)) = hi;
+        }
+    }
 }
 
 // End of a group-share kernel: a lane owns query i; its accumulator registers O(db, r) hold
