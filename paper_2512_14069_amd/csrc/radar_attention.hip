@@ -21,8 +21,8 @@
 // comes from HBM once per group of heads.  Two wavefronts per SIMD let one
 // wavefront's MFMAs run underneath the other's softmax arithmetic.  Tiles are
 // double-buffered in LDS (one barrier per tile) and the next tile's global loads
-// are in flight during the arithmetic.  Ranges of cache rows are merged from fp32
-// partials by a small second kernel; how many ranges to cut is decided on the host
+// are in flight during the arithmetic.  Ranges of cache rows are merged from partials
+// (fp16 pairs scaled per row, plus maximum, sum and scale in fp32) by a small second kernel; how many ranges to cut is decided on the host
 // from a cost model that counts whole rounds of resident workgroups and the
 // partial traffic.
 #include "radar_device.h"
@@ -51,7 +51,7 @@ struct AttnArgs {
     int64_t q_sb, q_st, q_sh, kv_sb, kv_sh, kv_ss, o_sb, o_st, o_sh;
     float scale_log2;                      // softmax scale * log2(e), > 0
     uint32_t *part_o;                      // [B][Hq][max_splits][D/2][64]: partial outputs, fp16 pairs (d, d+1), scaled per row
-    float *part_ml;                        // [B][Hq][max_splits][2][64]: running maximum (log2 units) and sum
+    float *part_ml;                        // [B][Hq][max_splits][3][64]: running maximum (log2 units), sum, and the scale of part_o
 };
 
 // Byte offset of the 16-byte chunk `chunk` of cache row `key` in a K tile.  The chunks of a row are
