@@ -222,14 +222,28 @@ template <int D>
 __device__ __forceinline__ void gs_load_tile(GsTileRegs<D> &g, const __bf16 *kbase, const __bf16 *vbase, int kv_ss,
                                              int t0, int kend, int tid) {
     constexpr int CH = GsTileRegs<D>::CH;
+    const int item = min(tid, GsTileRegs<D>::VITEMS - 1);
+    const int ch = item % CH, kp = item / CH;
+    if (t0 + kKT <= kend) {
+        // Whole tile inside the range (all tiles but a range's last): a uniform tile address plus a
+        // byte offset that depends on the lane only, so nothing is computed per tile and per lane.
+        const char *kt = reinterpret_cast<const char *>(kbase + (size_t)t0 * kv_ss);
+        const char *vt = reinterpret_cast<const char *>(vbase + (size_t)t0 * kv_ss);
+        const uint32_t koff = (uint32_t)((tid / CH) * kv_ss + (tid % CH) * 8) * 2u;
+        const uint32_t voff = (uint32_t)(2 * kp * kv_ss + ch * 8) * 2u;
+#pragma unroll
+        for (int i = 0; i < GsTileRegs<D>::KL; ++i)
+            g.k[i] = *reinterpret_cast<const u32x4 *>(kt + (size_t)i * (512 / CH) * kv_ss * 2 + koff);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) g.v[i] = *reinterpret_cast<const u32x4 *>(vt + (size_t)i * kv_ss * 2 + voff);
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < GsTileRegs<D>::KL; ++i) {
         const int c = i * 512 + tid;
         const int kpos = min(t0 + c / CH, kend - 1);
         g.k[i] = *reinterpret_cast<const u32x4 *>(kbase + (uint32_t)(kpos * kv_ss + (c % CH) * 8));
     }
-    const int item = min(tid, GsTileRegs<D>::VITEMS - 1);
-    const int ch = item % CH, kp = item / CH;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int kpos = min(t0 + 2 * kp + i, kend - 1);
@@ -250,8 +264,10 @@ __device__ __forceinline__ void gs_store_tile(const GsTileRegs<D> &g, unsigned c
     if (tid < GsTileRegs<D>::VITEMS) {
         const int ch = tid % CH, kp = tid / CH;
         u32x4 v0 = g.v[0], v1 = g.v[1];
-        and_mask(v0, t0 + 2 * kp < kend);
-        and_mask(v1, t0 + 2 * kp + 1 < kend);
+        if (t0 + kKT > kend) {                                             // wave-uniform: a range's last tile only
+            and_mask(v0, t0 + 2 * kp < kend);
+            and_mask(v1, t0 + 2 * kp + 1 < kend);
+        }
         const int pos0 = key_slot(2 * kp);                                 // even; the pair's second row sits next to it
 #pragma unroll
         for (int e2 = 0; e2 < 4; ++e2) {
