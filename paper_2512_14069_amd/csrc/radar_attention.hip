@@ -218,26 +218,15 @@ struct GsTileRegs {
     u32x4 k[KL], v[2];
 };
 
+// (One straight line of loads, no separate path for tiles that need no clamping: wherever loads sit
+// under a condition the compiler cannot tell how many are in flight at the store, and waits for all
+// of them, the tile after next included.)
 template <int D>
 __device__ __forceinline__ void gs_load_tile(GsTileRegs<D> &g, const __bf16 *kbase, const __bf16 *vbase, int kv_ss,
                                              int t0, int kend, int tid) {
     constexpr int CH = GsTileRegs<D>::CH;
     const int item = min(tid, GsTileRegs<D>::VITEMS - 1);
     const int ch = item % CH, kp = item / CH;
-    if (t0 + kKT <= kend) {
-        // Whole tile inside the range (all tiles but a range's last): a uniform tile address plus a
-        // byte offset that depends on the lane only, so nothing is computed per tile and per lane.
-        const char *kt = reinterpret_cast<const char *>(kbase + (size_t)t0 * kv_ss);
-        const char *vt = reinterpret_cast<const char *>(vbase + (size_t)t0 * kv_ss);
-        const uint32_t koff = (uint32_t)((tid / CH) * kv_ss + (tid % CH) * 8) * 2u;
-        const uint32_t voff = (uint32_t)(2 * kp * kv_ss + ch * 8) * 2u;
-#pragma unroll
-        for (int i = 0; i < GsTileRegs<D>::KL; ++i)
-            g.k[i] = *reinterpret_cast<const u32x4 *>(kt + (size_t)i * (512 / CH) * kv_ss * 2 + koff);
-#pragma unroll
-        for (int i = 0; i < 2; ++i) g.v[i] = *reinterpret_cast<const u32x4 *>(vt + (size_t)i * kv_ss * 2 + voff);
-        return;
-    }
 #pragma unroll
     for (int i = 0; i < GsTileRegs<D>::KL; ++i) {
         const int c = i * 512 + tid;
@@ -378,7 +367,7 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
     // (their time goes into a cold start, where code size counts).
     GsTileRegs<D> regs0, regs1;
     gs_load_tile<D>(regs0, kbase, vbase, kv_ss, kbeg, kend, tid);
-    if (DEEP && ntiles > 1) gs_load_tile<D>(regs1, kbase, vbase, kv_ss, kbeg + kKT, kend, tid);
+    if (DEEP) gs_load_tile<D>(regs1, kbase, vbase, kv_ss, kbeg + kKT, kend, tid);
     // this lane's query operands, kept in registers for the whole kernel: row i, d = 16*st + 8*g2 .. +8
     bf16x8 qop[D / 16];
     {
@@ -393,7 +382,7 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
     if (tid < RADAR_T_MAX) s_par[tid] = a.parents[(size_t)b * a.T + min(tid, nn - 1)];
     gs_store_tile<D>(regs0, smem, smem + TILE / 2, kbeg, kend, tid);
     __syncthreads();
-    if (DEEP) { if (ntiles > 2) gs_load_tile<D>(regs0, kbase, vbase, kv_ss, kbeg + 2 * kKT, kend, tid); }
+    if (DEEP) gs_load_tile<D>(regs0, kbase, vbase, kv_ss, kbeg + 2 * kKT, kend, tid);
     else if (ntiles > 1) gs_load_tile<D>(regs0, kbase, vbase, kv_ss, kbeg + kKT, kend, tid);
     uint64_t anc[1];
     anc[0] = (kend > L && i < nn) ? ancestor_word(s_par, i) : 0ull;
@@ -414,14 +403,19 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
         if (t + 1 < ntiles) {
             gs_store_tile<D>(next_regs, nxt, nxt + TILE / 2, kbeg + (t + 1) * kKT, kend, tid);
             __syncthreads();
-            if (t + ahead < ntiles) gs_load_tile<D>(next_regs, kbase, vbase, kv_ss, kbeg + (t + ahead) * kKT, kend, tid);
         }
+        // Two tiles ahead, the loads are issued whether or not the range still has such a tile (rows past
+        // its end re-read its last row): only if every step issues the same loads does the compiler
+        // know how many are in flight when a set is stored, and wait for that set alone.
+        if (DEEP || t + ahead < ntiles) gs_load_tile<D>(next_regs, kbase, vbase, kv_ss, kbeg + (t + ahead) * kKT, kend, tid);
     };
     if (DEEP) {                                           // unrolled by two: odd tiles travel through regs1, even ones through regs0
-        for (int t = 0; t < ntiles; t += 2) {
+        int t = 0;
+        for (; t + 1 < ntiles; t += 2) {
             step(t, regs1, 3);
-            if (t + 1 < ntiles) step(t + 1, regs0, 3);
+            step(t + 1, regs0, 3);
         }
+        if (t < ntiles) step(t, regs1, 3);
     } else {
         for (int t = 0; t < ntiles; ++t) step(t, regs0, 2);
     }
