@@ -120,15 +120,24 @@ __device__ __forceinline__ void wave_tile(const unsigned char *Ks, const unsigne
     for (int qb = 0; qb < NQB; ++qb) {
         static_assert(NQB == 1, "the query operands of one 32-row block are passed in registers");
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
+        for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int r = 0; r < 16; ++r) sacc[qb][sub][r] = 0.f;
+        // The two sub-tiles take turns (consecutive MFMAs are independent) and the K operands are read
+        // kAhead MFMAs before they are needed, so that an MFMA does not start by waiting for LDS.
+        constexpr int NS = 2 * KSTEPS, kAhead = 4;
+        auto kread = [&](int k) {
+            return *reinterpret_cast<const u32x4 *>(Ks + ks_off<D>(32 * (k & 1) + j32, 2 * (k >> 1) + g2));
+        };
+        u32x4 kf[kAhead];
 #pragma unroll
-            for (int st = 0; st < KSTEPS; ++st) {
-                const u32x4 raw = *reinterpret_cast<const u32x4 *>(Ks + ks_off<D>(32 * sub + j32, 2 * st + g2));
-                sacc[qb][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), qop[st],
-                                                                        sacc[qb][sub], 0, 0, 0);
-            }
+        for (int k = 0; k < kAhead; ++k) kf[k] = kread(k);
+#pragma unroll
+        for (int k = 0; k < NS; ++k) {
+            const u32x4 cur = kf[k % kAhead];
+            if (k + kAhead < NS) kf[k % kAhead] = kread(k + kAhead);
+            sacc[qb][k & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, cur), qop[k >> 1],
+                                                                      sacc[qb][k & 1], 0, 0, 0);
         }
     }
 
@@ -183,16 +192,25 @@ __device__ __forceinline__ void wave_tile(const unsigned char *Ks, const unsigne
         l_run[qb] += rs;
 
         // ---- O^T += V^T P^T for this query block
+        // the output blocks take turns, operands are read kAhead MFMAs ahead as above
+        {
+            constexpr int NP = 4 * DB, kAhead = 4;
+            auto vread = [&](int k) {
+                const int db = k % DB, ss = k / DB;                          // ss = 2 * sub + s2
+                return *reinterpret_cast<const u32x4 *>(Vt + vt_off(32 * db + j32, 16 * ss + 8 * g2));
+            };
+            u32x4 vf[kAhead];
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
+            for (int k = 0; k < kAhead; ++k) vf[k] = vread(k);
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int s2 = 0; s2 < 2; ++s2) {
-                    const u32x4 raw = *reinterpret_cast<const u32x4 *>(Vt + vt_off(32 * db + j32, 32 * sub + 16 * s2 + 8 * g2));
-                    oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), pk[sub][s2],
-                                                                           oacc[db][qb], 0, 0, 0);
-                }
+            for (int k = 0; k < NP; ++k) {
+                const u32x4 cur = vf[k % kAhead];
+                if (k + kAhead < NP) vf[k % kAhead] = vread(k + kAhead);
+                const int db = k % DB, ss = k / DB;
+                oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, cur), pk[ss >> 1][ss & 1],
+                                                                       oacc[db][qb], 0, 0, 0);
+            }
+        }
     }
 }
 
