@@ -139,6 +139,12 @@ __device__ __forceinline__ void wave_tile(const unsigned char *Ks, const unsigne
             sacc[qb][k & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, cur), qop[k >> 1],
                                                                       sacc[qb][k & 1], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);          // the order written above, for the scheduler
+#pragma unroll
+        for (int k = 0; k < NS; ++k) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (k + kAhead < NS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
     }
 
 #pragma unroll
