@@ -1,6 +1,11 @@
 """GPU parity on randomly drawn shapes (fixed seeds): every entry point against the CPU oracle at sizes
 nobody picked by hand -- vocabularies that are not multiples of 4 or of a block, k equal to V, trees of one
-node, group sizes that leave wavefronts idle, odd batch sizes.  Same bars as the hand-written cases."""
+node, group sizes that leave wavefronts idle, odd batch sizes.  Same bars as the hand-written cases.
+
+RADAR_TEST_EXTRA_SEEDS=n in the environment adds n further seeds to every test of this file (a sweep of
+n = 1000 takes about a minute on the GPU)."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -9,6 +14,8 @@ from paper_2512_14069_amd import synth
 from gpu_util import bf16_dev, bf16_bits, dev, host
 
 pytestmark = pytest.mark.gpu
+
+EXTRA = int(os.environ.get("RADAR_TEST_EXTRA_SEEDS", "0"))
 
 
 def rand_tree(rng, n, k, V):
@@ -21,7 +28,7 @@ def rand_tree(rng, n, k, V):
     return par, tok
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", range(12 + EXTRA))
 def test_attention_random_shapes(oracle, seed):
     from paper_2512_14069_amd import binding as b
     rng = np.random.default_rng(synth.seed_for(51, seed))
@@ -51,7 +58,7 @@ def test_attention_random_shapes(oracle, seed):
         assert np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30) <= 1e-2
 
 
-@pytest.mark.parametrize("seed", range(16))
+@pytest.mark.parametrize("seed", range(16 + EXTRA))
 def test_expand_random_shapes(oracle, seed):
     from paper_2512_14069_amd import binding as b
     rng = np.random.default_rng(synth.seed_for(52, seed))
@@ -91,7 +98,7 @@ def test_expand_random_shapes(oracle, seed):
         assert np.array_equal(host(getattr(t, name)), tree[name]), (seed, name)
 
 
-@pytest.mark.parametrize("seed", range(16))
+@pytest.mark.parametrize("seed", range(16 + EXTRA))
 def test_accept_random_shapes(oracle, seed):
     from paper_2512_14069_amd import binding as b
     rng = np.random.default_rng(synth.seed_for(53, seed))
@@ -127,7 +134,7 @@ def test_accept_random_shapes(oracle, seed):
     assert np.max(np.abs(host(dist) - dref)) <= 1e-6, (seed, B, T, V)
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", range(12 + EXTRA))
 def test_accept_q_random_shapes(oracle, seed):
     from paper_2512_14069_amd import binding as b
     rng = np.random.default_rng(synth.seed_for(54, seed))
@@ -151,7 +158,7 @@ def test_accept_q_random_shapes(oracle, seed):
             assert np.array_equal(r_[ok], host(g_)[ok]), (seed, limit, B, T, V)
 
 
-@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("seed", range(8 + EXTRA))
 def test_policy_random_shapes(oracle, seed):
     from paper_2512_14069_amd import binding as b
     rng = np.random.default_rng(synth.seed_for(55, seed))
