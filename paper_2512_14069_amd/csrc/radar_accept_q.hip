@@ -1,7 +1,7 @@
 // radar_verify_accept_q: verification with draft distributions (Sec. 3, Eq. 1-2), for trees
 // whose tokens were drawn from the draft model's distributions.
 //
-// Two launches.  (1) Row statistics, spread over the whole chip: one workgroup per 16384
+// Two launches, or three when the walk is shared.  (1) Row statistics, spread over the whole chip: one workgroup per 16384
 // logits of every target row and every draft row streams its chunk once and leaves (max, sum
 // of exp) partials; the workgroup that completes a row (arrival ticket) merges them into the
 // row's normaliser.  This is the HBM-bound part: it reads every logit once.  (2) The walk, one
@@ -10,7 +10,9 @@
 // workgroup that turns the unnormalised residual u into max(0, u - W q) (W = sum u), keeps it
 // in a workspace row and leaves sums per 256 tokens in LDS; the bonus token is then found from
 // those sums without another pass.  A walk that ends without a rejection draws the bonus from
-// the row's chunk partials and one 16384-token chunk.
+// the row's chunk partials and one 16384-token chunk.  Where the chip has room the walk of a
+// sequence is shared by up to 32 workgroups instead (further down), followed by a launch that
+// redoes, with one workgroup, any sequence whose workgroups could not meet.
 #include "radar_device.h"
 #include "radar_host.h"
 
