@@ -70,6 +70,24 @@ def test_config2_shape(oracle, mode):
     compare(oracle, b, x, mode, require_all=(mode == 1))
 
 
+def test_config4_ragged_full_size(oracle):
+    """Configuration 4 at full size: 16 sequences with trees of 2..60 nodes, V = 128256, greedy."""
+    from paper_2512_14069_amd import binding as b
+    c = synth.config(4)
+    x = synth.accept_inputs(c.attn, c.vocab, seed=synth.seed_for(4, 3), plant=0.75)
+    ref, _ = compare(oracle, b, x, 0)
+    assert ref[0].max() >= 2 and ref[0].min() <= 1       # accepted lengths are spread
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_config5_full_size(oracle, mode):
+    """Configuration 5 at full size: four sequences of 60 rows, V = 128256, greedy and sampled."""
+    from paper_2512_14069_amd import binding as b
+    c = synth.config(5)
+    x = synth.accept_inputs(c.attn, c.vocab, seed=synth.seed_for(5, mode), plant=0.75)
+    compare(oracle, b, x, mode)
+
+
 @pytest.mark.parametrize("mode,temperature", [(0, 1.0), (1, 1.0), (1, 0.6)])
 def test_ragged_batch(oracle, mode, temperature):
     from paper_2512_14069_amd import binding as b
