@@ -367,7 +367,10 @@ radar_status radar_draft_expand_policy(const float *logits, const float *parent_
  * made.  The host enqueues the longest cycle it allows (t_max draft calls,
  * Sec. 4.2) once -- directly or captured in a HIP graph -- and never reads a
  * result in between:
- *   radar_cycle_begin          resets the state (one small kernel, no memset)
+ *   radar_cycle_begin          resets the state (one small kernel, no memset);
+ *       not needed before a cycle whose first draft call is made through
+ *       radar_draft_expand_cycle with desc->pool_count == 0: that call starts
+ *       the cycle itself (it ignores what the state holds and writes all of it)
  *   radar_draft_expand_cycle   one draft call's expansion; does NOTHING (every
  *       workgroup leaves at once, no output is touched) when the state says
  *       stopped; otherwise radar_draft_expand with the pool count taken from
@@ -378,7 +381,8 @@ radar_status radar_draft_expand_policy(const float *logits, const float *parent_
  *       is needed after it).  desc->pool_count is the LARGEST count the state
  *       can hold when this call runs (what it would be had every earlier call
  *       run): the capacity check uses it, and a state outside [0, that] makes
- *       the call a no-op.
+ *       the call a no-op.  With desc->pool_count == 0 the call is the first
+ *       of a cycle and always runs.
  *   radar_draft_rerank_cycle   radar_draft_rerank over the candidates the state
  *       counts (at most pool_count_max).
  * Because a skipped call leaves its outputs alone, the frontier arrays chained

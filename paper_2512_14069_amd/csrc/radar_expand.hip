@@ -158,7 +158,10 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
     __shared__ ExpandSmem s;
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int f = blockIdx.y, chunk = blockIdx.x;
-    if (cycle) {
+    // The first draft call of a cycle (the host says so: the largest count the state may hold is 0)
+    // never reads the state; its last workgroup writes all of it.
+    const bool cycle_first = cycle != nullptr && a.pool_count == 0;
+    if (cycle && !cycle_first) {
         // A drafting cycle that has stopped skips its remaining draft calls: every workgroup leaves
         // before touching anything.  (The state is only written by the last workgroup of a launch,
         // after every other workgroup has handed over its results, i.e. long after this read.)
@@ -343,7 +346,8 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
             select_frontier(a, s, nullptr);
             if (cycle && lane == 0) {
                 cycle->pool_count = a.pool_count + a.F * a.k;
-                cycle->steps_done += 1;
+                cycle->steps_done = cycle_first ? 1 : cycle->steps_done + 1;
+                if (cycle_first) { cycle->stopped = 0; cycle->last_action = -1; }
             }
         }
         return;
@@ -359,9 +363,10 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
         [&](int action) {
             if (cycle) {
                 cycle->pool_count = a.pool_count + a.F * a.k;
-                cycle->steps_done += 1;
+                cycle->steps_done = cycle_first ? 1 : cycle->steps_done + 1;
                 cycle->last_action = action;
                 if (action == 0) cycle->stopped = 1;
+                else if (cycle_first) cycle->stopped = 0;
             }
         });
 }

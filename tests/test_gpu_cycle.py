@@ -87,9 +87,10 @@ class DeviceCycle:
         self.target.copy_(torch.from_numpy(x["target"]))
         self.acc_uni.copy_(torch.from_numpy(x["acc_uni"]))
 
-    def enqueue(self):
+    def enqueue(self, begin=True):
         b = self.b
-        b.radar_cycle_begin(self.state)
+        if begin:                                        # optional: the first draft call starts the cycle itself
+            b.radar_cycle_begin(self.state)
         ps, pi, count_max = self.ps0, self.pi0, 0
         for s in range(T_MAX):
             decide = s + 1 < T_MAX
@@ -154,6 +155,24 @@ def test_cycle_stops_on_the_device_where_the_oracle_chain_stops(oracle, V, stop_
     for _ in range(2):                                   # twice on the same buffers: a skipped call leaves no trace
         cyc.load(x)
         cyc.enqueue()
+        check(oracle, cyc, x, ref)
+
+
+def test_cycles_back_to_back_without_cycle_begin(oracle):
+    """The first draft call of a cycle (descriptor count 0) ignores what the state holds and rewrites
+    all of it: cycles that stop early, late and not at all follow each other with no reset in between."""
+    from paper_2512_14069_amd import binding as b
+    V = 32000
+    rng = np.random.default_rng(synth.seed_for(41, 55))
+    p = synth.policy_params(rng, K, 128, 128, 2.0)
+    cyc = DeviceCycle(b, V, p)
+    cyc.state.fill_(123)                                 # never initialised
+    for stop_after in (2, 8, 1, 5, 8, 3):
+        x = make_inputs(rng, V, stop_after)
+        ref = oracle_cycle(oracle, x, p, V)
+        assert ref["steps"] == stop_after
+        cyc.load(x)
+        cyc.enqueue(begin=False)
         check(oracle, cyc, x, ref)
 
 
@@ -228,9 +247,15 @@ def test_argument_errors(oracle):
     pp4 = b.policy_params({n: dev(v) for n, v in synth.policy_params(rng, 4, 128, 128).items()})
     with pytest.raises(b.RadarError):                      # model built for another k
         b.radar_draft_expand_cycle(cyc.logits[0], cyc.ps0, cyc.pi0, K, cyc.pool, 0, cyc.state, params=pp4)
-    # a state that claims more candidates than the host allows turns the call into a no-op
-    cyc.state.copy_(torch.tensor([0, 50, 0, -1], dtype=torch.int32))
-    cyc.eouts[0].frontier_tokens.fill_(-7)
+    # a state that claims more candidates than the host allows turns a later call into a no-op
+    cyc.state.copy_(torch.tensor([0, 50, 1, -1], dtype=torch.int32))
+    cyc.eouts[1].frontier_tokens.fill_(-7)
+    b.radar_draft_expand_cycle(cyc.logits[1], cyc.eouts[0].frontier_scores, cyc.eouts[0].frontier_pool_idx, K, cyc.pool, K,
+                               cyc.state, out=cyc.eouts[1])
+    torch.cuda.synchronize()
+    assert host(cyc.state).tolist() == [0, 50, 1, -1] and np.all(host(cyc.eouts[1].frontier_tokens) == -7)
+    # while a call whose descriptor says 0 starts a cycle whatever the state holds
+    cyc.state.copy_(torch.tensor([1, 50, 7, 0], dtype=torch.int32))
     b.radar_draft_expand_cycle(cyc.logits[0], cyc.ps0, cyc.pi0, K, cyc.pool, 0, cyc.state, out=cyc.eouts[0])
     torch.cuda.synchronize()
-    assert host(cyc.state).tolist() == [0, 50, 0, -1] and np.all(host(cyc.eouts[0].frontier_tokens) == -7)
+    assert host(cyc.state).tolist() == [0, K, 1, -1]
