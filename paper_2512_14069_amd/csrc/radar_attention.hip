@@ -536,7 +536,7 @@ static AttnPlan plan_attention(const radar_attn_desc *d) {
         // Number of key ranges: the one that minimises a small cost model, in units of one tile of
         // one workgroup (measured ~2.7 us): rounds of 256 resident workgroups x (tiles per range +
         // 3 for prologue and epilogue), plus what the merge of the ranges costs (every range writes
-        // and re-reads T*Hq*D fp32 of partial output, which soon exceeds the KV bytes themselves).
+        // and re-reads T*Hq*D fp16 of partial output, which soon exceeds the KV bytes themselves).
         // Counting whole rounds matters: 576 workgroups take as long as 768.
         const long units = (long)d->B * d->Hkv * p.n_ublk;
         const long tiles_all = ((long)d->S_max + kKT - 1) / kKT;
@@ -549,7 +549,7 @@ static AttnPlan plan_attention(const radar_attn_desc *d) {
             if (cost < best) { best = cost; best_ns = ns; }
         }
         kps = (tiles_all + best_ns - 1) / best_ns * kKT;
-}
+    }
     p.kps = (int)kps;
     p.max_splits = (int)(((long)d->S_max + kps - 1) / kps);
     size_t off = 0;
