@@ -285,7 +285,9 @@ def main():
                    "context": A.ctx_lens[0], "tree_rows": A.T, "q_heads": A.Hq, "kv_heads": A.Hkv, "head_dim": A.D,
                    "vocab": V, "k": k, "frontier_rows": F, "expand_calls": steps_per_cycle, "rerank_N": N,
                    "prediction_model": args.policy,
-                   "cache": "cold: inputs rotate through %d MB (attention) / %d MB (logits)" % (
+                   # cold only if every rotation exceeds what L2 and the 256 MB memory-side cache can hold
+                   "cache": "%s: inputs rotate through %d MB (attention) / %d MB (logits)" % (
+                       "cold" if min(attn_bytes * len(attn_sets), ea_bytes * len(cycle_sets)) > 512 * 2**20 else "warm",
                        attn_bytes * len(attn_sets) // 2**20, ea_bytes * len(cycle_sets) // 2**20)},
         "attention_us": round(a_us, 2),
         "attention_pct_peak_hbm": round(100 * attn_gbps / PEAK_HBM_GBPS, 2),
