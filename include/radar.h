@@ -414,6 +414,40 @@ radar_status radar_draft_rerank_cycle(const int32_t *pool_tokens, const float *p
                                       int32_t *tree_depth, int32_t *tree_pool_idx, int32_t *n_nodes_out,
                                       void *workspace, size_t workspace_bytes, void *stream);
 
+/* --------------------------------------------------------------------------
+ * One draft call for B sequences in ONE launch (the batch the other two steps
+ * already take; Sec. 4.1-4.2: every sequence runs its own cycle and stops at
+ * its own draft call, which is what makes the batch's trees ragged).
+ *
+ * Sequence b is an independent radar_draft_expand_cycle (states != NULL),
+ * radar_draft_expand_policy (states == NULL, params != NULL) or
+ * radar_draft_expand (both NULL): same results, same limits.  Every array of
+ * those calls gains a leading dimension B, densely packed:
+ * logits [B,F,V]; parent_scores, parent_pool_idx [B,F]; cand_* [B,F*k];
+ * frontier_* [B,k]; pool_* [B,pool_capacity]; states [B]; and in io: h_in,
+ * c_in, h_out, c_out [B,H], uniform [B], logits, probs [B,2], action [B].
+ * desc (F, V, k, pool_count, pool_capacity) is shared by all sequences:
+ * without states every sequence's pool holds desc->pool_count candidates; with
+ * states each holds its own state's count, desc->pool_count being the largest
+ * any may have, and a sequence whose state says stopped is skipped (its
+ * workgroups leave at once) while the others run.  The model's weights
+ * (params) are shared.
+ * Limits: 1 <= B <= 65535.  The workspace is sized by
+ * radar_draft_expand_batch_workspace_bytes(desc, B) (equal to
+ * radar_draft_expand_workspace_bytes(desc) for B = 1).
+ */
+size_t radar_draft_expand_batch_workspace_bytes(const radar_expand_desc *desc, int32_t B);
+
+radar_status radar_draft_expand_batch(const float *logits, const float *parent_scores, const int32_t *parent_pool_idx,
+                                      int32_t *cand_tokens, float *cand_scores,
+                                      int32_t *frontier_pool_idx, int32_t *frontier_tokens,
+                                      float *frontier_scores, float *frontier_conf,
+                                      int32_t *pool_tokens, float *pool_scores, int32_t *pool_parents,
+                                      const radar_expand_desc *desc, int32_t B,
+                                      const radar_policy_params *params, const radar_policy_io *io,
+                                      radar_cycle_state *states,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+
 /* Counts, per call, the nodes i < n_nodes[b] whose parent breaks the tree
  * convention; *bad_count_out (device i32) is overwritten.  parents i32
  * [B,T_max]; n_nodes i32 [B] or NULL. */

@@ -75,6 +75,7 @@ EXPORTS = [
     "radar_draft_expand_workspace_bytes", "radar_draft_expand", "radar_draft_expand_policy",
     "radar_draft_rerank_workspace_bytes", "radar_draft_rerank",
     "radar_cycle_begin", "radar_draft_expand_cycle", "radar_draft_rerank_cycle",
+    "radar_draft_expand_batch_workspace_bytes", "radar_draft_expand_batch",
     "radar_verify_accept_workspace_bytes", "radar_verify_accept",
     "radar_accept_length_distribution", "radar_policy_step",
     "radar_verify_accept_q_workspace_bytes", "radar_verify_accept_q",
@@ -112,6 +113,11 @@ def load():
     lib.radar_cycle_begin.argtypes = [vp, vp]
     lib.radar_draft_expand_cycle.restype = i32
     lib.radar_draft_expand_cycle.argtypes = [vp] * 12 + [ctypes.POINTER(ExpandDesc), ctypes.POINTER(PolicyParams),
+                                             ctypes.POINTER(PolicyIO), vp, vp, sz, vp]
+    lib.radar_draft_expand_batch_workspace_bytes.restype = sz
+    lib.radar_draft_expand_batch_workspace_bytes.argtypes = [ctypes.POINTER(ExpandDesc), i32]
+    lib.radar_draft_expand_batch.restype = i32
+    lib.radar_draft_expand_batch.argtypes = [vp] * 12 + [ctypes.POINTER(ExpandDesc), i32, ctypes.POINTER(PolicyParams),
                                              ctypes.POINTER(PolicyIO), vp, vp, sz, vp]
     lib.radar_draft_rerank_cycle.restype = i32
     lib.radar_draft_rerank_cycle.argtypes = [vp] * 4 + [i32, i32, i32] + [vp] * 6 + [vp, sz, vp]
@@ -262,24 +268,27 @@ def radar_tree_attention(q, k_cache, v_cache, parents, ctx_lens, n_nodes=None, o
 # ------------------------------------------------------------ draft expansion
 
 class DraftPool:
-    """Caller-owned pool arrays (tokens, scores, parents) and the host-side count."""
+    """Caller-owned pool arrays (tokens, scores, parents) and the host-side count; with B, the pools of
+    B sequences ([B, capacity] arrays, one count for all)."""
 
-    def __init__(self, capacity, device="cuda"):
+    def __init__(self, capacity, device="cuda", B=None):
         self.capacity = int(capacity)
-        self.tokens = torch.zeros(self.capacity, dtype=torch.int32, device=device)
-        self.scores = torch.zeros(self.capacity, dtype=torch.float32, device=device)
-        self.parents = torch.zeros(self.capacity, dtype=torch.int32, device=device)
+        shape = (self.capacity,) if B is None else (int(B), self.capacity)
+        self.tokens = torch.zeros(shape, dtype=torch.int32, device=device)
+        self.scores = torch.zeros(shape, dtype=torch.float32, device=device)
+        self.parents = torch.zeros(shape, dtype=torch.int32, device=device)
         self.count = 0
 
 
 class ExpandOut:
-    def __init__(self, F, k, device):
-        self.cand_tokens = torch.empty(F * k, dtype=torch.int32, device=device)
-        self.cand_scores = torch.empty(F * k, dtype=torch.float32, device=device)
-        self.frontier_pool_idx = torch.empty(k, dtype=torch.int32, device=device)
-        self.frontier_tokens = torch.empty(k, dtype=torch.int32, device=device)
-        self.frontier_scores = torch.empty(k, dtype=torch.float32, device=device)
-        self.frontier_conf = torch.empty(k, dtype=torch.float32, device=device)
+    def __init__(self, F, k, device, B=None):
+        lead = () if B is None else (int(B),)
+        self.cand_tokens = torch.empty(lead + (F * k,), dtype=torch.int32, device=device)
+        self.cand_scores = torch.empty(lead + (F * k,), dtype=torch.float32, device=device)
+        self.frontier_pool_idx = torch.empty(lead + (k,), dtype=torch.int32, device=device)
+        self.frontier_tokens = torch.empty(lead + (k,), dtype=torch.int32, device=device)
+        self.frontier_scores = torch.empty(lead + (k,), dtype=torch.float32, device=device)
+        self.frontier_conf = torch.empty(lead + (k,), dtype=torch.float32, device=device)
 
 
 def expand_desc(F, V, k, pool_count, pool_capacity):
@@ -434,6 +443,62 @@ def radar_draft_expand_cycle(logits, parent_scores, parent_pool_idx, k, pool, po
         _ptr(state, torch.int32, "state"), wp, wn, _stream())
     keep = (logits, parent_scores, parent_pool_idx, out, pool, desc, workspace, pp, held, io, h, c, uniform, policy_out, state)
     return _finish("radar_draft_expand_cycle", load().radar_draft_expand_cycle, args, keep, (out, policy_out), prepared)
+
+
+def radar_draft_expand_batch_workspace_bytes(desc, B):
+    return int(load().radar_draft_expand_batch_workspace_bytes(ctypes.byref(desc), int(B)))
+
+
+def radar_draft_expand_batch(logits, parent_scores, parent_pool_idx, k, pool, states=None, pool_count_max=None, params=None,
+                             h=None, c=None, uniform=None, out=None, policy_out=None, workspace=None, prepared=False):
+    """One draft call for B sequences in one launch.  logits f32 [B,F,V]; parent_scores f32, parent_pool_idx i32
+    [B,F]; pool: DraftPool(capacity, B=B).  states None: every sequence's pool holds pool.count candidates
+    (pool.count advances by F*k); states i32 [B,4]: per-sequence cycle states as in radar_draft_expand_cycle
+    (pool_count_max required, pool.count untouched).  params None: no decision; otherwise h, c f32 [B,H] or
+    None, uniform f32 [B] or None.  Returns (ExpandOut, PolicyOut or None), both with a leading B."""
+    B, F, V = logits.shape
+    if tuple(pool.tokens.shape) != (B, pool.capacity):
+        raise ValueError("pool: expected DraftPool(capacity, B=%d)" % B)
+    if states is not None and pool_count_max is None:
+        raise ValueError("a call with states needs pool_count_max")
+    desc = expand_desc(F, V, k, int(pool.count if states is None else pool_count_max), pool.capacity)
+    if out is None:
+        out = ExpandOut(F, k, logits.device, B=B)
+    if workspace is None:
+        workspace = new_workspace(radar_draft_expand_batch_workspace_bytes(desc, B), logits.device)
+    pp = held = io = None
+    if params is not None:
+        pp, held = params
+        if policy_out is None:
+            policy_out = PolicyOut(B, pp.H, logits.device)
+        if (h is None) != (c is None):
+            raise ValueError("h and c must be given together")
+        for n, t, want in (("h", h, B * pp.H), ("c", c, B * pp.H), ("uniform", uniform, B)):
+            if t is not None and t.numel() != want:
+                raise ValueError(f"{n}: expected {want} elements, got {t.numel()}")
+        io = PolicyIO()
+        val = lambda t, dt, n: None if t is None else _ptr(_dense(t, n), dt, n).value
+        io.h_in, io.c_in = val(h, torch.float32, "h"), val(c, torch.float32, "c")
+        io.uniform = val(uniform, torch.float32, "uniform")
+        io.h_out, io.c_out = policy_out.h.data_ptr(), policy_out.c.data_ptr()
+        io.logits, io.probs, io.action = policy_out.logits.data_ptr(), policy_out.probs.data_ptr(), policy_out.action.data_ptr()
+    if states is not None and states.numel() != 4 * B:
+        raise ValueError("states: expected [B, 4] int32")
+    wp, wn = _ws_args(workspace)
+    args = (
+        _ptr(_dense(logits, "logits"), torch.float32, "logits"),
+        _ptr(_dense(parent_scores, "parent_scores"), torch.float32, "parent_scores"),
+        _ptr(_dense(parent_pool_idx, "parent_pool_idx"), torch.int32, "parent_pool_idx"),
+        _ptr(out.cand_tokens, torch.int32), _ptr(out.cand_scores, torch.float32),
+        _ptr(out.frontier_pool_idx, torch.int32), _ptr(out.frontier_tokens, torch.int32),
+        _ptr(out.frontier_scores, torch.float32), _ptr(out.frontier_conf, torch.float32),
+        _ptr(pool.tokens, torch.int32), _ptr(pool.scores, torch.float32), _ptr(pool.parents, torch.int32),
+        ctypes.byref(desc), int(B), None if pp is None else ctypes.byref(pp), None if io is None else ctypes.byref(io),
+        None if states is None else _ptr(_dense(states, "states"), torch.int32, "states"), wp, wn, _stream())
+    keep = (logits, parent_scores, parent_pool_idx, out, pool, desc, workspace, pp, held, io, h, c, uniform, policy_out, states)
+    if states is None:
+        pool.count += F * k
+    return _finish("radar_draft_expand_batch", load().radar_draft_expand_batch, args, keep, (out, policy_out), prepared)
 
 
 def radar_draft_rerank_cycle(pool, state, pool_count_max, N, root_token, out=None, workspace=None, prepared=False):

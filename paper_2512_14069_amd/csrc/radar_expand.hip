@@ -12,6 +12,10 @@
 // host round trip.  radar_draft_expand_policy lets the same workgroup go on to
 // the prediction model's step on the k confidences it has just produced
 // (Sec. 4.2), so the continue / stop decision costs no launch of its own.
+// radar_draft_expand_batch adds a grid dimension: one such call per sequence,
+// B sequences in one launch, each with its own arrays, tickets and last workgroup.
+#include <algorithm>
+
 #include "radar_topk.h"
 #include "radar_policy.h"
 #include "radar_host.h"
@@ -41,6 +45,7 @@ struct ExpandArgs {
     float *pool_scores;
     int32_t *pool_parents;
     int F, V, k, nchunks, pool_count;
+    int pool_capacity;          // length of one sequence's pool arrays (their stride in a batched call)
     unsigned int *counters;     // [0] rows finished, [(1+f) * kCounterStride] chunks of row f finished
     uint64_t *part_keys;        // [F][nchunks][RADAR_K_MAX] best first, 0 where a chunk has fewer
     double *part_l;             // [F][nchunks] sum of exp(x - part_m) over the chunk
@@ -152,12 +157,28 @@ __device__ __forceinline__ void select_frontier(const ExpandArgs &a, ExpandSmem 
 template <bool VEC4, int EPT, bool EXT>
 __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
     const bool has_policy = EXT && a.has_policy != 0;
-    radar_cycle_state *const cycle = EXT ? a.cycle : nullptr;
     static_assert(EPT == 4 || EPT == 8 || EPT == 16, "EPT");
     constexpr int kChunk = kExpThreads * EPT;
     __shared__ ExpandSmem s;
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int f = blockIdx.y, chunk = blockIdx.x;
+    const int bz = EXT ? (int)blockIdx.z : 0;
+    if (EXT && bz != 0) {
+        // Sequence bz of a batched call: every array of the call, the workspace parts and the cycle
+        // states have a leading batch dimension; from here on the workgroup sees its own sequence only.
+        const size_t b = (size_t)bz, fk = (size_t)a.F * a.k, fc = (size_t)a.F * a.nchunks;
+        a.logits += b * a.F * a.V;
+        a.parent_scores += b * a.F; a.parent_pool_idx += b * a.F;
+        a.cand_tokens += b * fk; a.cand_scores += b * fk;
+        a.frontier_pool_idx += b * a.k; a.frontier_tokens += b * a.k;
+        a.frontier_scores += b * a.k; a.frontier_conf += b * a.k;
+        a.pool_tokens += b * a.pool_capacity; a.pool_scores += b * a.pool_capacity; a.pool_parents += b * a.pool_capacity;
+        a.counters += b * (kCounterBytes / sizeof(unsigned int));
+        a.part_keys += b * fc * RADAR_K_MAX; a.part_l += b * fc; a.part_m += b * fc;
+        a.gate_pre += b * (4 * kPolH);
+        if (a.cycle) a.cycle += b;
+    }
+    radar_cycle_state *const cycle = EXT ? a.cycle : nullptr;
     // The first draft call of a cycle (the host says so: the largest count the state may hold is 0)
     // never reads the state; its last workgroup writes all of it.
     const bool cycle_first = cycle != nullptr && a.pool_count == 0;
@@ -192,7 +213,7 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
     // launch: its loads travel with the logits', its results are handed to the last workgroup
     // through the workspace like the chunk partials.
     if (has_policy && a.pol_has_state)
-        policy_hidden_rows<4>(a.pol, 0, blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y,
+        policy_hidden_rows<4>(a.pol, bz, blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y,
                               [&](int r, float v) { store_shared_result(&a.gate_pre[r], v); });
     float x[EPT];
 #pragma unroll
@@ -358,7 +379,7 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
     static_assert(sizeof(PolicySmem) <= (kExpWaves - 1) * sizeof(WaveTopkSmem) && sizeof(WaveTopkSmem) % 16 == 0, "policy LDS overlay");
     PolicySmem &ps = *reinterpret_cast<PolicySmem *>(&s.wtk[1]);
     policy_step_block<true>(
-        a.pol, 0, a.pol_has_state != 0, ps, [&](int row) { return load_shared_result(&a.gate_pre[row]); },
+        a.pol, bz, a.pol_has_state != 0, ps, [&](int row) { return load_shared_result(&a.gate_pre[row]); },
         [&] { select_frontier(a, s, ps.x); },
         [&](int action) {
             if (cycle) {
@@ -469,14 +490,23 @@ static int plan_expand_ept(int F, int V) {
     return 16;
 }
 
-extern "C" size_t radar_draft_expand_workspace_bytes(const radar_expand_desc *d) {
-    if (!d || d->F < 1 || d->V < 1) return 0;
-    const size_t nchunks = ((size_t)d->V + kExpThreads * kExpMinEPT - 1) / (kExpThreads * kExpMinEPT);   // most chunks any plan uses
-    size_t bytes = kCounterBytes;
-    bytes += (size_t)d->F * nchunks * RADAR_K_MAX * sizeof(uint64_t);
-    bytes += (size_t)d->F * nchunks * (sizeof(double) + sizeof(float));
-    bytes = ((bytes + 255) & ~size_t(255)) + 4 * kPolH * sizeof(float);      // w_hh h of the fused prediction model
-    return (bytes + 255) & ~size_t(255);
+// Workspace of a call over B sequences: [B] counter blocks, [B][F][chunks] chunk lists, sums and maxima
+// (sized for the most chunks any plan uses), [B] w_hh h of the fused prediction model.
+static size_t expand_gate_bytes(size_t B) { return (B * 4 * kPolH * sizeof(float) + 255) & ~size_t(255); }
+
+static size_t expand_workspace_bytes(const radar_expand_desc *d, size_t B) {
+    if (!d || d->F < 1 || d->V < 1 || B < 1) return 0;
+    const size_t nchunks = ((size_t)d->V + kExpThreads * kExpMinEPT - 1) / (kExpThreads * kExpMinEPT);
+    size_t bytes = B * kCounterBytes;
+    bytes += B * d->F * nchunks * RADAR_K_MAX * sizeof(uint64_t);
+    bytes += B * d->F * nchunks * (sizeof(double) + sizeof(float));
+    return ((bytes + 255) & ~size_t(255)) + expand_gate_bytes(B);
+}
+
+extern "C" size_t radar_draft_expand_workspace_bytes(const radar_expand_desc *d) { return expand_workspace_bytes(d, 1); }
+
+extern "C" size_t radar_draft_expand_batch_workspace_bytes(const radar_expand_desc *d, int32_t B) {
+    return B < 1 ? 0 : expand_workspace_bytes(d, (size_t)B);
 }
 
 namespace radar { radar_status policy_args_from(const radar_policy_params *pp, PolicyArgs *out); }
@@ -486,7 +516,7 @@ static radar_status launch_expand(const float *logits, const float *parent_score
                                   int32_t *frontier_pool_idx, int32_t *frontier_tokens,
                                   float *frontier_scores, float *frontier_conf, int32_t *pool_tokens,
                                   float *pool_scores, int32_t *pool_parents, const radar_expand_desc *d,
-                                  const PolicyArgs *pol, radar_cycle_state *cycle, void *workspace,
+                                  const PolicyArgs *pol, radar_cycle_state *cycle, int B, void *workspace,
                                   size_t workspace_bytes, void *stream) {
     if (!d || !logits || !parent_scores || !parent_pool_idx || !cand_tokens || !cand_scores || !frontier_pool_idx ||
         !frontier_tokens || !frontier_scores || !frontier_conf || !pool_tokens || !pool_scores || !pool_parents ||
@@ -495,11 +525,13 @@ static radar_status launch_expand(const float *logits, const float *parent_score
     if (d->F < 1 || d->V < 1 || d->k < 1 || d->k > d->V || d->pool_count < 0 ||
         (int64_t)d->pool_count + (int64_t)d->F * d->k > (int64_t)d->pool_capacity)
         return RADAR_INVALID_ARG;
-    const int ept = plan_expand_ept(d->F, d->V);
+    if (B < 1) return RADAR_INVALID_ARG;
+    if (B > 65535) return RADAR_UNSUPPORTED_SHAPE;
+    const int ept = plan_expand_ept((int)std::min<int64_t>((int64_t)d->F * B, 1 << 20), d->V);
     const int64_t chunk = (int64_t)kExpThreads * ept;
     const int64_t nchunks = ((int64_t)d->V + chunk - 1) / chunk;
     if (d->F > RADAR_F_MAX || d->k > RADAR_K_MAX || nchunks > kExpMaxChunks) return RADAR_UNSUPPORTED_SHAPE;
-    if (workspace_bytes < radar_draft_expand_workspace_bytes(d)) return RADAR_WORKSPACE_TOO_SMALL;
+    if (workspace_bytes < expand_workspace_bytes(d, (size_t)B)) return RADAR_WORKSPACE_TOO_SMALL;
     if (((uintptr_t)workspace & 255) != 0) return RADAR_INVALID_ARG;
 
     ExpandArgs a;
@@ -509,23 +541,25 @@ static radar_status launch_expand(const float *logits, const float *parent_score
     a.frontier_scores = frontier_scores; a.frontier_conf = frontier_conf;
     a.pool_tokens = pool_tokens; a.pool_scores = pool_scores; a.pool_parents = pool_parents;
     a.F = d->F; a.V = d->V; a.k = d->k; a.nchunks = (int)nchunks; a.pool_count = d->pool_count;
+    a.pool_capacity = d->pool_capacity;
     char *ws = static_cast<char *>(workspace);
+    const size_t nb = (size_t)B, cbytes = nb * kCounterBytes;
     a.counters = reinterpret_cast<unsigned int *>(ws);
-    a.part_keys = reinterpret_cast<uint64_t *>(ws + kCounterBytes);
-    const size_t nslots = (size_t)d->F * nchunks;
-    a.part_l = reinterpret_cast<double *>(ws + kCounterBytes + nslots * RADAR_K_MAX * sizeof(uint64_t));
-    a.part_m = reinterpret_cast<float *>(ws + kCounterBytes + nslots * (RADAR_K_MAX * sizeof(uint64_t) + sizeof(double)));
-    a.gate_pre = reinterpret_cast<float *>(ws + radar_draft_expand_workspace_bytes(d) - ((4 * kPolH * sizeof(float) + 255) & ~size_t(255)));
+    a.part_keys = reinterpret_cast<uint64_t *>(ws + cbytes);
+    const size_t nslots = nb * d->F * nchunks;
+    a.part_l = reinterpret_cast<double *>(ws + cbytes + nslots * RADAR_K_MAX * sizeof(uint64_t));
+    a.part_m = reinterpret_cast<float *>(ws + cbytes + nslots * (RADAR_K_MAX * sizeof(uint64_t) + sizeof(double)));
+    a.gate_pre = reinterpret_cast<float *>(ws + expand_workspace_bytes(d, nb) - expand_gate_bytes(nb));
     a.cycle = cycle;
     a.pol = pol ? *pol : PolicyArgs{};
     a.has_policy = pol ? 1 : 0;
     a.pol_has_state = (pol && pol->h_in) ? 1 : 0;
 
-    const dim3 grid((unsigned)nchunks, (unsigned)d->F), block(kExpThreads);
+    const dim3 grid((unsigned)nchunks, (unsigned)d->F, (unsigned)B), block(kExpThreads);
     const bool vec4 = (d->V % 4 == 0) && (((uintptr_t)logits & 15) == 0);
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
-    const bool ext = pol != nullptr || cycle != nullptr;
+    const bool ext = pol != nullptr || cycle != nullptr || B > 1;
 #define RADAR_EXPAND_LAUNCH(V4, E)                                                                   \
     (ext ? launch("expand", expand_kernel<V4, E, true>, grid, block, 0, st, a)                        \
          : launch("expand", expand_kernel<V4, E, false>, grid, block, 0, st, a))
@@ -544,7 +578,7 @@ extern "C" radar_status radar_draft_expand(const float *logits, const float *par
                                            void *workspace, size_t workspace_bytes, void *stream) {
     return launch_expand(logits, parent_scores, parent_pool_idx, cand_tokens, cand_scores, frontier_pool_idx,
                          frontier_tokens, frontier_scores, frontier_conf, pool_tokens, pool_scores, pool_parents, d,
-                         nullptr, nullptr, workspace, workspace_bytes, stream);
+                         nullptr, nullptr, 1, workspace, workspace_bytes, stream);
 }
 
 extern "C" radar_status radar_draft_expand_policy(const float *logits, const float *parent_scores,
@@ -565,7 +599,7 @@ extern "C" radar_status radar_draft_expand_policy(const float *logits, const flo
     pa.h_out = io->h_out; pa.c_out = io->c_out; pa.logits = io->logits; pa.probs = io->probs; pa.action = io->action;
     return launch_expand(logits, parent_scores, parent_pool_idx, cand_tokens, cand_scores, frontier_pool_idx,
                          frontier_tokens, frontier_scores, frontier_conf, pool_tokens, pool_scores, pool_parents, d,
-                         &pa, nullptr, workspace, workspace_bytes, stream);
+                         &pa, nullptr, 1, workspace, workspace_bytes, stream);
 }
 
 // fill kernel for the cycle state (a graph may not hold a memset node)
@@ -593,7 +627,7 @@ extern "C" radar_status radar_draft_expand_cycle(const float *logits, const floa
         if (io) return RADAR_INVALID_ARG;
         return launch_expand(logits, parent_scores, parent_pool_idx, cand_tokens, cand_scores, frontier_pool_idx,
                              frontier_tokens, frontier_scores, frontier_conf, pool_tokens, pool_scores, pool_parents, d,
-                             nullptr, state, workspace, workspace_bytes, stream);
+                             nullptr, state, 1, workspace, workspace_bytes, stream);
     }
     PolicyArgs pa;
     const radar_status st = policy_args_from(params, &pa);
@@ -605,7 +639,36 @@ extern "C" radar_status radar_draft_expand_cycle(const float *logits, const floa
     pa.h_out = io->h_out; pa.c_out = io->c_out; pa.logits = io->logits; pa.probs = io->probs; pa.action = io->action;
     return launch_expand(logits, parent_scores, parent_pool_idx, cand_tokens, cand_scores, frontier_pool_idx,
                          frontier_tokens, frontier_scores, frontier_conf, pool_tokens, pool_scores, pool_parents, d,
-                         &pa, state, workspace, workspace_bytes, stream);
+                         &pa, state, 1, workspace, workspace_bytes, stream);
+}
+
+extern "C" radar_status radar_draft_expand_batch(const float *logits, const float *parent_scores,
+                                                 const int32_t *parent_pool_idx, int32_t *cand_tokens,
+                                                 float *cand_scores, int32_t *frontier_pool_idx,
+                                                 int32_t *frontier_tokens, float *frontier_scores,
+                                                 float *frontier_conf, int32_t *pool_tokens, float *pool_scores,
+                                                 int32_t *pool_parents, const radar_expand_desc *d, int32_t B,
+                                                 const radar_policy_params *params, const radar_policy_io *io,
+                                                 radar_cycle_state *states, void *workspace, size_t workspace_bytes,
+                                                 void *stream) {
+    if (!d) return RADAR_INVALID_ARG;
+    if (!params) {
+        if (io) return RADAR_INVALID_ARG;
+        return launch_expand(logits, parent_scores, parent_pool_idx, cand_tokens, cand_scores, frontier_pool_idx,
+                             frontier_tokens, frontier_scores, frontier_conf, pool_tokens, pool_scores, pool_parents, d,
+                             nullptr, states, B, workspace, workspace_bytes, stream);
+    }
+    PolicyArgs pa;
+    const radar_status st = policy_args_from(params, &pa);
+    if (st != RADAR_OK) return st;
+    if (!io || !io->h_out || !io->c_out || !io->logits || !io->probs || !io->action) return RADAR_INVALID_ARG;
+    if ((io->h_in == nullptr) != (io->c_in == nullptr) || ((uintptr_t)io->h_in & 15) != 0) return RADAR_INVALID_ARG;
+    if (params->k != d->k) return RADAR_INVALID_ARG;
+    pa.h_in = io->h_in; pa.c_in = io->c_in; pa.uniforms = io->uniform;
+    pa.h_out = io->h_out; pa.c_out = io->c_out; pa.logits = io->logits; pa.probs = io->probs; pa.action = io->action;
+    return launch_expand(logits, parent_scores, parent_pool_idx, cand_tokens, cand_scores, frontier_pool_idx,
+                         frontier_tokens, frontier_scores, frontier_conf, pool_tokens, pool_scores, pool_parents, d,
+                         &pa, states, B, workspace, workspace_bytes, stream);
 }
 
 extern "C" size_t radar_draft_rerank_workspace_bytes(int32_t pool_count, int32_t N) {

@@ -1,6 +1,6 @@
 """Times the entry points that widen the hot path, at the 8B shape (V = 128256, k = 10, 61 tree rows):
-acceptance-length distribution, prediction-model step (alone and fused into the expansion), and
-verification with draft distributions.  One JSON line per entry point with the per-kernel device
+acceptance-length distribution, prediction-model step (alone and fused into the expansion), the
+expansion of 4, 16 and 64 sequences in one launch, and verification with draft distributions.  One JSON line per entry point with the per-kernel device
 durations the library records (radar_profile_begin / radar_profile_end) and the algorithmic bytes.
 
     python -m paper_2512_14069_amd.rows_bench [--reps 100]
@@ -84,6 +84,30 @@ def main():
         timed("radar_draft_expand F=%d" % F, [plain], F * V * 4, "for comparison")
         timed("radar_draft_expand_policy F=%d" % F, [fused], F * V * 4 + pbytes, "expansion and decision in one launch")
         timed("radar_draft_expand + radar_policy_step F=%d" % F, [plain, sep], F * V * 4 + pbytes, "two launches")
+
+    # one draft call for B sequences in one launch; inputs rotated through more memory than the caches hold
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.seed_for(3, 92))
+    for B in (4, 16, 64):
+        nsets = max(2, int(600e6 // (B * k * V * 4)) + 1)
+        sets = [torch.log_softmax(torch.randn((B, k, V), generator=gen, device=dev) * c3.logit_std, dim=-1).contiguous()
+                for _ in range(nsets)]
+        ps = torch.zeros((B, k), device=dev)
+        pi = torch.full((B, k), -1, dtype=torch.int32, device=dev)
+        pool = b.DraftPool(k * k, B=B)
+        bws = b.new_workspace(b.radar_draft_expand_batch_workspace_bytes(b.expand_desc(k, V, k, 0, k * k), B))
+        eo = b.ExpandOut(k, k, dev, B=B)
+        calls = []
+        for lg in sets:
+            pool.count = 0
+            calls.append(b.radar_draft_expand_batch(lg, ps, pi, k, pool, out=eo, workspace=bws, prepared=True))
+        # timed() runs the whole list per repetition: report per call
+        args.reps, keep = max(1, args.reps // nsets), args.reps
+        timed("radar_draft_expand_batch B=%d F=%d (%d calls)" % (B, k, nsets), calls, nsets * B * k * V * 4,
+              "%d sequences per launch; time and bytes are for %d calls on different inputs" % (B, nsets))
+        args.reps = keep
+        del sets, calls
+        torch.cuda.empty_cache()
 
     qd = b.accept_q_desc(1, T, T, V, T - 1)
     qws = b.new_workspace(b.radar_verify_accept_q_workspace_bytes(qd))

@@ -1,0 +1,138 @@
+"""GPU parity: radar_draft_expand_batch (one draft call for B sequences in one launch, through the
+C ABI) against the CPU oracle run sequence by sequence on the same seeded inputs: plain calls, and
+whole cycles in which every sequence stops at its own draft call (Sec. 4.1-4.2).  Token ids,
+frontier choices, pool contents, stop steps and trees must be equal; scores within 1e-5."""
+import types
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_14069_amd import synth
+from gpu_util import dev, host
+from test_gpu_cycle import K, N, T_MAX, CAP, POLICY_TOL, make_inputs, oracle_cycle
+
+pytestmark = pytest.mark.gpu
+
+SCORE_TOL = 1e-5
+GAP = 1e-4
+
+
+@pytest.mark.parametrize("B,F,V,k,pre", [
+    (5, 10, 32000, 10, 37),        # several sequences, pools already holding candidates
+    (16, 10, 128256, 10, 0),       # the 8B shape for a batch of 16: 16 logits per lane, several rounds of workgroups
+    (3, 1, 128256, 10, 0),         # first draft call of the paper's schedule (the root alone)
+    (7, 3, 4097, 5, 11),           # ragged tail, unaligned rows (scalar loads)
+    (2, 64, 8192, 2, 0),           # most rows
+    (1, 4, 4096, 4, 0),            # B = 1 through the batched entry point
+])
+def test_batched_call_matches_oracle_per_sequence(oracle, B, F, V, k, pre):
+    from paper_2512_14069_amd import binding as b
+    rng = np.random.default_rng(synth.seed_for(9, B * 1000 + F + k))
+    cap = pre + F * k
+    logits = np.stack([synth.expand_logits(rng, F, V, 2.5) for _ in range(B)])
+    ps = (-rng.random((B, F))).astype(np.float32)
+    ppi = (rng.integers(0, pre, (B, F)).astype(np.int32) if pre else np.full((B, F), -1, np.int32))
+    gp = b.DraftPool(cap, B=B)
+    gp.tokens.fill_(-5); gp.parents.fill_(-5)            # what the call must not touch stays recognisable
+    gp.count = pre
+    g, pol = b.radar_draft_expand_batch(dev(logits), dev(ps), dev(ppi), k, gp)
+    torch.cuda.synchronize()
+    assert pol is None and gp.count == cap
+    assert np.all(host(gp.tokens)[:, :pre] == -5)
+    for s in range(B):
+        cp = dict(tokens=np.zeros(cap, np.int32), scores=np.zeros(cap, np.float32), parents=np.zeros(cap, np.int32))
+        r = oracle.draft_expand(logits[s], ps[s], ppi[s], k, cp, pre)
+        assert np.array_equal(host(g.cand_tokens)[s].reshape(F, k), r["cand_tokens"]), s
+        assert np.max(np.abs(host(g.cand_scores)[s].reshape(F, k).astype(np.float64) - r["cand_scores"])) <= SCORE_TOL
+        flat = np.sort(r["cand_scores"].reshape(-1))[::-1][:k + 1].astype(np.float64)
+        if len(flat) < 2 or np.min(-np.diff(flat)) > GAP:
+            assert np.array_equal(host(g.frontier_pool_idx)[s], r["frontier_pool_idx"]), s
+            assert np.array_equal(host(g.frontier_tokens)[s], r["frontier_tokens"]), s
+            assert np.max(np.abs(host(g.frontier_scores)[s].astype(np.float64) - r["frontier_scores"])) <= SCORE_TOL
+            assert np.allclose(host(g.frontier_conf)[s], r["frontier_conf"], rtol=2e-5, atol=0)
+        assert np.array_equal(host(gp.tokens)[s, pre:cap], cp["tokens"][pre:cap]), s
+        assert np.array_equal(host(gp.parents)[s, pre:cap], cp["parents"][pre:cap]), s
+        assert np.max(np.abs(host(gp.scores)[s, pre:cap].astype(np.float64) - cp["scores"][pre:cap])) <= SCORE_TOL
+
+
+@pytest.mark.parametrize("V,stops", [(32000, (1, 3, 8, 5, 2, 8)), (128256, (4, 8, 1))])
+def test_batched_cycles_stop_sequence_by_sequence(oracle, V, stops):
+    """t_max batched draft calls with the prediction model and per-sequence cycle states: every sequence
+    stops where its own oracle chain stops, the others go on; a stopped sequence's arrays stay as its
+    last executed call left them.  Run twice on the same buffers without resetting the states."""
+    from paper_2512_14069_amd import binding as b
+    B = len(stops)
+    rng = np.random.default_rng(synth.seed_for(43, V % 1000 + B))
+    p = synth.policy_params(rng, K, 128, 128, 2.0)
+    pp = b.policy_params({n: dev(v) for n, v in p.items()})
+    pool = b.DraftPool(CAP, B=B)
+    states = torch.full((B, 4), 77, dtype=torch.int32, device="cuda")          # never initialised
+    pout = b.PolicyOut(B, 128, "cuda")
+    eouts = [b.ExpandOut(1 if s == 0 else K, K, "cuda", B=B) for s in range(T_MAX)]
+    ws = b.new_workspace(b.radar_draft_expand_batch_workspace_bytes(b.expand_desc(K, V, K, 0, CAP), B))
+    ps0 = torch.zeros((B, 1), dtype=torch.float32, device="cuda")
+    pi0 = torch.full((B, 1), -1, dtype=torch.int32, device="cuda")
+    for rep in range(2):
+        order = stops if rep == 0 else stops[::-1]
+        xs = [make_inputs(rng, V, st) for st in order]
+        refs = [oracle_cycle(oracle, x, p, V) for x in xs]
+        assert [r["steps"] for r in refs] == list(order)
+        logits = [dev(np.stack([x["logits"][s] for x in xs])) for s in range(T_MAX)]
+        uni = dev(np.stack([x["uni"] for x in xs]))                              # [B, T_MAX]
+        ps, pi, count_max = ps0, pi0, 0
+        for s in range(T_MAX):
+            decide = s + 1 < T_MAX
+            b.radar_draft_expand_batch(
+                logits[s], ps, pi, K, pool, states=states, pool_count_max=count_max, params=pp if decide else None,
+                h=pout.h if decide and s > 0 else None, c=pout.c if decide and s > 0 else None,
+                uniform=uni[:, s].contiguous() if decide else None, out=eouts[s], policy_out=pout if decide else None,
+                workspace=ws)
+            count_max += (1 if s == 0 else K) * K
+            ps, pi = eouts[s].frontier_scores, eouts[s].frontier_pool_idx
+        torch.cuda.synchronize()
+        st = host(states)
+        for q, ref in enumerate(refs):
+            assert st[q].tolist()[:3] == [1 if ref["steps"] < T_MAX else 0, ref["count"], ref["steps"]], (q, st[q])
+            for s in range(ref["steps"]):
+                e, r = eouts[s], ref["fronts"][s]
+                assert np.array_equal(host(e.frontier_tokens)[q], r["frontier_tokens"]), (q, s)
+                assert np.array_equal(host(e.frontier_pool_idx)[q], r["frontier_pool_idx"]), (q, s)
+                assert np.max(np.abs(host(e.frontier_scores)[q] - r["frontier_scores"])) <= 1e-5
+            n = ref["count"]
+            assert np.array_equal(host(pool.tokens)[q, :n], ref["pool"]["tokens"][:n])
+            assert np.array_equal(host(pool.parents)[q, :n], ref["pool"]["parents"][:n])
+            assert np.max(np.abs(host(pool.scores)[q, :n] - ref["pool"]["scores"][:n])) <= 1e-5
+            if ref["policy"]:
+                last = ref["policy"][-1]
+                for name in ("h", "c", "logits", "probs"):
+                    assert np.max(np.abs(host(getattr(pout, name))[q] - last[name][0])) <= POLICY_TOL, (q, name)
+                assert host(pout.action)[q] == last["action"][0]
+            # the tree of sequence q: the device's rerank of its own pool against the oracle's
+            view = types.SimpleNamespace(tokens=pool.tokens[q], scores=pool.scores[q], parents=pool.parents[q], capacity=CAP)
+            t = b.radar_draft_rerank_cycle(view, states[q], CAP, N, 1234)
+            torch.cuda.synchronize()
+            gpool = dict(tokens=host(pool.tokens)[q].copy(), scores=host(pool.scores)[q].copy(), parents=host(pool.parents)[q].copy())
+            tree = oracle.draft_rerank(gpool, n, N, 1234)
+            assert int(host(t.n_nodes)[0]) == tree["n_nodes"] == 1 + min(N, n)
+            for name in ("tokens", "parents", "depth", "pool_idx", "scores"):
+                assert np.array_equal(host(getattr(t, name)), tree[name]), (q, name)
+
+
+def test_batched_call_argument_errors(oracle):
+    from paper_2512_14069_amd import binding as b
+    B, F, V, k = 3, 2, 4096, 4
+    rng = np.random.default_rng(5)
+    logits = dev(np.stack([synth.expand_logits(rng, F, V, 2.0) for _ in range(B)]))
+    ps, ppi = dev(np.zeros((B, F), np.float32)), dev(np.full((B, F), -1, np.int32))
+    desc = b.expand_desc(F, V, k, 0, F * k)
+    assert b.radar_draft_expand_batch_workspace_bytes(desc, 1) == b.radar_draft_expand_workspace_bytes(desc)
+    assert b.radar_draft_expand_batch_workspace_bytes(desc, 0) == 0
+    assert b.radar_draft_expand_batch_workspace_bytes(desc, B) > 2 * b.radar_draft_expand_workspace_bytes(desc)
+    with pytest.raises(b.RadarError):                      # a single sequence's workspace does not do for three
+        b.radar_draft_expand_batch(logits, ps, ppi, k, b.DraftPool(F * k, B=B),
+                                   workspace=b.new_workspace(b.radar_draft_expand_workspace_bytes(desc)))
+    with pytest.raises(ValueError):                        # the pool must carry the batch dimension
+        b.radar_draft_expand_batch(logits, ps, ppi, k, b.DraftPool(F * k))
+    with pytest.raises(b.RadarError):                      # the pools would overflow
+        b.radar_draft_expand_batch(logits, ps, ppi, k, b.DraftPool(F * k - 1, B=B))
