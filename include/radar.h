@@ -146,6 +146,13 @@ typedef struct radar_expand_desc {
     int32_t pool_capacity;   /* length of the three pool arrays */
 } radar_expand_desc;
 
+/* One workspace serves every draft call of a cycle: the expansion family
+ * (radar_draft_expand, _policy, _cycle, _batch) keeps its arrival counters at
+ * fixed places at the head of the workspace and leaves them zero, and rewrites
+ * everything else before reading it, so calls with different descriptors (F = 1
+ * for the root, then F = k; a growing pool_count) and different members of the
+ * family may follow each other on one stream without radar_workspace_init in
+ * between, provided the workspace has the size the largest of them asks for. */
 size_t radar_draft_expand_workspace_bytes(const radar_expand_desc *desc);
 
 /* logits f32 [F,V]; parent_scores f32 [F]; parent_pool_idx i32 [F] (-1 = root);

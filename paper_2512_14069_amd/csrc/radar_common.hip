@@ -68,7 +68,7 @@ extern "C" const char *radar_status_string(radar_status status) {
     }
 }
 
-extern "C" int radar_version(void) { return 200; }   // 0.2.0: prediction model, cycle state, draft-distribution verification
+extern "C" int radar_version(void) { return 300; }   // 0.3.0: draft calls for a batch of sequences; 0.2.0: prediction model, cycle state, draft-distribution verification
 
 extern "C" radar_status radar_profile_begin(int32_t max_launches) {
     if (max_launches < 1 || max_launches > (1 << 20)) return RADAR_INVALID_ARG;
