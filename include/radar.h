@@ -152,7 +152,9 @@ typedef struct radar_expand_desc {
  * everything else before reading it, so calls with different descriptors (F = 1
  * for the root, then F = k; a growing pool_count) and different members of the
  * family may follow each other on one stream without radar_workspace_init in
- * between, provided the workspace has the size the largest of them asks for. */
+ * between, provided the workspace has the size the largest of them asks for
+ * and, for radar_draft_expand_batch, B stays the same (sequence b's counters
+ * sit where another B keeps other data). */
 size_t radar_draft_expand_workspace_bytes(const radar_expand_desc *desc);
 
 /* logits f32 [F,V]; parent_scores f32 [F]; parent_pool_idx i32 [F] (-1 = root);
