@@ -30,6 +30,7 @@ constexpr int kCounterStride = 32;                    // arrival counters sit 12
                                                       // cache line serialise at roughly 10 ns each
 constexpr size_t kCounterBytes = 16384;               // leading counter block of the workspace
 constexpr float kLog2eF = 1.4426950408889634f;
+constexpr int64_t kStreamMinLogits = 4 << 20;         // batched calls of at least 16 MB of logits take the streaming path
 
 struct ExpandArgs {
     const float *logits;
@@ -152,6 +153,124 @@ __device__ __forceinline__ void select_frontier(const ExpandArgs &a, ExpandSmem 
     }
 }
 
+// Sequence bz of a batched call: every array of the call, the workspace parts and the cycle states
+// have a leading batch dimension; after this the workgroup sees its own sequence only.
+__device__ __forceinline__ void sequence_view(ExpandArgs &a, int bz) {
+    const size_t b = (size_t)bz, fk = (size_t)a.F * a.k, fc = (size_t)a.F * a.nchunks;
+    a.logits += b * a.F * a.V;
+    a.parent_scores += b * a.F; a.parent_pool_idx += b * a.F;
+    a.cand_tokens += b * fk; a.cand_scores += b * fk;
+    a.frontier_pool_idx += b * a.k; a.frontier_tokens += b * a.k;
+    a.frontier_scores += b * a.k; a.frontier_conf += b * a.k;
+    a.pool_tokens += b * a.pool_capacity; a.pool_scores += b * a.pool_capacity; a.pool_parents += b * a.pool_capacity;
+    a.counters += b * (kCounterBytes / sizeof(unsigned int));
+    a.part_keys += b * fc * RADAR_K_MAX; a.part_l += b * fc; a.part_m += b * fc;
+    a.gate_pre += b * (4 * kPolH);
+    if (a.cycle) a.cycle += b;
+}
+
+// What the last workgroup of a sequence's call does once every chunk list and partial sum of the
+// sequence is in the workspace (all 1024 lanes must call): rows are merged, candidates scored and
+// pooled, the next frontier chosen; with a prediction model its step follows, with a cycle state
+// its update.  `a` is already the sequence's own view of the call (bz = its index in the batch).
+template <bool EXT>
+__device__ __forceinline__ void expand_finish(const ExpandArgs &a, ExpandSmem &s, int bz, radar_cycle_state *cycle,
+                                              bool cycle_first) {
+    const bool has_policy = EXT && a.has_policy != 0;
+    const int lane = lane_id(), w = wave_id();
+    const int K = a.k;
+    // One wavefront per row (rows w, w+16, ...):
+    // top-k of the row's chunk lists, log-sum-exp of the row, cumulative scores, pool append.
+    const int nslot = a.nchunks * RADAR_K_MAX;
+    for (int fr = w; fr < a.F; fr += kExpWaves) {
+        const uint64_t *pk = a.part_keys + (size_t)fr * nslot;
+        const bool few = nslot <= 4 * kWave;                       // up to 16 chunks per row (V <= 131072 at 8 per lane)
+        uint64_t kk[9];
+        if (few) {                                                 // four slots per lane: half the loads, a shorter selection
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int i = topk_slot_of(e);
+                const uint64_t key = load_shared_result(pk + min(i, nslot - 1));
+                kk[e] = (i < nslot && (i & 15) < K) ? key : 0;
+            }
+        } else {
+            load_key_block(pk, nslot, 0, K, kk);
+        }
+        float ml;
+        double ll;
+        {                                                          // chunk partials, one chunk per lane first
+            const int c = min(lane, a.nchunks - 1);
+            ml = load_shared_result(&a.part_m[(size_t)fr * a.nchunks + c]);
+            ll = load_shared_result(&a.part_l[(size_t)fr * a.nchunks + c]);
+            if (lane >= a.nchunks) { ml = -INFINITY; ll = 0.0; }
+        }
+        const float pscore = a.parent_scores[fr];
+        const int ppool = a.parent_pool_idx[fr];
+        uint64_t top;
+        if (few) {
+            const uint64_t k4[4] = {kk[0], kk[1], kk[2], kk[3]};
+            top = wave_topk<4>(k4, K, s.wtk[w]);
+        } else {
+            top = row_topk(kk, pk, nslot, K, s.wtk[w]);
+        }
+        for (int c = lane + kWave; c < a.nchunks; c += kWave) {        // V > 262144 only
+            const float m2 = load_shared_result(&a.part_m[(size_t)fr * a.nchunks + c]);
+            const double l2 = load_shared_result(&a.part_l[(size_t)fr * a.nchunks + c]);
+            const float mn = fmaxf(ml, m2);
+            if (mn > -INFINITY)
+                ll = ll * (double)__builtin_amdgcn_exp2f((ml - mn) * kLog2eF) + l2 * (double)__builtin_amdgcn_exp2f((m2 - mn) * kLog2eF);
+            ml = mn;
+        }
+        const float M = wave_max_f32(ml);
+        const double L = wave_sum_f64(ml > -INFINITY ? ll * (double)__builtin_amdgcn_exp2f((ml - M) * kLog2eF) : 0.0);
+        // log in fp32 (1 ulp of a value below 14: 1e-6, a tenth of the tolerance on log-probabilities); the
+        // fp64 routine costs 0.3 us on this serial path
+        const double lse = (double)M + (double)logf((float)L);
+        if (lane < K) {
+            const int tok = (int)key_index(top);
+            const double logp = (double)key_value(top) - lse;
+            const float cum = (float)((double)pscore + logp);
+            const int c = fr * K + lane;
+            a.cand_tokens[c] = tok;
+            a.cand_scores[c] = cum;
+            a.pool_tokens[a.pool_count + c] = tok;
+            a.pool_scores[a.pool_count + c] = cum;
+            a.pool_parents[a.pool_count + c] = ppool;
+            s.cand_sc[fr * 16 + lane] = cum;
+            s.cand_tok[fr * 16 + lane] = tok;
+        }
+    }
+    __syncthreads();
+    if (!has_policy) {
+        if (w == 0) {
+            select_frontier(a, s, nullptr);
+            if (cycle && lane == 0) {
+                cycle->pool_count = a.pool_count + a.F * a.k;
+                cycle->steps_done = cycle_first ? 1 : cycle->steps_done + 1;
+                if (cycle_first) { cycle->stopped = 0; cycle->last_action = -1; }
+            }
+        }
+        return;
+    }
+    // ---- prediction-model step on the new frontier's confidences.  Its LDS reuses the
+    // selection scratch of wavefronts 1.., idle since the barrier above; the other wavefronts
+    // fetch the model's operands while wavefront 0 still selects the frontier.
+    static_assert(sizeof(PolicySmem) <= (kExpWaves - 1) * sizeof(WaveTopkSmem) && sizeof(WaveTopkSmem) % 16 == 0, "policy LDS overlay");
+    PolicySmem &ps = *reinterpret_cast<PolicySmem *>(&s.wtk[1]);
+    policy_step_block<true>(
+        a.pol, bz, a.pol_has_state != 0, ps, [&](int row) { return load_shared_result(&a.gate_pre[row]); },
+        [&] { select_frontier(a, s, ps.x); },
+        [&](int action) {
+            if (cycle) {
+                cycle->pool_count = a.pool_count + a.F * a.k;
+                cycle->steps_done = cycle_first ? 1 : cycle->steps_done + 1;
+                cycle->last_action = action;
+                if (action == 0) cycle->stopped = 1;
+                else if (cycle_first) cycle->stopped = 0;
+            }
+        });
+}
+
 // EXT: the launch may carry a prediction model and / or a device-side cycle state; the plain
 // expansion is compiled without any of that code.
 template <bool VEC4, int EPT, bool EXT>
@@ -163,21 +282,7 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int f = blockIdx.y, chunk = blockIdx.x;
     const int bz = EXT ? (int)blockIdx.z : 0;
-    if (EXT && bz != 0) {
-        // Sequence bz of a batched call: every array of the call, the workspace parts and the cycle
-        // states have a leading batch dimension; from here on the workgroup sees its own sequence only.
-        const size_t b = (size_t)bz, fk = (size_t)a.F * a.k, fc = (size_t)a.F * a.nchunks;
-        a.logits += b * a.F * a.V;
-        a.parent_scores += b * a.F; a.parent_pool_idx += b * a.F;
-        a.cand_tokens += b * fk; a.cand_scores += b * fk;
-        a.frontier_pool_idx += b * a.k; a.frontier_tokens += b * a.k;
-        a.frontier_scores += b * a.k; a.frontier_conf += b * a.k;
-        a.pool_tokens += b * a.pool_capacity; a.pool_scores += b * a.pool_capacity; a.pool_parents += b * a.pool_capacity;
-        a.counters += b * (kCounterBytes / sizeof(unsigned int));
-        a.part_keys += b * fc * RADAR_K_MAX; a.part_l += b * fc; a.part_m += b * fc;
-        a.gate_pre += b * (4 * kPolH);
-        if (a.cycle) a.cycle += b;
-    }
+    if (EXT && bz != 0) sequence_view(a, bz);
     radar_cycle_state *const cycle = EXT ? a.cycle : nullptr;
     // The first draft call of a cycle (the host says so: the largest count the state may hold is 0)
     // never reads the state; its last workgroup writes all of it.
@@ -300,96 +405,8 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
     if (s.ticket2 != (unsigned int)(a.F - 1)) return;
     if (tid == 0) store_shared_result(&a.counters[0], 0u);
 
-    // ================= last workgroup of the call.  One wavefront per row (rows w, w+16, ...):
-    // top-k of the row's chunk lists, log-sum-exp of the row, cumulative scores, pool append.
-    const int nslot = a.nchunks * RADAR_K_MAX;
-    for (int fr = w; fr < a.F; fr += kExpWaves) {
-        const uint64_t *pk = a.part_keys + (size_t)fr * nslot;
-        const bool few = nslot <= 4 * kWave;                       // up to 16 chunks per row (V <= 131072 at 8 per lane)
-        uint64_t kk[9];
-        if (few) {                                                 // four slots per lane: half the loads, a shorter selection
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int i = topk_slot_of(e);
-                const uint64_t key = load_shared_result(pk + min(i, nslot - 1));
-                kk[e] = (i < nslot && (i & 15) < K) ? key : 0;
-            }
-        } else {
-            load_key_block(pk, nslot, 0, K, kk);
-        }
-        float ml;
-        double ll;
-        {                                                          // chunk partials, one chunk per lane first
-            const int c = min(lane, a.nchunks - 1);
-            ml = load_shared_result(&a.part_m[(size_t)fr * a.nchunks + c]);
-            ll = load_shared_result(&a.part_l[(size_t)fr * a.nchunks + c]);
-            if (lane >= a.nchunks) { ml = -INFINITY; ll = 0.0; }
-        }
-        const float pscore = a.parent_scores[fr];
-        const int ppool = a.parent_pool_idx[fr];
-        uint64_t top;
-        if (few) {
-            const uint64_t k4[4] = {kk[0], kk[1], kk[2], kk[3]};
-            top = wave_topk<4>(k4, K, s.wtk[w]);
-        } else {
-            top = row_topk(kk, pk, nslot, K, s.wtk[w]);
-        }
-        for (int c = lane + kWave; c < a.nchunks; c += kWave) {        // V > 262144 only
-            const float m2 = load_shared_result(&a.part_m[(size_t)fr * a.nchunks + c]);
-            const double l2 = load_shared_result(&a.part_l[(size_t)fr * a.nchunks + c]);
-            const float mn = fmaxf(ml, m2);
-            if (mn > -INFINITY)
-                ll = ll * (double)__builtin_amdgcn_exp2f((ml - mn) * kLog2eF) + l2 * (double)__builtin_amdgcn_exp2f((m2 - mn) * kLog2eF);
-            ml = mn;
-        }
-        const float M = wave_max_f32(ml);
-        const double L = wave_sum_f64(ml > -INFINITY ? ll * (double)__builtin_amdgcn_exp2f((ml - M) * kLog2eF) : 0.0);
-        // log in fp32 (1 ulp of a value below 14: 1e-6, a tenth of the tolerance on log-probabilities); the
-        // fp64 routine costs 0.3 us on this serial path
-        const double lse = (double)M + (double)logf((float)L);
-        if (lane < K) {
-            const int tok = (int)key_index(top);
-            const double logp = (double)key_value(top) - lse;
-            const float cum = (float)((double)pscore + logp);
-            const int c = fr * K + lane;
-            a.cand_tokens[c] = tok;
-            a.cand_scores[c] = cum;
-            a.pool_tokens[a.pool_count + c] = tok;
-            a.pool_scores[a.pool_count + c] = cum;
-            a.pool_parents[a.pool_count + c] = ppool;
-            s.cand_sc[fr * 16 + lane] = cum;
-            s.cand_tok[fr * 16 + lane] = tok;
-        }
-    }
-    __syncthreads();
-    if (!has_policy) {
-        if (w == 0) {
-            select_frontier(a, s, nullptr);
-            if (cycle && lane == 0) {
-                cycle->pool_count = a.pool_count + a.F * a.k;
-                cycle->steps_done = cycle_first ? 1 : cycle->steps_done + 1;
-                if (cycle_first) { cycle->stopped = 0; cycle->last_action = -1; }
-            }
-        }
-        return;
-    }
-    // ---- prediction-model step on the new frontier's confidences.  Its LDS reuses the
-    // selection scratch of wavefronts 1.., idle since the barrier above; the other wavefronts
-    // fetch the model's operands while wavefront 0 still selects the frontier.
-    static_assert(sizeof(PolicySmem) <= (kExpWaves - 1) * sizeof(WaveTopkSmem) && sizeof(WaveTopkSmem) % 16 == 0, "policy LDS overlay");
-    PolicySmem &ps = *reinterpret_cast<PolicySmem *>(&s.wtk[1]);
-    policy_step_block<true>(
-        a.pol, bz, a.pol_has_state != 0, ps, [&](int row) { return load_shared_result(&a.gate_pre[row]); },
-        [&] { select_frontier(a, s, ps.x); },
-        [&](int action) {
-            if (cycle) {
-                cycle->pool_count = a.pool_count + a.F * a.k;
-                cycle->steps_done = cycle_first ? 1 : cycle->steps_done + 1;
-                cycle->last_action = action;
-                if (action == 0) cycle->stopped = 1;
-                else if (cycle_first) cycle->stopped = 0;
-            }
-        });
+    // ================= last workgroup of the call
+    expand_finish<EXT>(a, s, bz, cycle, cycle_first);
 }
 
 // ------------------------------------------------------------------ rerank
@@ -476,6 +493,131 @@ __global__ __launch_bounds__(kTopkThreads) void rerank_kernel(RerankArgs a) {
     if (tid == 0) *a.n_nodes_out = 1 + keep;
 }
 
+// ------------------------------------------------------------------ large batches: stream, then finish
+// For many sequences per call the single launch above is bound by what every workgroup does around
+// its share of the stream (one workgroup per CU, hand-over and ticket per chunk).  Two launches
+// instead: a streaming kernel of small workgroups (several per CU, out of step with each other)
+// without tickets or hand-over -- a wavefront owns 1024 consecutive logits, the four of a workgroup
+// meet once to leave one top-k list, maximum and sum of exponentials per 4096 logits in the
+// workspace -- then one workgroup per sequence that does what the last workgroup of the single
+// launch does.
+constexpr int kStreamThreads = 256;
+constexpr int kStreamWaves = kStreamThreads / kWave;
+constexpr int kStreamWaveLogits = 1024;
+constexpr int kStreamChunk = kStreamWaves * kStreamWaveLogits;
+
+// true: the sequence's cycle has stopped (or its state is out of range) and the call leaves it alone
+__device__ __forceinline__ bool cycle_skips(const radar_cycle_state *st, int pool_count_max, int *pool_count) {
+    if (st == nullptr || pool_count_max == 0) return false;        // no cycle, or its first call
+    const int pc = st->pool_count;
+    if (st->stopped != 0 || pc < 0 || pc > pool_count_max) return true;
+    *pool_count = pc;
+    return false;
+}
+
+template <bool VEC4>
+__global__ __launch_bounds__(kStreamThreads) void expand_stream_kernel(ExpandArgs a) {
+    __shared__ WaveTopkSmem wtk[kStreamWaves];
+    __shared__ uint64_t wlists[kStreamWaves][2 * kWaveListSlots];
+    __shared__ float wave_m[kStreamWaves];
+    __shared__ double wave_l[kStreamWaves];
+    const int lane = lane_id(), w = wave_id();
+    const int row = blockIdx.y;                                    // sequence * F + frontier row
+    int unused;
+    if (cycle_skips(a.cycle ? a.cycle + row / a.F : nullptr, a.pool_count, &unused)) return;   // the whole workgroup
+    // which 1024 logits of the row; a wavefront past the end of the row sees -inf only and leaves an empty list
+    const int base = blockIdx.x * kStreamChunk + w * kStreamWaveLogits;
+    const float *rowp = a.logits + (size_t)row * a.V;
+    const int K = a.k;
+
+    float4 raw[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int idx0 = base + g * (kWave * 4) + lane * 4;
+        if (VEC4) {
+            raw[g] = *reinterpret_cast<const float4 *>(rowp + (idx0 < a.V ? idx0 : 0));
+        } else {
+            raw[g].x = rowp[min(idx0 + 0, a.V - 1)];
+            raw[g].y = rowp[min(idx0 + 1, a.V - 1)];
+            raw[g].z = rowp[min(idx0 + 2, a.V - 1)];
+            raw[g].w = rowp[min(idx0 + 3, a.V - 1)];
+        }
+    }
+    float x[2][8];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int idx0 = base + g * (kWave * 4) + lane * 4;
+        const float v[4] = {raw[g].x, raw[g].y, raw[g].z, raw[g].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) x[g >> 1][4 * (g & 1) + j] = (idx0 + j < a.V) ? v[j] : -INFINITY;
+    }
+    float hm[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        hm[h] = x[h][0];
+#pragma unroll
+        for (int e = 1; e < 8; ++e) hm[h] = fmaxf(hm[h], x[h][e]);
+    }
+    const float wm = wave_max_f32(fmaxf(hm[0], hm[1]));
+    float tl = 0.f;
+    if (wm > -INFINITY) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) tl += __builtin_amdgcn_exp2f((x[h][e] - wm) * kLog2eF);
+    }
+    const double wl = wave_sum_f64((double)tl);
+
+    // candidates of each half (512 logits, eight per lane), then the top-k of the two lists
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        uint64_t *list = &wlists[w][h * kWaveListSlots];
+        const int hbase = base + h * (kStreamWaveLogits / 2);
+        if (!wave_candidates<8>(x[h], hm[h], uint32_t(hbase + lane * 4), uint32_t(kWave * 4), uint32_t(a.V), K, wtk[w], list)) {
+            uint64_t keys[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int idx = hbase + (e >> 2) * (kWave * 4) + lane * 4 + (e & 3);
+                keys[e] = idx < a.V ? make_key(x[h][e], uint32_t(idx)) : 0;
+            }
+            const uint64_t wt = wave_topk<8>(keys, K, wtk[w]);
+            if (lane < kWaveListSlots) list[lane] = wt;            // lanes 16.. hold 0
+        }
+    }
+    if (lane == 0) { wave_m[w] = wm; wave_l[w] = wl; }
+    __syncthreads();
+    const size_t slot = (size_t)row * a.nchunks + blockIdx.x;
+    if (w == 0) {                                                              // the chunk's list: top-k of the eight lists
+        constexpr int NS = kStreamWaves * 2 * kWaveListSlots / kWave;
+        uint64_t kk[NS];
+#pragma unroll
+        for (int e = 0; e < NS; ++e) kk[e] = (&wlists[0][0])[topk_slot_of(e)];   // rotated: the used slots lead each list
+        const uint64_t ctop = wave_topk<NS>(kk, K, wtk[0]);
+        if (lane < RADAR_K_MAX) a.part_keys[slot * RADAR_K_MAX + lane] = ctop;    // 0 beyond the k-th
+    } else if (w == 1 && lane == 0) {                                          // fixed order of addition
+        float m = wave_m[0];
+#pragma unroll
+        for (int i = 1; i < kStreamWaves; ++i) m = fmaxf(m, wave_m[i]);
+        double l = 0.0;
+#pragma unroll
+        for (int i = 0; i < kStreamWaves; ++i)
+            if (wave_m[i] > -INFINITY) l += wave_l[i] * (double)__builtin_amdgcn_exp2f((wave_m[i] - m) * kLog2eF);
+        a.part_m[slot] = m;
+        a.part_l[slot] = l;
+    }
+}
+
+// one workgroup per sequence, after expand_stream_kernel
+__global__ __launch_bounds__(kExpThreads, 1) void expand_finish_kernel(ExpandArgs a) {
+    __shared__ ExpandSmem s;
+    const int bz = blockIdx.x;
+    if (bz != 0) sequence_view(a, bz);
+    radar_cycle_state *const cycle = a.cycle;
+    const bool cycle_first = cycle != nullptr && a.pool_count == 0;
+    if (cycle_skips(cycle, a.pool_count, &a.pool_count)) return;
+    expand_finish<true>(a, s, bz, cycle, cycle_first);
+}
+
 }  // namespace radar
 
 using namespace radar;
@@ -496,7 +638,9 @@ static size_t expand_gate_bytes(size_t B) { return (B * 4 * kPolH * sizeof(float
 
 static size_t expand_workspace_bytes(const radar_expand_desc *d, size_t B) {
     if (!d || d->F < 1 || d->V < 1 || B < 1) return 0;
-    const size_t nchunks = ((size_t)d->V + kExpThreads * kExpMinEPT - 1) / (kExpThreads * kExpMinEPT);
+    static_assert(kStreamChunk == kExpThreads * kExpMinEPT, "both paths' smallest chunk");
+    const size_t per_chunk = (size_t)kExpThreads * kExpMinEPT;                // most chunks any plan uses
+    const size_t nchunks = ((size_t)d->V + per_chunk - 1) / per_chunk;
     size_t bytes = B * kCounterBytes;
     bytes += B * d->F * nchunks * RADAR_K_MAX * sizeof(uint64_t);
     bytes += B * d->F * nchunks * (sizeof(double) + sizeof(float));
@@ -517,7 +661,7 @@ static radar_status launch_expand(const float *logits, const float *parent_score
                                   float *frontier_scores, float *frontier_conf, int32_t *pool_tokens,
                                   float *pool_scores, int32_t *pool_parents, const radar_expand_desc *d,
                                   const PolicyArgs *pol, radar_cycle_state *cycle, int B, void *workspace,
-                                  size_t workspace_bytes, void *stream) {
+                                  size_t workspace_bytes, void *stream_) {
     if (!d || !logits || !parent_scores || !parent_pool_idx || !cand_tokens || !cand_scores || !frontier_pool_idx ||
         !frontier_tokens || !frontier_scores || !frontier_conf || !pool_tokens || !pool_scores || !pool_parents ||
         !workspace)
@@ -527,8 +671,12 @@ static radar_status launch_expand(const float *logits, const float *parent_score
         return RADAR_INVALID_ARG;
     if (B < 1) return RADAR_INVALID_ARG;
     if (B > 65535) return RADAR_UNSUPPORTED_SHAPE;
+    // Batches large enough to fill the chip several times over take the two-launch streaming path
+    // (no prediction model there: its input-free part is shared out over the single launch's workgroups).
+    const bool stream = B > 1 && pol == nullptr && (int64_t)B * d->F <= 65535 &&
+                        (int64_t)B * d->F * d->V >= kStreamMinLogits;
     const int ept = plan_expand_ept((int)std::min<int64_t>((int64_t)d->F * B, 1 << 20), d->V);
-    const int64_t chunk = (int64_t)kExpThreads * ept;
+    const int64_t chunk = stream ? kStreamChunk : (int64_t)kExpThreads * ept;
     const int64_t nchunks = ((int64_t)d->V + chunk - 1) / chunk;
     if (d->F > RADAR_F_MAX || d->k > RADAR_K_MAX || nchunks > kExpMaxChunks) return RADAR_UNSUPPORTED_SHAPE;
     if (workspace_bytes < expand_workspace_bytes(d, (size_t)B)) return RADAR_WORKSPACE_TOO_SMALL;
@@ -557,8 +705,16 @@ static radar_status launch_expand(const float *logits, const float *parent_score
 
     const dim3 grid((unsigned)nchunks, (unsigned)d->F, (unsigned)B), block(kExpThreads);
     const bool vec4 = (d->V % 4 == 0) && (((uintptr_t)logits & 15) == 0);
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipStream_t st = static_cast<hipStream_t>(stream_);
     hipError_t e;
+    if (stream) {
+        const dim3 sgrid((unsigned)nchunks, (unsigned)(B * d->F));
+        e = vec4 ? launch("expand_stream", expand_stream_kernel<true>, sgrid, dim3(kStreamThreads), 0, st, a)
+                 : launch("expand_stream", expand_stream_kernel<false>, sgrid, dim3(kStreamThreads), 0, st, a);
+        if (e != hipSuccess) return RADAR_HIP_ERROR;
+        e = launch("expand_finish", expand_finish_kernel, dim3((unsigned)B), block, 0, st, a);
+        return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
+    }
     const bool ext = pol != nullptr || cycle != nullptr || B > 1;
 #define RADAR_EXPAND_LAUNCH(V4, E)                                                                   \
     (ext ? launch("expand", expand_kernel<V4, E, true>, grid, block, 0, st, a)                        \

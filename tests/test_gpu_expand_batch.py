@@ -25,6 +25,9 @@ GAP = 1e-4
     (7, 3, 4097, 5, 11),           # ragged tail, unaligned rows (scalar loads)
     (2, 64, 8192, 2, 0),           # most rows
     (1, 4, 4096, 4, 0),            # B = 1 through the batched entry point
+    (40, 3, 40001, 16, 11),        # streaming path (>= 4 Mi logits): odd V (scalar loads), ragged last wavefront, largest k
+    (64, 10, 8192, 2, 0),          # streaming path with eight lists per row
+    (4, 10, 128256, 10, 700),      # streaming path at its smallest 8B-shaped batch, pools nearly full
 ])
 def test_batched_call_matches_oracle_per_sequence(oracle, B, F, V, k, pre):
     from paper_2512_14069_amd import binding as b
@@ -117,6 +120,45 @@ def test_batched_cycles_stop_sequence_by_sequence(oracle, V, stops):
             assert int(host(t.n_nodes)[0]) == tree["n_nodes"] == 1 + min(N, n)
             for name in ("tokens", "parents", "depth", "pool_idx", "scores"):
                 assert np.array_equal(host(getattr(t, name)), tree[name]), (q, name)
+
+
+def test_streaming_path_with_cycle_states(oracle):
+    """A batch large enough for the two-launch path, every sequence with its own cycle state: different
+    pool counts, two sequences already stopped (left alone by both launches), no decision in the call."""
+    from paper_2512_14069_amd import binding as b
+    B, F, V, k = 6, 10, 128256, 10
+    rng = np.random.default_rng(synth.seed_for(9, 77))
+    counts = [10, 110, 50, 110, 20, 0]
+    stopped = [0, 0, 1, 0, 1, 0]
+    count_max, cap = 110, 110 + F * k
+    logits = np.stack([synth.expand_logits(rng, F, V, 2.5) for _ in range(B)])
+    ps = (-rng.random((B, F))).astype(np.float32)
+    ppi = np.stack([rng.integers(0, max(c, 1), F).astype(np.int32) for c in counts])
+    pool = b.DraftPool(cap, B=B)
+    pool.tokens.fill_(-5)
+    states = dev(np.array([[stopped[q], counts[q], 3, 1] for q in range(B)], np.int32))
+    out = b.ExpandOut(F, k, "cuda", B=B)
+    out.frontier_tokens.fill_(-7); out.cand_tokens.fill_(-7)
+    b.radar_draft_expand_batch(dev(logits), dev(ps), dev(ppi), k, pool, states=states, pool_count_max=count_max, out=out)
+    torch.cuda.synchronize()
+    st = host(states)
+    for q in range(B):
+        if stopped[q]:
+            assert st[q].tolist() == [1, counts[q], 3, 1]
+            assert np.all(host(out.frontier_tokens)[q] == -7) and np.all(host(out.cand_tokens)[q] == -7)
+            assert np.all(host(pool.tokens)[q] == -5)
+            continue
+        assert st[q].tolist() == [0, counts[q] + F * k, 4, 1], (q, st[q])
+        cp = dict(tokens=np.zeros(cap, np.int32), scores=np.zeros(cap, np.float32), parents=np.zeros(cap, np.int32))
+        r = oracle.draft_expand(logits[q], ps[q], ppi[q], k, cp, counts[q])
+        lo, hi = counts[q], counts[q] + F * k
+        assert np.array_equal(host(out.cand_tokens)[q].reshape(F, k), r["cand_tokens"]), q
+        assert np.max(np.abs(host(out.cand_scores)[q].reshape(F, k).astype(np.float64) - r["cand_scores"])) <= SCORE_TOL
+        assert np.array_equal(host(out.frontier_pool_idx)[q], r["frontier_pool_idx"]), q
+        assert np.array_equal(host(out.frontier_tokens)[q], r["frontier_tokens"]), q
+        assert np.array_equal(host(pool.tokens)[q, lo:hi], cp["tokens"][lo:hi]) and np.all(host(pool.tokens)[q, :lo] == -5)
+        assert np.array_equal(host(pool.parents)[q, lo:hi], cp["parents"][lo:hi])
+        assert np.max(np.abs(host(pool.scores)[q, lo:hi].astype(np.float64) - cp["scores"][lo:hi])) <= SCORE_TOL
 
 
 def test_batched_call_argument_errors(oracle):

@@ -98,6 +98,37 @@ def test_expand_random_shapes(oracle, seed):
         assert np.array_equal(host(getattr(t, name)), tree[name]), (seed, name)
 
 
+@pytest.mark.parametrize("seed", range(12 + EXTRA))
+def test_expand_batch_random_shapes(oracle, seed):
+    """radar_draft_expand_batch on batches on both sides of the size from which it streams in two launches."""
+    from paper_2512_14069_amd import binding as b
+    rng = np.random.default_rng(synth.seed_for(57, seed))
+    V = int(rng.choice([63, 1000, 1023, 4097, 9999, 33333, 70001]))
+    k = int(rng.integers(1, min(16, V) + 1))
+    F = int(rng.integers(1, 33))
+    target = (1 << 20) if seed % 2 else (5 << 20)
+    B = int(max(2, min(-(-target // (F * V)), 65535 // F, 300)))
+    pre = int(rng.integers(0, 8))
+    cap = pre + F * k
+    logits = np.stack([synth.expand_logits(rng, F, V, 3.0, normalised=bool(rng.integers(0, 2))) for _ in range(B)])
+    ps = (-rng.random((B, F)) * 4).astype(np.float32)
+    pidx = (rng.integers(0, pre, (B, F)) if pre else np.full((B, F), -1)).astype(np.int32)
+    gp = b.DraftPool(cap, B=B)
+    gp.count = pre
+    g, _ = b.radar_draft_expand_batch(dev(logits), dev(ps), dev(pidx), k, gp)
+    torch.cuda.synchronize()
+    for q in range(B):
+        cp = dict(tokens=np.zeros(cap, np.int32), scores=np.zeros(cap, np.float32), parents=np.zeros(cap, np.int32))
+        r = oracle.draft_expand(logits[q], ps[q], pidx[q], k, cp, pre)
+        assert np.array_equal(host(g.cand_tokens)[q].reshape(F, k), r["cand_tokens"]), (seed, q, B, F, V, k)
+        assert np.max(np.abs(host(g.cand_scores)[q].reshape(F, k).astype(np.float64) - r["cand_scores"])) <= 1e-5
+        assert np.array_equal(host(gp.tokens)[q, pre:], cp["tokens"][pre:]) and np.array_equal(host(gp.parents)[q, pre:], cp["parents"][pre:])
+        flat = np.sort(r["cand_scores"].reshape(-1))[::-1].astype(np.float64)
+        if len(flat) <= k or np.min(-np.diff(flat[:k + 1])) > 1e-4:
+            assert np.array_equal(host(g.frontier_pool_idx)[q], r["frontier_pool_idx"]), (seed, q, B, F, V, k)
+            assert np.array_equal(host(g.frontier_tokens)[q], r["frontier_tokens"])
+
+
 @pytest.mark.parametrize("seed", range(16 + EXTRA))
 def test_accept_random_shapes(oracle, seed):
     from paper_2512_14069_amd import binding as b
