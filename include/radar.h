@@ -441,9 +441,9 @@ radar_status radar_draft_rerank_cycle(const int32_t *pool_tokens, const float *p
  * any may have, and a sequence whose state says stopped is skipped (its
  * workgroups leave at once) while the others run.  The model's weights
  * (params) are shared.
- * Small batches, and batches with params, are one launch; a batch of at least
- * 4 Mi logits (B*F*V) without params is two: a streaming kernel over all
- * sequences, then one workgroup per sequence.  Integer results are the same
+ * Small batches are one launch; a batch of at least 4 Mi logits (B*F*V) is
+ * two: a streaming kernel over all sequences, then one workgroup per sequence
+ * (which also runs the prediction model's step when params != NULL).  Integer results are the same
  * either way; scores may differ in the last bit (the sums are grouped differently).
  * Limits: 1 <= B <= 65535.  The workspace is sized by
  * radar_draft_expand_batch_workspace_bytes(desc, B) (equal to

@@ -67,6 +67,7 @@ struct alignas(16) ExpandSmem {
     float cand_sc[RADAR_F_MAX * 16];
     int cand_tok[RADAR_F_MAX * 16];
     unsigned int ticket, ticket2;
+    float gate_pre[4 * kPolH];                    // w_hh h of the prediction model where the finishing workgroup computes it itself
 };
 
 // sum over the wavefront entries of l_i * exp(m_i - m): lanes 0..15 of a wavefront take one term
@@ -173,9 +174,11 @@ __device__ __forceinline__ void sequence_view(ExpandArgs &a, int bz) {
 // sequence is in the workspace (all 1024 lanes must call): rows are merged, candidates scored and
 // pooled, the next frontier chosen; with a prediction model its step follows, with a cycle state
 // its update.  `a` is already the sequence's own view of the call (bz = its index in the batch).
-template <bool EXT>
+// hidden(row) returns row `row` of w_hh h (complete before the call; only used with a prediction
+// model that has a state).
+template <bool EXT, typename Hidden>
 __device__ __forceinline__ void expand_finish(const ExpandArgs &a, ExpandSmem &s, int bz, radar_cycle_state *cycle,
-                                              bool cycle_first) {
+                                              bool cycle_first, Hidden &&hidden) {
     const bool has_policy = EXT && a.has_policy != 0;
     const int lane = lane_id(), w = wave_id();
     const int K = a.k;
@@ -258,7 +261,7 @@ __device__ __forceinline__ void expand_finish(const ExpandArgs &a, ExpandSmem &s
     static_assert(sizeof(PolicySmem) <= (kExpWaves - 1) * sizeof(WaveTopkSmem) && sizeof(WaveTopkSmem) % 16 == 0, "policy LDS overlay");
     PolicySmem &ps = *reinterpret_cast<PolicySmem *>(&s.wtk[1]);
     policy_step_block<true>(
-        a.pol, bz, a.pol_has_state != 0, ps, [&](int row) { return load_shared_result(&a.gate_pre[row]); },
+        a.pol, bz, a.pol_has_state != 0, ps, hidden,
         [&] { select_frontier(a, s, ps.x); },
         [&](int action) {
             if (cycle) {
@@ -406,7 +409,7 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
     if (tid == 0) store_shared_result(&a.counters[0], 0u);
 
     // ================= last workgroup of the call
-    expand_finish<EXT>(a, s, bz, cycle, cycle_first);
+    expand_finish<EXT>(a, s, bz, cycle, cycle_first, [&](int row) { return load_shared_result(&a.gate_pre[row]); });
 }
 
 // ------------------------------------------------------------------ rerank
@@ -615,7 +618,10 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_finish_kernel(ExpandArg
     radar_cycle_state *const cycle = a.cycle;
     const bool cycle_first = cycle != nullptr && a.pool_count == 0;
     if (cycle_skips(cycle, a.pool_count, &a.pool_count)) return;
-    expand_finish<true>(a, s, bz, cycle, cycle_first);
+    // the prediction model's input-free part, by the whole workgroup into LDS; the barrier that ends
+    // the row merge in expand_finish comes before its first use
+    if (a.has_policy && a.pol_has_state) policy_hidden_rows<16>(a.pol, bz, 0, 1, [&](int r, float v) { s.gate_pre[r] = v; });
+    expand_finish<true>(a, s, bz, cycle, cycle_first, [&](int row) { return s.gate_pre[row]; });
 }
 
 }  // namespace radar
@@ -671,9 +677,8 @@ static radar_status launch_expand(const float *logits, const float *parent_score
         return RADAR_INVALID_ARG;
     if (B < 1) return RADAR_INVALID_ARG;
     if (B > 65535) return RADAR_UNSUPPORTED_SHAPE;
-    // Batches large enough to fill the chip several times over take the two-launch streaming path
-    // (no prediction model there: its input-free part is shared out over the single launch's workgroups).
-    const bool stream = B > 1 && pol == nullptr && (int64_t)B * d->F <= 65535 &&
+    // Batches large enough to fill the chip several times over take the two-launch streaming path.
+    const bool stream = B > 1 && (int64_t)B * d->F <= 65535 &&
                         (int64_t)B * d->F * d->V >= kStreamMinLogits;
     const int ept = plan_expand_ept((int)std::min<int64_t>((int64_t)d->F * B, 1 << 20), d->V);
     const int64_t chunk = stream ? kStreamChunk : (int64_t)kExpThreads * ept;

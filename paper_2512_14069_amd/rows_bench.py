@@ -105,6 +105,17 @@ def main():
         args.reps, keep = max(1, args.reps // nsets), args.reps
         timed("radar_draft_expand_batch B=%d F=%d (%d calls)" % (B, k, nsets), calls, nsets * B * k * V * 4,
               "%d sequences per launch; time and bytes are for %d calls on different inputs" % (B, nsets))
+        if B == 16:                                        # the same calls with the decision of every sequence in them
+            poutB = b.PolicyOut(B, synth.POLICY_H, dev)
+            poutB.h.zero_(); poutB.c.zero_()
+            calls = []
+            for lg in sets:
+                pool.count = 0
+                calls.append(b.radar_draft_expand_batch(lg, ps, pi, k, pool, params=pp, h=poutB.h, c=poutB.c, out=eo,
+                                                        policy_out=poutB, workspace=bws, prepared=True))
+            args.reps = max(1, keep // nsets)
+            timed("radar_draft_expand_batch B=%d F=%d with the prediction model (%d calls)" % (B, k, nsets), calls,
+                  nsets * (B * k * V * 4 + pbytes), "as above, with every sequence's continue / stop decision in the call")
         args.reps = keep
         del sets, calls
         torch.cuda.empty_cache()

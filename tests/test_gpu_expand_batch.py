@@ -59,7 +59,11 @@ def test_batched_call_matches_oracle_per_sequence(oracle, B, F, V, k, pre):
         assert np.max(np.abs(host(gp.scores)[s, pre:cap].astype(np.float64) - cp["scores"][pre:cap])) <= SCORE_TOL
 
 
-@pytest.mark.parametrize("V,stops", [(32000, (1, 3, 8, 5, 2, 8)), (128256, (4, 8, 1))])
+@pytest.mark.parametrize("V,stops", [
+    (32000, (1, 3, 8, 5, 2, 8)),       # single-launch form throughout
+    (128256, (4, 8, 1)),
+    (128256, (2, 8, 5, 1, 7)),         # calls with k rows stream in two launches (the root-only first call does not)
+])
 def test_batched_cycles_stop_sequence_by_sequence(oracle, V, stops):
     """t_max batched draft calls with the prediction model and per-sequence cycle states: every sequence
     stops where its own oracle chain stops, the others go on; a stopped sequence's arrays stay as its
