@@ -461,6 +461,20 @@ radar_status radar_draft_expand_batch(const float *logits, const float *parent_s
                                       radar_cycle_state *states,
                                       void *workspace, size_t workspace_bytes, void *stream);
 
+/* radar_draft_rerank for B sequences in one launch: pool_* [B,pool_capacity];
+ * root_tokens i32 [B]; tree_* [B,N+1]; n_nodes_out i32 [B], i.e. the parents,
+ * tokens and n_nodes arrays that radar_tree_attention and radar_verify_accept
+ * take for a batch with T_max = N+1.  states == NULL: every pool holds
+ * pool_count candidates; states [B]: each holds its own state's count, at most
+ * pool_count.  Limits: those of radar_draft_rerank; pool_count <= pool_capacity;
+ * 1 <= B <= 65535.  Workspace as for radar_draft_rerank. */
+radar_status radar_draft_rerank_batch(const int32_t *pool_tokens, const float *pool_scores, const int32_t *pool_parents,
+                                      const radar_cycle_state *states, int32_t pool_count, int32_t pool_capacity,
+                                      int32_t B, int32_t N, const int32_t *root_tokens,
+                                      int32_t *tree_tokens, int32_t *tree_parents, float *tree_scores,
+                                      int32_t *tree_depth, int32_t *tree_pool_idx, int32_t *n_nodes_out,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+
 /* Counts, per call, the nodes i < n_nodes[b] whose parent breaks the tree
  * convention; *bad_count_out (device i32) is overwritten.  parents i32
  * [B,T_max]; n_nodes i32 [B] or NULL. */

@@ -75,7 +75,7 @@ EXPORTS = [
     "radar_draft_expand_workspace_bytes", "radar_draft_expand", "radar_draft_expand_policy",
     "radar_draft_rerank_workspace_bytes", "radar_draft_rerank",
     "radar_cycle_begin", "radar_draft_expand_cycle", "radar_draft_rerank_cycle",
-    "radar_draft_expand_batch_workspace_bytes", "radar_draft_expand_batch",
+    "radar_draft_expand_batch_workspace_bytes", "radar_draft_expand_batch", "radar_draft_rerank_batch",
     "radar_verify_accept_workspace_bytes", "radar_verify_accept",
     "radar_accept_length_distribution", "radar_policy_step",
     "radar_verify_accept_q_workspace_bytes", "radar_verify_accept_q",
@@ -119,6 +119,8 @@ def load():
     lib.radar_draft_expand_batch.restype = i32
     lib.radar_draft_expand_batch.argtypes = [vp] * 12 + [ctypes.POINTER(ExpandDesc), i32, ctypes.POINTER(PolicyParams),
                                              ctypes.POINTER(PolicyIO), vp, vp, sz, vp]
+    lib.radar_draft_rerank_batch.restype = i32
+    lib.radar_draft_rerank_batch.argtypes = [vp] * 4 + [i32, i32, i32, i32] + [vp] * 7 + [vp, sz, vp]
     lib.radar_draft_rerank_cycle.restype = i32
     lib.radar_draft_rerank_cycle.argtypes = [vp] * 4 + [i32, i32, i32] + [vp] * 6 + [vp, sz, vp]
     lib.radar_draft_rerank_workspace_bytes.restype = sz
@@ -366,13 +368,14 @@ def radar_draft_expand_policy(logits, parent_scores, parent_pool_idx, k, pool, p
 
 
 class TreeOut:
-    def __init__(self, N, device):
-        self.tokens = torch.empty(N + 1, dtype=torch.int32, device=device)
-        self.parents = torch.empty(N + 1, dtype=torch.int32, device=device)
-        self.scores = torch.empty(N + 1, dtype=torch.float32, device=device)
-        self.depth = torch.empty(N + 1, dtype=torch.int32, device=device)
-        self.pool_idx = torch.empty(N + 1, dtype=torch.int32, device=device)
-        self.n_nodes = torch.empty(1, dtype=torch.int32, device=device)
+    def __init__(self, N, device, B=None):
+        shape = (N + 1,) if B is None else (int(B), N + 1)
+        self.tokens = torch.empty(shape, dtype=torch.int32, device=device)
+        self.parents = torch.empty(shape, dtype=torch.int32, device=device)
+        self.scores = torch.empty(shape, dtype=torch.float32, device=device)
+        self.depth = torch.empty(shape, dtype=torch.int32, device=device)
+        self.pool_idx = torch.empty(shape, dtype=torch.int32, device=device)
+        self.n_nodes = torch.empty(1 if B is None else int(B), dtype=torch.int32, device=device)
 
 
 def radar_draft_rerank_workspace_bytes(pool_count, N):
@@ -513,6 +516,31 @@ def radar_draft_rerank_cycle(pool, state, pool_count_max, N, root_token, out=Non
         _ptr(out.depth, torch.int32), _ptr(out.pool_idx, torch.int32), _ptr(out.n_nodes, torch.int32),
         wp, wn, _stream())
     return _finish("radar_draft_rerank_cycle", load().radar_draft_rerank_cycle, args, (pool, state, out, workspace), out, prepared)
+
+
+def radar_draft_rerank_batch(pool, N, root_tokens, states=None, pool_count_max=None, out=None, workspace=None, prepared=False):
+    """radar_draft_rerank for the B sequences of a DraftPool(capacity, B=B) in one launch.  root_tokens i32 [B];
+    states None: every pool holds pool.count candidates; states i32 [B,4]: each its own state's count (at most
+    pool_count_max, default the capacity).  Returns a TreeOut with a leading B (what radar_tree_attention and
+    radar_verify_accept take as parents / tokens / n_nodes)."""
+    B = pool.tokens.shape[0]
+    if pool.tokens.dim() != 2 or root_tokens.numel() != B:
+        raise ValueError("expected DraftPool(capacity, B=B) and B root tokens")
+    if states is not None and states.numel() != 4 * B:
+        raise ValueError("states: expected [B, 4] int32")
+    if out is None:
+        out = TreeOut(N, pool.tokens.device, B=B)
+    count = pool.count if states is None else (pool.capacity if pool_count_max is None else pool_count_max)
+    wp, wn = _ws_args(workspace)
+    args = (
+        _ptr(pool.tokens, torch.int32), _ptr(pool.scores, torch.float32), _ptr(pool.parents, torch.int32),
+        None if states is None else _ptr(_dense(states, "states"), torch.int32, "states"),
+        int(count), int(pool.capacity), int(B), int(N), _ptr(_dense(root_tokens, "root_tokens"), torch.int32, "root_tokens"),
+        _ptr(out.tokens, torch.int32), _ptr(out.parents, torch.int32), _ptr(out.scores, torch.float32),
+        _ptr(out.depth, torch.int32), _ptr(out.pool_idx, torch.int32), _ptr(out.n_nodes, torch.int32),
+        wp, wn, _stream())
+    return _finish("radar_draft_rerank_batch", load().radar_draft_rerank_batch, args, (pool, states, root_tokens, out, workspace),
+                   out, prepared)
 
 
 # ------------------------------------------------------------ verification

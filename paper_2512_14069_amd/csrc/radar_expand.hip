@@ -419,6 +419,8 @@ struct RerankArgs {
     const int32_t *pool_parents;
     int pool_count, N, root_token;
     const radar_cycle_state *cycle;   // or null; when set, pool_count is the state's, clamped to the value above
+    const int32_t *root_tokens;       // batched call: one root token per sequence (else null: root_token)
+    int pool_capacity;                // batched call: stride of the pool arrays
     int32_t *tree_tokens;
     int32_t *tree_parents;
     float *tree_scores;
@@ -437,6 +439,15 @@ template <int EPT>                       // pool entries per lane: 4 (pools up t
 __global__ __launch_bounds__(kTopkThreads) void rerank_kernel(RerankArgs a) {
     __shared__ RerankSmem s;
     const int tid = threadIdx.x;
+    if (blockIdx.x != 0) {                               // sequence b of a batched call: every array has a leading batch dimension
+        const size_t b = blockIdx.x, n1 = (size_t)a.N + 1;
+        a.pool_tokens += b * a.pool_capacity; a.pool_scores += b * a.pool_capacity; a.pool_parents += b * a.pool_capacity;
+        a.tree_tokens += b * n1; a.tree_parents += b * n1; a.tree_scores += b * n1;
+        a.tree_depth += b * n1; a.tree_pool_idx += b * n1;
+        a.n_nodes_out += b;
+        if (a.cycle) a.cycle += b;
+    }
+    if (a.root_tokens) a.root_token = a.root_tokens[blockIdx.x];
     if (a.cycle) a.pool_count = min(max(a.cycle->pool_count, 0), a.pool_count);
     const int keep = min(a.N, a.pool_count);
 
@@ -840,20 +851,23 @@ extern "C" size_t radar_draft_rerank_workspace_bytes(int32_t pool_count, int32_t
 static radar_status launch_rerank(const int32_t *pool_tokens, const float *pool_scores, const int32_t *pool_parents,
                                   int32_t pool_count, const radar_cycle_state *cycle, int32_t N, int32_t root_token,
                                   int32_t *tree_tokens, int32_t *tree_parents, float *tree_scores,
-                                  int32_t *tree_depth, int32_t *tree_pool_idx, int32_t *n_nodes_out, void *stream) {
+                                  int32_t *tree_depth, int32_t *tree_pool_idx, int32_t *n_nodes_out, void *stream,
+                                  int32_t B = 1, const int32_t *root_tokens = nullptr, int32_t pool_capacity = 0) {
     if (!pool_tokens || !pool_scores || !pool_parents || !tree_tokens || !tree_parents || !tree_scores ||
         !tree_depth || !tree_pool_idx || !n_nodes_out)
         return RADAR_INVALID_ARG;
     if (pool_count < 0 || N < 0) return RADAR_INVALID_ARG;
     if (pool_count > RADAR_POOL_MAX || N >= RADAR_T_MAX) return RADAR_UNSUPPORTED_SHAPE;
+    if (B < 1 || (B > 1 && pool_capacity < pool_count)) return RADAR_INVALID_ARG;
     RerankArgs a;
+    a.root_tokens = root_tokens; a.pool_capacity = pool_capacity;
     a.pool_tokens = pool_tokens; a.pool_scores = pool_scores; a.pool_parents = pool_parents;
     a.pool_count = pool_count; a.N = N; a.root_token = root_token; a.cycle = cycle;
     a.tree_tokens = tree_tokens; a.tree_parents = tree_parents; a.tree_scores = tree_scores;
     a.tree_depth = tree_depth; a.tree_pool_idx = tree_pool_idx; a.n_nodes_out = n_nodes_out;
     const hipError_t e = pool_count <= 4 * kTopkThreads
-        ? launch("rerank", rerank_kernel<4>, dim3(1), dim3(kTopkThreads), 0, static_cast<hipStream_t>(stream), a)
-        : launch("rerank", rerank_kernel<16>, dim3(1), dim3(kTopkThreads), 0, static_cast<hipStream_t>(stream), a);
+        ? launch("rerank", rerank_kernel<4>, dim3((unsigned)B), dim3(kTopkThreads), 0, static_cast<hipStream_t>(stream), a)
+        : launch("rerank", rerank_kernel<16>, dim3((unsigned)B), dim3(kTopkThreads), 0, static_cast<hipStream_t>(stream), a);
     return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
 }
 
@@ -878,4 +892,18 @@ extern "C" radar_status radar_draft_rerank_cycle(const int32_t *pool_tokens, con
     if (!state) return RADAR_INVALID_ARG;
     return launch_rerank(pool_tokens, pool_scores, pool_parents, pool_count_max, state, N, root_token, tree_tokens,
                          tree_parents, tree_scores, tree_depth, tree_pool_idx, n_nodes_out, stream);
+}
+
+extern "C" radar_status radar_draft_rerank_batch(const int32_t *pool_tokens, const float *pool_scores,
+                                                 const int32_t *pool_parents, const radar_cycle_state *states,
+                                                 int32_t pool_count, int32_t pool_capacity, int32_t B, int32_t N,
+                                                 const int32_t *root_tokens, int32_t *tree_tokens,
+                                                 int32_t *tree_parents, float *tree_scores, int32_t *tree_depth,
+                                                 int32_t *tree_pool_idx, int32_t *n_nodes_out, void *workspace,
+                                                 size_t workspace_bytes, void *stream) {
+    (void)workspace; (void)workspace_bytes;
+    if (!root_tokens || B < 1 || pool_capacity < 0) return RADAR_INVALID_ARG;
+    if (B > 65535) return RADAR_UNSUPPORTED_SHAPE;
+    return launch_rerank(pool_tokens, pool_scores, pool_parents, pool_count, states, N, 0, tree_tokens, tree_parents,
+                         tree_scores, tree_depth, tree_pool_idx, n_nodes_out, stream, B, root_tokens, pool_capacity);
 }

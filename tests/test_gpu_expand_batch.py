@@ -97,6 +97,13 @@ def test_batched_cycles_stop_sequence_by_sequence(oracle, V, stops):
                 workspace=ws)
             count_max += (1 if s == 0 else K) * K
             ps, pi = eouts[s].frontier_scores, eouts[s].frontier_pool_idx
+        # the batch's trees in one launch, then the verify walk over the ragged batch
+        roots = dev(np.arange(1000, 1000 + B, dtype=np.int32))
+        tb = b.radar_draft_rerank_batch(pool, N, roots, states=states, pool_count_max=CAP)
+        target = dev(np.concatenate([x["target"] for x in xs]))                  # [B, N+1, V]
+        acc_uni = dev(np.concatenate([x["acc_uni"] for x in xs]))                # [B, N+2]
+        alen, apath, bonus = b.radar_verify_accept(target, tb.tokens, tb.parents, tb.n_nodes, acc_uni,
+                                                   mode=b.RADAR_ACCEPT_SAMPLE, D_max=N)
         torch.cuda.synchronize()
         st = host(states)
         for q, ref in enumerate(refs):
@@ -115,15 +122,24 @@ def test_batched_cycles_stop_sequence_by_sequence(oracle, V, stops):
                 for name in ("h", "c", "logits", "probs"):
                     assert np.max(np.abs(host(getattr(pout, name))[q] - last[name][0])) <= POLICY_TOL, (q, name)
                 assert host(pout.action)[q] == last["action"][0]
-            # the tree of sequence q: the device's rerank of its own pool against the oracle's
+            # the tree of sequence q: the device's rerank of its own pool against the oracle's, by the batched
+            # call and by the single-sequence call on a view of the same arrays
             view = types.SimpleNamespace(tokens=pool.tokens[q], scores=pool.scores[q], parents=pool.parents[q], capacity=CAP)
-            t = b.radar_draft_rerank_cycle(view, states[q], CAP, N, 1234)
+            t = b.radar_draft_rerank_cycle(view, states[q], CAP, N, 1000 + q)
             torch.cuda.synchronize()
             gpool = dict(tokens=host(pool.tokens)[q].copy(), scores=host(pool.scores)[q].copy(), parents=host(pool.parents)[q].copy())
-            tree = oracle.draft_rerank(gpool, n, N, 1234)
-            assert int(host(t.n_nodes)[0]) == tree["n_nodes"] == 1 + min(N, n)
+            tree = oracle.draft_rerank(gpool, n, N, 1000 + q)
+            assert int(host(t.n_nodes)[0]) == int(host(tb.n_nodes)[q]) == tree["n_nodes"] == 1 + min(N, n)
             for name in ("tokens", "parents", "depth", "pool_idx", "scores"):
                 assert np.array_equal(host(getattr(t, name)), tree[name]), (q, name)
+                assert np.array_equal(host(getattr(tb, name))[q], tree[name]), (q, name)
+            nn = np.array([tree["n_nodes"]], np.int32)
+            x = xs[q]
+            o_len, o_path, o_bonus = oracle.verify_accept(x["target"], tree["tokens"][None], tree["parents"][None], nn,
+                                                          x["acc_uni"], mode=1, D_max=N)
+            m = oracle.accept_margins(x["target"], tree["tokens"][None], tree["parents"][None], nn, x["acc_uni"])
+            if (m > 2e-7).all():
+                assert host(alen)[q] == o_len[0] and np.array_equal(host(apath)[q], o_path[0]) and host(bonus)[q] == o_bonus[0]
 
 
 def test_streaming_path_with_cycle_states(oracle):
@@ -163,6 +179,37 @@ def test_streaming_path_with_cycle_states(oracle):
         assert np.array_equal(host(pool.tokens)[q, lo:hi], cp["tokens"][lo:hi]) and np.all(host(pool.tokens)[q, :lo] == -5)
         assert np.array_equal(host(pool.parents)[q, lo:hi], cp["parents"][lo:hi])
         assert np.max(np.abs(host(pool.scores)[q, lo:hi].astype(np.float64) - cp["scores"][lo:hi])) <= SCORE_TOL
+
+
+@pytest.mark.parametrize("B,count,cap,N", [(5, 810, 900, 60), (3, 4096, 4096, 63), (4, 3, 10, 7), (2, 0, 4, 5), (70, 64, 64, 0)])
+def test_batched_rerank_matches_oracle_per_sequence(oracle, B, count, cap, N):
+    """radar_draft_rerank_batch without states: forests with exact score ties, every sequence its own."""
+    from paper_2512_14069_amd import binding as b
+    rng = np.random.default_rng(B * 7 + count + N)
+    pool = b.DraftPool(cap, B=B)
+    cps = []
+    for q in range(B):
+        cp = dict(tokens=np.zeros(cap, np.int32), scores=np.zeros(cap, np.float32), parents=np.zeros(cap, np.int32))
+        for i in range(count):
+            par = -1 if i < 4 or rng.random() < 0.1 else int(rng.integers(0, i))
+            cp["parents"][i] = par
+            cp["scores"][i] = (cp["scores"][par] if par >= 0 else 0.0) - float(rng.integers(0, 4)) * 0.25
+            cp["tokens"][i] = int(rng.integers(0, 1000))
+        cps.append(cp)
+    for name in ("tokens", "scores", "parents"):
+        getattr(pool, name).copy_(dev(np.stack([cp[name] for cp in cps])))
+    pool.count = count
+    roots = dev(np.arange(7, 7 + B, dtype=np.int32))
+    t = b.radar_draft_rerank_batch(pool, N, roots)
+    torch.cuda.synchronize()
+    for q in range(B):
+        tree = oracle.draft_rerank(cps[q], count, N, root_token=7 + q)
+        assert int(host(t.n_nodes)[q]) == tree["n_nodes"]
+        for name in ("tokens", "parents", "depth", "pool_idx", "scores"):
+            assert np.array_equal(host(getattr(t, name))[q], tree[name]), (q, name)
+    with pytest.raises(b.RadarError):                      # more candidates than the arrays hold
+        pool.count = cap + 1
+        b.radar_draft_rerank_batch(pool, N, roots)
 
 
 def test_batched_call_argument_errors(oracle):
