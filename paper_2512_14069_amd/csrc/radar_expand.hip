@@ -67,7 +67,6 @@ struct alignas(16) ExpandSmem {
     float cand_sc[RADAR_F_MAX * 16];
     int cand_tok[RADAR_F_MAX * 16];
     unsigned int ticket, ticket2;
-    float gate_pre[4 * kPolH];                    // w_hh h of the prediction model where the finishing workgroup computes it itself
 };
 
 // sum over the wavefront entries of l_i * exp(m_i - m): lanes 0..15 of a wavefront take one term
@@ -543,6 +542,14 @@ __global__ __launch_bounds__(kStreamThreads) void expand_stream_kernel(ExpandArg
     const int base = blockIdx.x * kStreamChunk + w * kStreamWaveLogits;
     const float *rowp = a.logits + (size_t)row * a.V;
     const int K = a.k;
+    // The prediction model's input-free part (w_hh h) of this row's sequence is shared out over the
+    // sequence's workgroups, eight rows each, as the single launch does; the finish kernel reads it.
+    if (a.has_policy && a.pol_has_state) {
+        const int bz = row / a.F;
+        float *gate = a.gate_pre + (size_t)bz * (4 * kPolH);
+        policy_hidden_rows<4, kStreamThreads / 32>(a.pol, bz, (row - bz * a.F) * gridDim.x + blockIdx.x, a.F * gridDim.x,
+                                                   [&](int r, float v) { gate[r] = v; });
+    }
 
     float4 raw[4];
 #pragma unroll
@@ -629,10 +636,8 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_finish_kernel(ExpandArg
     radar_cycle_state *const cycle = a.cycle;
     const bool cycle_first = cycle != nullptr && a.pool_count == 0;
     if (cycle_skips(cycle, a.pool_count, &a.pool_count)) return;
-    // the prediction model's input-free part, by the whole workgroup into LDS; the barrier that ends
-    // the row merge in expand_finish comes before its first use
-    if (a.has_policy && a.pol_has_state) policy_hidden_rows<16>(a.pol, bz, 0, 1, [&](int r, float v) { s.gate_pre[r] = v; });
-    expand_finish<true>(a, s, bz, cycle, cycle_first, [&](int row) { return s.gate_pre[row]; });
+    // (the prediction model's input-free part was left in the workspace by the streaming kernel)
+    expand_finish<true>(a, s, bz, cycle, cycle_first, [&](int row) { return a.gate_pre[row]; });
 }
 
 }  // namespace radar

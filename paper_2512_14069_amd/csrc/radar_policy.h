@@ -67,21 +67,21 @@ __device__ __forceinline__ float fast_tanh(float a) { return 1.f - 2.f * __frcp_
 
 // The part of the gate pre-activations that needs no input: rows of w_hh times h_in.  A row is
 // 128 floats = one 32-lane half-wavefront x 16 bytes.  The calling workgroup is part `part` of
-// `parts` that share the 4H rows; its 32 half-wavefronts take rows (part + parts * i) * 32 +
-// half-wavefront for i = 0, 1, ... in batches of NR (4 or 16) rows per lane, all loads of a
-// batch issued before its sums are folded.  store(row, value) is called by one lane per row.
-template <int NR, typename Store>
+// `parts` that share the 4H rows; its HW half-wavefronts (32 in a workgroup of 1024 lanes) take rows
+// (part + parts * i) * HW + half-wavefront for i = 0, 1, ... in batches of NR (4 or 16) rows per lane,
+// all loads of a batch issued before its sums are folded.  store(row, value) is called by one lane per row.
+template <int NR, int HW = 32, typename Store>
 __device__ __forceinline__ void policy_hidden_rows(const PolicyArgs &p, int b, int part, int parts, Store &&store) {
     static_assert(NR == 4 || NR == 16, "NR");
     const int lane = threadIdx.x % kWave, j = lane & 31, hwave = threadIdx.x >> 5;
     const int rows = 4 * kPolH;
-    if (part * 32 >= rows) return;
+    if (part * HW >= rows) return;
     const float4 h4 = *reinterpret_cast<const float4 *>(p.h_in + (size_t)b * kPolH + 4 * j);
-    for (int i0 = 0; (part + parts * i0) * 32 < rows; i0 += NR) {
+    for (int i0 = 0; (part + parts * i0) * HW < rows; i0 += NR) {
         float v[NR];
 #pragma unroll
         for (int i = 0; i < NR; ++i) {
-            const int row = min((part + parts * (i0 + i)) * 32 + hwave, rows - 1);      // clamped: stays a legal read
+            const int row = min((part + parts * (i0 + i)) * HW + hwave, rows - 1);      // clamped: stays a legal read
             const float4 wv = *reinterpret_cast<const float4 *>(p.w_hh + (size_t)row * kPolH + 4 * j);
             v[i] = fmaf(wv.x, h4.x, fmaf(wv.y, h4.y, fmaf(wv.z, h4.z, wv.w * h4.w)));
         }
@@ -103,7 +103,7 @@ __device__ __forceinline__ void policy_hidden_rows(const PolicyArgs &p, int b, i
         }
         const int blk = part + parts * (i0 + mine);
         const bool writer = NR == 16 ? (lane & 1) == 0 : (lane & 7) == 0;
-        if (writer && blk * 32 < rows) store(blk * 32 + hwave, v[0]);
+        if (writer && blk * HW < rows) store(blk * HW + hwave, v[0]);
     }
 }
 
