@@ -497,8 +497,9 @@ radar_status radar_debug_validate_tree(const int32_t *parents, const int32_t *n_
  * entries in *n_out and destroys the events.  These two calls are the only
  * ones that create or destroy anything and that synchronise. */
 typedef struct radar_kernel_time {
-    char name[48];      /* "expand", "rerank", "accept", "accept_length_distribution",
-                           "tree_attn_group_share", "tree_attn_merge", ... */
+    char name[48];      /* "expand", "expand_stream", "expand_finish", "rerank", "accept",
+                           "accept_length_distribution", "tree_attn_group_share",
+                           "tree_attn_merge", ... */
     int64_t calls;
     double total_us;
     double min_us;
