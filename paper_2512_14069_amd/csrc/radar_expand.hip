@@ -531,7 +531,7 @@ __device__ __forceinline__ bool cycle_skips(const radar_cycle_state *st, int poo
 template <bool VEC4>
 __global__ __launch_bounds__(kStreamThreads) void expand_stream_kernel(ExpandArgs a) {
     __shared__ WaveTopkSmem wtk[kStreamWaves];
-    __shared__ uint64_t wlists[kStreamWaves][2 * kWaveListSlots];
+    __shared__ uint64_t wlists[kStreamWaves][kWaveListSlots];
     __shared__ float wave_m[kStreamWaves];
     __shared__ double wave_l[kStreamWaves];
     const int lane = lane_id(), w = wave_id();
@@ -564,52 +564,50 @@ __global__ __launch_bounds__(kStreamThreads) void expand_stream_kernel(ExpandArg
             raw[g].w = rowp[min(idx0 + 3, a.V - 1)];
         }
     }
-    float x[2][8];
+    float x[16];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-        const int idx0 = base + g * (kWave * 4) + lane * 4;
-        const float v[4] = {raw[g].x, raw[g].y, raw[g].z, raw[g].w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) x[g >> 1][4 * (g & 1) + j] = (idx0 + j < a.V) ? v[j] : -INFINITY;
+        x[4 * g + 0] = raw[g].x; x[4 * g + 1] = raw[g].y; x[4 * g + 2] = raw[g].z; x[4 * g + 3] = raw[g].w;
     }
-    float hm[2];
+    if (base + kStreamWaveLogits > a.V) {                          // wave-uniform: the row's last wavefront(s) only
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        hm[h] = x[h][0];
-#pragma unroll
-        for (int e = 1; e < 8; ++e) hm[h] = fmaxf(hm[h], x[h][e]);
+        for (int e = 0; e < 16; ++e) {
+            const int idx = base + (e >> 2) * (kWave * 4) + lane * 4 + (e & 3);
+            x[e] = idx < a.V ? x[e] : -INFINITY;
+        }
     }
-    const float wm = wave_max_f32(fmaxf(hm[0], hm[1]));
+    float tm = x[0];
+#pragma unroll
+    for (int e = 1; e < 16; ++e) tm = fmaxf(tm, x[e]);
+    const float wm = wave_max_f32(tm);
     float tl = 0.f;
     if (wm > -INFINITY) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) tl += __builtin_amdgcn_exp2f((x[h][e] - wm) * kLog2eF);
+        for (int e = 0; e < 16; ++e) tl += __builtin_amdgcn_exp2f((x[e] - wm) * kLog2eF);
     }
     const double wl = wave_sum_f64((double)tl);
 
-    // candidates of each half (512 logits, eight per lane), then the top-k of the two lists
+    // the wavefront's candidates (unranked; ranked only where more than 32 of them pass the threshold)
+    {
+        uint64_t *list = &wlists[w][0];
+        if (!wave_candidates_counted<16>(x, tm, uint32_t(base + lane * 4), uint32_t(kWave * 4), uint32_t(a.V), K, list)) {
+            uint64_t k1[8], k2[9];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        uint64_t *list = &wlists[w][h * kWaveListSlots];
-        const int hbase = base + h * (kStreamWaveLogits / 2);
-        if (!wave_candidates<8>(x[h], hm[h], uint32_t(hbase + lane * 4), uint32_t(kWave * 4), uint32_t(a.V), K, wtk[w], list)) {
-            uint64_t keys[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int idx = hbase + (e >> 2) * (kWave * 4) + lane * 4 + (e & 3);
-                keys[e] = idx < a.V ? make_key(x[h][e], uint32_t(idx)) : 0;
+            for (int e = 0; e < 16; ++e) {
+                const int idx = base + (e >> 2) * (kWave * 4) + lane * 4 + (e & 3);
+                const uint64_t key = idx < a.V ? make_key(x[e], uint32_t(idx)) : 0;
+                if (e < 8) k1[e] = key; else k2[e - 8] = key;
             }
-            const uint64_t wt = wave_topk<8>(keys, K, wtk[w]);
+            k2[8] = wave_topk<8>(k1, K, wtk[w]);
+            const uint64_t wt = wave_topk<9>(k2, K, wtk[w]);
             if (lane < kWaveListSlots) list[lane] = wt;            // lanes 16.. hold 0
         }
     }
     if (lane == 0) { wave_m[w] = wm; wave_l[w] = wl; }
     __syncthreads();
     const size_t slot = (size_t)row * a.nchunks + blockIdx.x;
-    if (w == 0) {                                                              // the chunk's list: top-k of the eight lists
-        constexpr int NS = kStreamWaves * 2 * kWaveListSlots / kWave;
+    if (w == 0) {                                                              // the chunk's list: top-k of the four lists
+        constexpr int NS = kStreamWaves * kWaveListSlots / kWave;
         uint64_t kk[NS];
 #pragma unroll
         for (int e = 0; e < NS; ++e) kk[e] = (&wlists[0][0])[topk_slot_of(e)];   // rotated: the used slots lead each list

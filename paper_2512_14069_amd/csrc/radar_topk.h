@@ -213,6 +213,36 @@ __device__ __forceinline__ bool wave_candidates(const float (&x)[EPL], float lan
     return true;
 }
 
+// The same for up to 16 elements per lane with the same small scratch: the survivors are counted
+// first (comparison masks stay in scalar registers) and compacted only if they fit the list.
+template <int EPL>
+__device__ __forceinline__ bool wave_candidates_counted(const float (&x)[EPL], float lane_max, uint32_t idx0, uint32_t gstride,
+                                                        uint32_t V, int K, uint64_t *list) {
+    static_assert(EPL <= 16, "masks");
+    const int lane = lane_id();
+    const uint32_t tau = quad_threshold(idx0 < V ? ord_of(lane_max) : 0u, K);
+    const float tau_f = tau < 0x00800000u ? -INFINITY : float_of_ord(tau);
+    uint64_t m[EPL];
+    int total = 0;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        const uint32_t idx = idx0 + (uint32_t)(e >> 2) * gstride + (uint32_t)(e & 3);
+        m[e] = __ballot(x[e] >= tau_f && idx < V);
+        total += __popcll(m[e]);
+    }
+    if (total > kWaveListSlots) return false;
+    if (lane < kWaveListSlots) list[lane] = 0;
+    wave_lds_sync();
+    int n = 0;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        const uint32_t idx = idx0 + (uint32_t)(e >> 2) * gstride + (uint32_t)(e & 3);
+        if ((m[e] >> lane) & 1) list[n + lanes_below(m[e])] = make_key(x[e], idx);
+        n += __popcll(m[e]);
+    }
+    return true;
+}
+
 // Lists of 16 slots of which the first K are used (slot i: list i / 16, rank i % 16), taken 64
 // slots per step: which slot a lane takes at step e.  Lanes rotate by 4 per step, so a lane
 // meets slots of different ranks and every quad of lanes holds used slots.
