@@ -428,10 +428,16 @@ struct RerankArgs {
     int32_t *n_nodes_out;
 };
 
+constexpr int kRerankStaged = 4 * kTopkThreads;       // pools up to this size are copied to LDS whole
+
 struct RerankSmem {
     TopkSmem topk;
     int16_t node_of[RADAR_POOL_MAX];     // pool index -> node number, -1 if dropped
     int32_t parent[RADAR_T_MAX];
+    // small pools: tokens, parents and scores ride along with the first loads, so that the kept
+    // entries are read from LDS instead of a second round trip to memory
+    int32_t tok[kRerankStaged], par[kRerankStaged];
+    float sc[kRerankStaged];
 };
 
 template <int EPT>                       // pool entries per lane: 4 (pools up to 1024) or 16
@@ -450,12 +456,29 @@ __global__ __launch_bounds__(kTopkThreads) void rerank_kernel(RerankArgs a) {
     if (a.cycle) a.pool_count = min(max(a.cycle->pool_count, 0), a.pool_count);
     const int keep = min(a.N, a.pool_count);
 
+    constexpr bool kStaged = EPT * kTopkThreads <= kRerankStaged;
     uint64_t keys[EPT];
+    if constexpr (kStaged) {
+        float sc[EPT];
+        int tk[EPT], pr[EPT];
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-        const int i = tid + e * kTopkThreads;
-        const float sc = a.pool_scores[max(0, min(i, a.pool_count - 1))];
-        keys[e] = (i < a.pool_count) ? make_key(sc, uint32_t(i)) : 0;
+        for (int e = 0; e < EPT; ++e) {                      // all loads first: one round trip
+            const int i = max(0, min(tid + e * kTopkThreads, a.pool_count - 1));
+            sc[e] = a.pool_scores[i]; tk[e] = a.pool_tokens[i]; pr[e] = a.pool_parents[i];
+        }
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const int i = tid + e * kTopkThreads;
+            keys[e] = (i < a.pool_count) ? make_key(sc[e], uint32_t(i)) : 0;
+            s.sc[i] = sc[e]; s.tok[i] = tk[e]; s.par[i] = pr[e];
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const int i = tid + e * kTopkThreads;
+            const float sc = a.pool_scores[max(0, min(i, a.pool_count - 1))];
+            keys[e] = (i < a.pool_count) ? make_key(sc, uint32_t(i)) : 0;
+        }
     }
     for (int i = tid; i < a.pool_count; i += kTopkThreads) s.node_of[i] = -1;
     if (keep > 0) block_topk<EPT>(keys, keep, s.topk);
@@ -474,10 +497,10 @@ __global__ __launch_bounds__(kTopkThreads) void rerank_kernel(RerankArgs a) {
         float sc = 0.f;
         if (tid == 0) { tok = a.root_token; }
         else if (tid <= keep) {
-            tok = a.pool_tokens[my_pool];
-            sc = a.pool_scores[my_pool];
+            tok = kStaged ? s.tok[my_pool] : a.pool_tokens[my_pool];
+            sc = kStaged ? s.sc[my_pool] : a.pool_scores[my_pool];
             pidx = my_pool;
-            const int pp = a.pool_parents[my_pool];
+            const int pp = kStaged ? s.par[my_pool] : a.pool_parents[my_pool];
             if (pp < 0) par = 0;
             else if (pp < a.pool_count && s.node_of[pp] >= 0 && s.node_of[pp] < tid) par = s.node_of[pp];
             else par = -2;
