@@ -928,7 +928,7 @@ extern "C" radar_status radar_draft_rerank_batch(const int32_t *pool_tokens, con
                                                  int32_t *tree_pool_idx, int32_t *n_nodes_out, void *workspace,
                                                  size_t workspace_bytes, void *stream) {
     (void)workspace; (void)workspace_bytes;
-    if (!root_tokens || B < 1 || pool_capacity < 0) return RADAR_INVALID_ARG;
+    if (!root_tokens || B < 1 || pool_capacity < 0 || pool_count > pool_capacity) return RADAR_INVALID_ARG;
     if (B > 65535) return RADAR_UNSUPPORTED_SHAPE;
     return launch_rerank(pool_tokens, pool_scores, pool_parents, pool_count, states, N, 0, tree_tokens, tree_parents,
                          tree_scores, tree_depth, tree_pool_idx, n_nodes_out, stream, B, root_tokens, pool_capacity);
