@@ -352,7 +352,9 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
         bool listed = false;
         if constexpr (EPT <= 8)
             listed = wave_candidates<EPT>(x, tm, uint32_t(base + tid * 4), uint32_t(kExpThreads * 4), uint32_t(a.V), K, s.wtk[w], list);
-        if (!listed) {                                             // 16 logits per lane, or more than 32 candidates: rank
+        else
+            listed = wave_candidates_counted<EPT>(x, tm, uint32_t(base + tid * 4), uint32_t(kExpThreads * 4), uint32_t(a.V), K, list);
+        if (!listed) {                                             // more than 32 candidates: rank
             uint64_t keys[EPT];
 #pragma unroll
             for (int e = 0; e < EPT; ++e) {
