@@ -22,3 +22,18 @@ def bf16_bits(t):
 
 def host(t):
     return t.detach().cpu().numpy()
+
+
+def tie_free_uniforms(margins_of, uniforms, rng, tries=200):
+    """The inputs' tie guard for sampled verification: sequences in which some decision sits too
+    close to its threshold for an fp32 device path get fresh uniforms (seeded), until none does.
+    margins_of(uniforms) -> bool[B], True where the sequence is decided clear of every threshold
+    (computed by the CPU oracle).  Returns the uniforms to use; every sequence can then be compared."""
+    u = np.array(uniforms, np.float32, copy=True)
+    for _ in range(tries):
+        ok = margins_of(u)
+        if ok.all():
+            return u
+        bad = np.nonzero(~ok)[0]
+        u[bad] = rng.random((len(bad),) + u.shape[1:], dtype=np.float32)
+    raise AssertionError("no tie-free uniforms found")

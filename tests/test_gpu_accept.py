@@ -1,16 +1,17 @@
 """GPU parity: radar_verify_accept (through the C ABI) against the CPU oracle.
-Accepted lengths, paths and bonus tokens must be bit-exact.  In sampling mode a case
-is compared only if the oracle reports that no decision sat within MARGIN of its
-threshold ("tie-free"): over a 128K vocabulary one token carries about 1e-5 of the mass,
-so the inverse-CDF draw always lands within that distance of a boundary and the device
-has to resolve far finer than that.  It sums exponentials in fp64 (fp32 only inside
-expf), which leaves about 1e-8; MARGIN sits an order of magnitude above."""
+Accepted lengths, paths and bonus tokens must be bit-exact, for EVERY sequence.  In sampling
+mode the inputs are made tie-free first: a sequence in which the oracle reports a decision
+within MARGIN of its threshold gets fresh seeded uniforms (the margins themselves are pinned
+in tests/test_oracle_margins.py).  Over a 128K vocabulary one token carries about 1e-5 of the
+mass, so the inverse-CDF draw always lands within that distance of a boundary and the device
+has to resolve far finer than that.  It sums exponentials in fp64 (fp32 only inside expf),
+which leaves about 1e-8; MARGIN sits an order of magnitude above."""
 import numpy as np
 import pytest
 import torch
 
 from paper_2512_14069_amd import synth
-from gpu_util import dev, host
+from gpu_util import dev, host, tie_free_uniforms
 
 pytestmark = pytest.mark.gpu
 
@@ -26,22 +27,17 @@ def run_gpu(b, x, mode, temperature=1.0, D_max=None, ws=None, use_n_nodes=True):
     return [host(t) for t in out]
 
 
-def compare(oracle, b, x, mode, temperature=1.0, require_all=False):
+def compare(oracle, b, x, mode, temperature=1.0):
+    if mode == 1:
+        def clear(u):
+            m = oracle.accept_margins(x["target_logits"], x["draft_tokens"], x["parents"], x["n_nodes"], u, temperature)
+            return (m[:, 0] > MARGIN) & (m[:, 1] > MARGIN)
+        x = dict(x, uniforms=tie_free_uniforms(clear, x["uniforms"], np.random.default_rng(int(x["uniforms"].size))))
     ref = oracle.verify_accept(x["target_logits"], x["draft_tokens"], x["parents"], x["n_nodes"],
                                x["uniforms"] if mode == 1 else None, mode=mode, temperature=temperature)
     got = run_gpu(b, x, mode, temperature)
-    B = x["target_logits"].shape[0]
-    ok = np.ones(B, bool)
-    if mode == 1:
-        m = oracle.accept_margins(x["target_logits"], x["draft_tokens"], x["parents"], x["n_nodes"],
-                                  x["uniforms"], temperature)
-        ok = (m[:, 0] > MARGIN) & (m[:, 1] > MARGIN)
-        if require_all:
-            assert ok.all(), f"seed gives a decision within {MARGIN} of its threshold: {m}"
-    assert ok.sum() >= max(1, B // 2)
-    assert np.array_equal(got[0][ok], ref[0][ok])
-    assert np.array_equal(got[1][ok], ref[1][ok])
-    assert np.array_equal(got[2][ok], ref[2][ok])
+    for name, g, r in zip(("accept_len", "accept_path", "bonus_token"), got, ref):
+        assert np.array_equal(g, r), (name, np.nonzero((g != r).reshape(len(r), -1).any(axis=1))[0][:8])
     return ref, got
 
 
@@ -67,7 +63,7 @@ def test_config2_shape(oracle, mode):
     from paper_2512_14069_amd import binding as b
     c = synth.config(2)
     x = synth.accept_inputs(c.attn, c.vocab, seed=synth.seed_for(2, mode), plant=0.75)
-    compare(oracle, b, x, mode, require_all=(mode == 1))
+    compare(oracle, b, x, mode)
 
 
 def test_config4_ragged_full_size(oracle):

@@ -14,7 +14,7 @@ import pytest
 import torch
 
 from paper_2512_14069_amd import synth
-from gpu_util import dev, host
+from gpu_util import dev, host, tie_free_uniforms
 
 pytestmark = pytest.mark.gpu
 
@@ -22,8 +22,20 @@ ACCEPT_MARGIN = 1e-5
 CDF_MARGIN = 5e-7
 
 
+def tie_free(oracle, x, q_rows=True, **kw):
+    """The inputs' tie guard: sequences with a decision too close to its threshold get fresh uniforms."""
+    qr = x["q_rows"] if q_rows else None
+
+    def clear(u):
+        m = oracle.verify_accept_q(x["target_logits"], x["draft_logits"], x["draft_tokens"], x["parents"], x["n_nodes"],
+                                   u, qr, want_margins=True, **kw)[3]
+        return (m[:, 0] > ACCEPT_MARGIN) & (m[:, 1] > CDF_MARGIN)
+    return dict(x, uniforms=tie_free_uniforms(clear, x["uniforms"], np.random.default_rng(int(x["uniforms"].size))))
+
+
 def run_both(oracle, b, x, q_rows=True, **kw):
     qr = x["q_rows"] if q_rows else None
+    x = tie_free(oracle, x, q_rows, **kw)
     ref = oracle.verify_accept_q(x["target_logits"], x["draft_logits"], x["draft_tokens"], x["parents"], x["n_nodes"],
                                  x["uniforms"], qr, want_margins=True, **kw)
     args = (dev(x["target_logits"]), dev(x["draft_logits"]), dev(x["draft_tokens"]), dev(x["parents"]),
@@ -39,9 +51,9 @@ def run_both(oracle, b, x, q_rows=True, **kw):
     return ref, got
 
 
-def compare(ref, got, min_sure):
+def compare(ref, got):
     sure = (ref[3][:, 0] > ACCEPT_MARGIN) & (ref[3][:, 1] > CDF_MARGIN)
-    assert sure.mean() >= min_sure, sure.mean()
+    assert sure.all()                                              # the guard above: every sequence is compared
     for name, r, g in zip(("accept_len", "accept_path", "bonus_token"), ref[:3], got):
         assert g.shape == r.shape, name
         bad = np.nonzero(sure & ~(g == r).reshape(len(sure), -1).all(axis=1))[0]
@@ -71,11 +83,11 @@ def test_ragged_batch_matches_oracle(oracle, V, T, shared):
     B = 24 if V < 100000 else 10
     x = synth.sampled_draft_inputs(rng, ragged_trees(rng, B, T, 4, V), V, T, std=2.0, noise=1.0, shared_rows=shared)
     ref, got = run_both(oracle, b, x)
-    compare(ref, got, 0.8)
+    compare(ref, got)
     assert len(set(ref[0].tolist())) >= 3                       # several accepted lengths occur
     if not shared:                                              # every node has its own row: the map may be left out
         ref2, got2 = run_both(oracle, b, x, q_rows=False)
-        compare(ref2, got2, 0.8)
+        compare(ref2, got2)
         assert all(np.array_equal(p, q) for p, q in zip(ref[:3], ref2[:3]))
 
 
@@ -88,10 +100,10 @@ def test_many_rejections_at_one_node_and_the_depth_cut(oracle):
     par = [synth.star_tree(T) if i % 2 == 0 else synth.make_tree(rng, T, 3, 10, V)[0] for i in range(B)]
     x = synth.sampled_draft_inputs(rng, par, V, T, std=1.5, noise=4.0, shared_rows=True)
     ref, got = run_both(oracle, b, x)
-    compare(ref, got, 0.7)
+    compare(ref, got)
     for D in (1, 0):
         ref, got = run_both(oracle, b, x, D_max=D)
-        compare(ref, got, 0.7)
+        compare(ref, got)
         assert got[1].shape == (B, D + 1)
 
 
@@ -101,7 +113,7 @@ def test_chain_with_temperatures_and_config3_shape(oracle):
     rng = np.random.default_rng(synth.seed_for(32, 6))
     x = synth.sampled_draft_inputs(rng, [synth.chain_tree(T)] * B, V, T, std=3.0, noise=1.5, shared_rows=False)
     ref, got = run_both(oracle, b, x, q_rows=False, temperature=0.7, draft_temperature=1.3)
-    compare(ref, got, 0.8)
+    compare(ref, got)
 
 
 def test_identical_distributions_and_point_mass(oracle):
@@ -113,7 +125,7 @@ def test_identical_distributions_and_point_mass(oracle):
     x = synth.sampled_draft_inputs(rng, par, V, T, std=2.0, shared_rows=True)
     x["draft_logits"] = x["target_logits"].copy()
     ref, got = run_both(oracle, b, x)
-    compare(ref, got, 0.9)
+    compare(ref, got)
     assert got[0].min() >= 1                                   # the first child is always accepted
     y = dict(x)
     y["draft_logits"] = np.zeros_like(x["target_logits"])
@@ -122,16 +134,17 @@ def test_identical_distributions_and_point_mass(oracle):
     for i in range(B):
         for c in range(1, T):
             y["target_logits"][i, x["parents"][i, c], x["draft_tokens"][i, c]] += 3.0
+    y["uniforms"] = tie_free_uniforms(
+        lambda u: (oracle.accept_margins(y["target_logits"], y["draft_tokens"], y["parents"], y["n_nodes"], u) > 1e-6).all(axis=1),
+        x["uniforms"], rng)
     got_q = b.radar_verify_accept_q(dev(y["target_logits"]), dev(y["draft_logits"]), dev(y["draft_tokens"]), dev(y["parents"]),
                                     dev(y["n_nodes"]), dev(y["uniforms"]))
     got_p = b.radar_verify_accept(dev(y["target_logits"]), dev(y["draft_tokens"]), dev(y["parents"]), dev(y["n_nodes"]),
                                   dev(y["uniforms"]), mode=b.RADAR_ACCEPT_SAMPLE)
     torch.cuda.synchronize()
-    m = oracle.accept_margins(y["target_logits"], y["draft_tokens"], y["parents"], y["n_nodes"], y["uniforms"])
-    sure = (m > 1e-6).all(axis=1)
-    assert sure.mean() > 0.8
-    for p, q in zip(got_p, got_q):
-        assert np.array_equal(host(p)[sure], host(q)[sure])
+    ref_p = oracle.verify_accept(y["target_logits"], y["draft_tokens"], y["parents"], y["n_nodes"], y["uniforms"], mode=1)
+    for p, q, r in zip(got_p, got_q, ref_p):
+        assert np.array_equal(host(p), host(q)) and np.array_equal(host(p), r)
 
 
 def test_workspace_reuse_prepared_call_and_errors(oracle):
@@ -142,6 +155,7 @@ def test_workspace_reuse_prepared_call_and_errors(oracle):
     desc = b.accept_q_desc(B, T, T, V, T - 1)
     ws = b.new_workspace(b.radar_verify_accept_q_workspace_bytes(desc))
     for x in xs:                                                 # one workspace, different inputs, twice each
+        x = tie_free(oracle, x)
         ref = oracle.verify_accept_q(x["target_logits"], x["draft_logits"], x["draft_tokens"], x["parents"], x["n_nodes"],
                                      x["uniforms"], x["q_rows"], want_margins=True)
         call = b.radar_verify_accept_q(dev(x["target_logits"]), dev(x["draft_logits"]), dev(x["draft_tokens"]),
@@ -150,7 +164,7 @@ def test_workspace_reuse_prepared_call_and_errors(oracle):
         for _ in range(2):
             call()
             torch.cuda.synchronize()
-            compare(ref, [host(t) for t in call.out], 0.6)
+            compare(ref, [host(t) for t in call.out])
     x = xs[0]
     with pytest.raises(b.RadarError):
         b.radar_verify_accept_q(dev(x["target_logits"]), dev(x["draft_logits"]), dev(x["draft_tokens"]), dev(x["parents"]),

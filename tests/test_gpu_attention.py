@@ -1,8 +1,13 @@
 """GPU parity: radar_tree_attention (through the C ABI) against the CPU oracle.
 
-Tolerance (bf16 inputs, fp32 accumulation, bf16 output; probabilities are rounded to
-bf16 before the P.V contraction): max-abs error <= 2e-2 and relative error (L2 norm
-over the compared block) <= 1e-2, the bounds of the baseline description."""
+Contract (bf16 inputs, fp32 accumulation, bf16 output; probabilities are rounded to bf16 before
+the P.V contraction): max-abs error <= 2e-2 and relative error (L2 norm over the compared block)
+<= 1e-2, the bounds of the baseline description.  The tests hold the kernels to tighter,
+per-element bounds derived from the arithmetic: both sides round the output to bf16 (half an ulp
+each, 2^-8 relative), and the device's bf16 probabilities add at most 2^-9 of the largest value
+in the row's average, so |error| <= ABS_TIGHT + REL_TIGHT * |reference| for every element.
+The log-sum-exp output is fp32 on both sides (fp32 score accumulation, hardware exp2 / log2):
+1e-4 absolute."""
 import numpy as np
 import pytest
 import torch
@@ -12,8 +17,11 @@ from gpu_util import bf16_dev, bf16_bits, dev, host
 
 pytestmark = pytest.mark.gpu
 
-MAX_ABS = 2e-2
+MAX_ABS = 2e-2          # the contract
 REL = 1e-2
+ABS_TIGHT = 6e-3        # per element: |err| <= ABS_TIGHT + REL_TIGHT * |ref|
+REL_TIGHT = 8e-3        # one bf16 ulp
+LSE_TOL = 1e-4
 
 
 def f64(bits):
@@ -27,6 +35,8 @@ def check_close(got_bits, ref_bits, what=""):
     rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
     assert err.max() <= MAX_ABS, f"{what}: max abs {err.max():.3e}"
     assert rel <= REL, f"{what}: rel {rel:.3e}"
+    over = err - (ABS_TIGHT + REL_TIGHT * np.abs(ref))
+    assert over.max() <= 0, f"{what}: element error {err.flat[over.argmax()]:.3e} at |ref| {abs(ref.flat[over.argmax()]):.3e}"
     return err.max(), rel
 
 
@@ -70,7 +80,7 @@ def test_small_cases_match_oracle(oracle, name, kps):
     for bb in range(a.B):
         n = a.n_nodes[bb]
         check_close(got[bb, :n], ref[bb, :n], f"{name} b={bb}")
-        assert np.max(np.abs(lse[bb, :n] - ref_lse[bb, :n])) < 2e-2
+        assert np.max(np.abs(lse[bb, :n] - ref_lse[bb, :n])) < LSE_TOL
         assert np.all(got[bb, n:] == 0) and np.all(lse[bb, n:] == 0)     # unused rows are zeroed
 
 
@@ -96,7 +106,7 @@ def test_long_ranges_match_oracle(oracle, name, kps):
     for bb in range(a.B):
         n = a.n_nodes[bb]
         check_close(got[bb, :n], ref[bb, :n], f"{name} b={bb} kps={kps}")
-        assert np.max(np.abs(lse[bb, :n] - ref_lse[bb, :n])) < 2e-2
+        assert np.max(np.abs(lse[bb, :n] - ref_lse[bb, :n])) < LSE_TOL
         assert np.all(got[bb, n:] == 0) and np.all(lse[bb, n:] == 0)
 
 
@@ -153,20 +163,19 @@ def test_strided_views_and_scale(oracle):
     check_close(bf16_bits(out), ref, "strided")
 
 
-def sampled_heads_check(oracle, b, a, seed, pairs, kps=0):
-    """Full-size launch; the oracle recomputes whole (sequence, query head) slices."""
+def whole_config_check(oracle, b, a, seed):
+    """Full-size launch in the default plan; every output element and every log-sum-exp compared."""
     x = synth.attention_inputs(a, seed=seed)
-    got = run_gpu(b, x, keys_per_split=kps)
-    G = a.Hq // a.Hkv
+    got, lse = run_gpu(b, x, want_lse=True)
+    ref, ref_lse = oracle.tree_attention(x["q"], x["k_cache"], x["v_cache"], x["parents"], x["ctx_lens"], x["n_nodes"],
+                                         want_lse=True)
     worst = (0.0, 0.0)
-    for (bb, h) in pairs:
-        sub = oracle.tree_attention(x["q"][bb:bb + 1, :, h:h + 1], x["k_cache"][bb:bb + 1, h // G:h // G + 1],
-                                    x["v_cache"][bb:bb + 1, h // G:h // G + 1], x["parents"][bb:bb + 1],
-                                    x["ctx_lens"][bb:bb + 1], x["n_nodes"][bb:bb + 1])
+    for bb in range(a.B):
         n = a.n_nodes[bb]
-        e = check_close(got[bb, :n, h], sub[0, :n, 0], f"b={bb} h={h}")
+        e = check_close(got[bb, :n], ref[bb, :n], f"b={bb}")
         worst = (max(worst[0], e[0]), max(worst[1], e[1]))
-        assert np.all(got[bb, n:, h] == 0)
+        assert np.max(np.abs(lse[bb, :n] - ref_lse[bb, :n])) < LSE_TOL
+        assert np.all(got[bb, n:] == 0) and np.all(lse[bb, n:] == 0)
     return worst
 
 
@@ -175,29 +184,27 @@ def test_config2_full(oracle):
     from paper_2512_14069_amd import binding as b
     a = synth.config(2).attn
     x = synth.attention_inputs(a, seed=synth.seed_for(2))
-    ref = oracle.tree_attention(x["q"], x["k_cache"], x["v_cache"], x["parents"], x["ctx_lens"], x["n_nodes"])
-    got = run_gpu(b, x)
+    ref, ref_lse = oracle.tree_attention(x["q"], x["k_cache"], x["v_cache"], x["parents"], x["ctx_lens"], x["n_nodes"],
+                                         want_lse=True)
+    got, lse = run_gpu(b, x, want_lse=True)
     check_close(got, ref, "config 2")
+    assert np.max(np.abs(lse - ref_lse)) < LSE_TOL
     again = run_gpu(b, x)
     assert np.array_equal(got, again)            # bit-reproducible
     for kps in (64, 256, 512, 1024, 4096):
         check_close(run_gpu(b, x, keys_per_split=kps), ref, f"config 2 kps {kps}")
 
 
-def test_config4_ragged_sampled(oracle):
+def test_config4_ragged_whole(oracle):
+    """Ragged dynamic-depth batch, 16 sequences: every output compared."""
     from paper_2512_14069_amd import binding as b
-    a = synth.config(4).attn
-    rng = np.random.default_rng(1)
-    pairs = [(bb, int(rng.integers(0, a.Hq))) for bb in range(a.B)]
-    sampled_heads_check(oracle, b, a, synth.seed_for(4), pairs)
+    whole_config_check(oracle, b, synth.config(4).attn, synth.seed_for(4))
 
 
-def test_config5_sampled(oracle):
+def test_config5_whole(oracle):
+    """70B-class verify layer (4 x 16384 context, 64 / 8 heads): every output compared."""
     from paper_2512_14069_amd import binding as b
-    a = synth.config(5).attn
-    rng = np.random.default_rng(2)
-    pairs = [(int(rng.integers(0, a.B)), int(rng.integers(0, a.Hq))) for _ in range(6)]
-    sampled_heads_check(oracle, b, a, synth.seed_for(5), pairs)
+    whole_config_check(oracle, b, synth.config(5).attn, synth.seed_for(5))
 
 
 def test_bad_descriptors_are_rejected():
