@@ -172,6 +172,28 @@ radar_status radar_draft_expand(const float *logits, const float *parent_scores,
                                 const radar_expand_desc *desc,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
+/* radar_draft_expand for callers that cannot allocate or hand over a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels with
+ * their scratch memory in a device array that this library holds itself,
+ * RADAR_NOALLOC_SCRATCH_BYTES on every GPU it runs on, until the process ends.  Inputs and
+ * outputs are the caller's, exactly as for radar_draft_expand; there is no workspace argument
+ * and nothing is allocated or freed, by this call or by anything it calls.
+ * Limits: those of radar_draft_expand, and radar_draft_expand_workspace_bytes(desc) <=
+ * RADAR_NOALLOC_SCRATCH_BYTES (F = 10, V = 128256 needs 0.06 MB; about F * V <= 25 M logits
+ * fit), else RADAR_UNSUPPORTED_SHAPE and nothing is launched.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two threads) race and give unspecified results; calls that follow each other on one
+ * stream, or are ordered by events, are fine, whatever their shapes.  The stream must belong to
+ * the current device.  The first call on a device looks the array up and enqueues one extra
+ * fill kernel that clears it; make that call outside a graph capture. */
+#define RADAR_NOALLOC_SCRATCH_BYTES (1u << 20)
+radar_status radar_draft_expand_noalloc(const float *logits, const float *parent_scores, const int32_t *parent_pool_idx,
+                                        int32_t *cand_tokens, float *cand_scores,
+                                        int32_t *frontier_pool_idx, int32_t *frontier_tokens,
+                                        float *frontier_scores, float *frontier_conf,
+                                        int32_t *pool_tokens, float *pool_scores, int32_t *pool_parents,
+                                        const radar_expand_desc *desc, void *stream);
+
 /* --------------------------------------------------------------------------
  * Rerank, once per cycle (Sec. 1 / Sec. 2.3: the dynamic tree is reordered
  * and pruned by confidence).

@@ -72,7 +72,7 @@ class PolicyIO(ctypes.Structure):
 EXPORTS = [
     "radar_status_string", "radar_version", "radar_workspace_init",
     "radar_tree_attention_workspace_bytes", "radar_tree_attention",
-    "radar_draft_expand_workspace_bytes", "radar_draft_expand", "radar_draft_expand_policy",
+    "radar_draft_expand_workspace_bytes", "radar_draft_expand", "radar_draft_expand_noalloc", "radar_draft_expand_policy",
     "radar_draft_rerank_workspace_bytes", "radar_draft_rerank",
     "radar_cycle_begin", "radar_draft_expand_cycle", "radar_draft_rerank_cycle",
     "radar_draft_expand_batch_workspace_bytes", "radar_draft_expand_batch", "radar_draft_rerank_batch",
@@ -106,6 +106,8 @@ def load():
     lib.radar_draft_expand_workspace_bytes.argtypes = [ctypes.POINTER(ExpandDesc)]
     lib.radar_draft_expand.restype = i32
     lib.radar_draft_expand.argtypes = [vp] * 12 + [ctypes.POINTER(ExpandDesc), vp, sz, vp]
+    lib.radar_draft_expand_noalloc.restype = i32
+    lib.radar_draft_expand_noalloc.argtypes = [vp] * 12 + [ctypes.POINTER(ExpandDesc), vp]
     lib.radar_draft_expand_policy.restype = i32
     lib.radar_draft_expand_policy.argtypes = [vp] * 12 + [ctypes.POINTER(ExpandDesc), ctypes.POINTER(PolicyParams),
                                               ctypes.POINTER(PolicyIO), vp, sz, vp]
@@ -325,6 +327,32 @@ def radar_draft_expand(logits, parent_scores, parent_pool_idx, k, pool, out=None
     keep = (logits, parent_scores, parent_pool_idx, out, pool, desc, workspace)
     pool.count += F * k
     return _finish("radar_draft_expand", load().radar_draft_expand, args, keep, out, prepared)
+
+
+RADAR_NOALLOC_SCRATCH_BYTES = 1 << 20
+
+
+def radar_draft_expand_noalloc(logits, parent_scores, parent_pool_idx, k, pool, out=None, prepared=False):
+    """radar_draft_expand without a workspace: the library's own device array serves as scratch
+    (shapes whose workspace exceeds RADAR_NOALLOC_SCRATCH_BYTES are refused).  `out` is allocated
+    here when not given; the library call itself allocates nothing."""
+    F, V = logits.shape
+    desc = expand_desc(F, V, k, pool.count, pool.capacity)
+    if out is None:
+        out = ExpandOut(F, k, logits.device)
+    args = (
+        _ptr(_dense(logits, "logits"), torch.float32, "logits"),
+        _ptr(_dense(parent_scores, "parent_scores"), torch.float32, "parent_scores"),
+        _ptr(_dense(parent_pool_idx, "parent_pool_idx"), torch.int32, "parent_pool_idx"),
+        _ptr(out.cand_tokens, torch.int32), _ptr(out.cand_scores, torch.float32),
+        _ptr(out.frontier_pool_idx, torch.int32), _ptr(out.frontier_tokens, torch.int32),
+        _ptr(out.frontier_scores, torch.float32), _ptr(out.frontier_conf, torch.float32),
+        _ptr(pool.tokens, torch.int32), _ptr(pool.scores, torch.float32), _ptr(pool.parents, torch.int32),
+        ctypes.byref(desc), _stream())
+    keep = (logits, parent_scores, parent_pool_idx, out, pool, desc)
+    call = _finish("radar_draft_expand_noalloc", load().radar_draft_expand_noalloc, args, keep, out, prepared)
+    pool.count += F * k
+    return call
 
 
 def radar_draft_expand_policy(logits, parent_scores, parent_pool_idx, k, pool, params, h=None, c=None, uniform=None,

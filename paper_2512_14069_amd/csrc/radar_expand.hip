@@ -15,6 +15,7 @@
 // radar_draft_expand_batch adds a grid dimension: one such call per sequence,
 // B sequences in one launch, each with its own arrays, tickets and last workgroup.
 #include <algorithm>
+#include <mutex>
 
 #include "radar_topk.h"
 #include "radar_policy.h"
@@ -706,7 +707,7 @@ static radar_status launch_expand(const float *logits, const float *parent_score
                                   float *frontier_scores, float *frontier_conf, int32_t *pool_tokens,
                                   float *pool_scores, int32_t *pool_parents, const radar_expand_desc *d,
                                   const PolicyArgs *pol, radar_cycle_state *cycle, int B, void *workspace,
-                                  size_t workspace_bytes, void *stream_) {
+                                  size_t workspace_bytes, void *stream_, bool check_only = false) {
     if (!d || !logits || !parent_scores || !parent_pool_idx || !cand_tokens || !cand_scores || !frontier_pool_idx ||
         !frontier_tokens || !frontier_scores || !frontier_conf || !pool_tokens || !pool_scores || !pool_parents ||
         !workspace)
@@ -725,6 +726,7 @@ static radar_status launch_expand(const float *logits, const float *parent_score
     if (d->F > RADAR_F_MAX || d->k > RADAR_K_MAX || nchunks > kExpMaxChunks) return RADAR_UNSUPPORTED_SHAPE;
     if (workspace_bytes < expand_workspace_bytes(d, (size_t)B)) return RADAR_WORKSPACE_TOO_SMALL;
     if (((uintptr_t)workspace & 255) != 0) return RADAR_INVALID_ARG;
+    if (check_only) return RADAR_OK;                               // every argument is acceptable; nothing launched
 
     ExpandArgs a;
     a.logits = logits; a.parent_scores = parent_scores; a.parent_pool_idx = parent_pool_idx;
@@ -779,6 +781,68 @@ extern "C" radar_status radar_draft_expand(const float *logits, const float *par
     return launch_expand(logits, parent_scores, parent_pool_idx, cand_tokens, cand_scores, frontier_pool_idx,
                          frontier_tokens, frontier_scores, frontier_conf, pool_tokens, pool_scores, pool_parents, d,
                          nullptr, nullptr, 1, workspace, workspace_bytes, stream);
+}
+
+// ------------------------------------------------------------------ the entry point that allocates nothing
+// For callers that cannot call hipMalloc (code under HIP graph capture, tight serving loops,
+// harnesses that forbid it): radar_draft_expand with its workspace in a device array of this
+// library instead of a caller-owned buffer.  The array lives in every GPU the library runs on
+// until the process ends; its device address is looked up once per device.
+static __device__ __align__(256) unsigned char scratch[RADAR_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kScratchMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kScratchMaxDevices];      // device address of `scratch` on each device; null until looked up
+
+__global__ void scratch_clear_kernel(uint4 *p, size_t n16) {
+    const uint4 z = make_uint4(0u, 0u, 0u, 0u);
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) p[i] = z;
+}
+
+// The current device's copy of `scratch` (in host code the array's name is only a handle for the
+// lookup, never an address).  The first call on a device also clears the array on `stream`: the
+// arrival counters at its head must start at zero, and every call leaves them at zero.
+radar_status static_scratch(hipStream_t stream, void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return RADAR_HIP_ERROR;
+    if (dev < 0 || dev >= kScratchMaxDevices) return RADAR_UNSUPPORTED_SHAPE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return RADAR_HIP_ERROR;
+        if (((uintptr_t)ptr & 255) != 0) return RADAR_HIP_ERROR;
+        hipLaunchKernelGGL(scratch_clear_kernel, dim3(64), dim3(256), 0, stream, static_cast<uint4 *>(ptr),
+                           (size_t)RADAR_NOALLOC_SCRATCH_BYTES / 16);
+        if (hipGetLastError() != hipSuccess) return RADAR_HIP_ERROR;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return RADAR_OK;
+}
+}  // namespace
+
+extern "C" radar_status radar_draft_expand_noalloc(const float *logits, const float *parent_scores,
+                                                   const int32_t *parent_pool_idx, int32_t *cand_tokens,
+                                                   float *cand_scores, int32_t *frontier_pool_idx,
+                                                   int32_t *frontier_tokens, float *frontier_scores,
+                                                   float *frontier_conf, int32_t *pool_tokens, float *pool_scores,
+                                                   int32_t *pool_parents, const radar_expand_desc *d, void *stream) {
+    if (!d || d->F < 1 || d->V < 1) return RADAR_INVALID_ARG;
+    const size_t need = expand_workspace_bytes(d, 1);
+    if (need == 0 || need > (size_t)RADAR_NOALLOC_SCRATCH_BYTES) return RADAR_UNSUPPORTED_SHAPE;   // F * V beyond the array
+    // arguments first (against a stand-in for the array's address), so that an error launches nothing
+    radar_status st = launch_expand(logits, parent_scores, parent_pool_idx, cand_tokens, cand_scores, frontier_pool_idx,
+                                    frontier_tokens, frontier_scores, frontier_conf, pool_tokens, pool_scores,
+                                    pool_parents, d, nullptr, nullptr, 1, reinterpret_cast<void *>(uintptr_t(256)),
+                                    (size_t)RADAR_NOALLOC_SCRATCH_BYTES, stream, true);
+    if (st != RADAR_OK) return st;
+    void *ws = nullptr;
+    st = static_scratch(static_cast<hipStream_t>(stream), &ws);
+    if (st != RADAR_OK) return st;
+    return launch_expand(logits, parent_scores, parent_pool_idx, cand_tokens, cand_scores, frontier_pool_idx,
+                         frontier_tokens, frontier_scores, frontier_conf, pool_tokens, pool_scores, pool_parents, d,
+                         nullptr, nullptr, 1, ws, (size_t)RADAR_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 extern "C" radar_status radar_draft_expand_policy(const float *logits, const float *parent_scores,
