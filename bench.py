@@ -10,12 +10,15 @@ step uses the next of several input sets whose total size exceeds L2 + Infinity 
 so the kernels read from HBM, not from cache.
 
 Prints one JSON line.  `value` is the attention call's achieved HBM bandwidth:
-algorithmic bytes / mean time between stream events placed around the call in the
-timed region, less the cost of an empty pair of events.  `roofline` is the same
-bytes over the attention kernel's own mean device duration, taken from HIP events
-that the library attaches to each launch (dispatch begin to end, as in a kernel
-trace) in a second pass over the same steps; `kernels` lists every kernel of the
-step that way.  The expand+accept time per cycle is reported next to it.
+algorithmic bytes / the summed mean device durations of the kernels the call launches
+(dispatch begin to end, as in a kernel trace), taken from HIP events that the library
+attaches to each launch in a second pass over the same steps.  Nothing is subtracted
+anywhere: the phase times between stream events in the timed pass are reported as
+measured (`*_window_us`; they include the events' own cost, given as
+`event_pair_overhead_us`).  `roofline` prices the attention kernel, `roofline_dominant`
+the kernel that takes most of the step, `kernels` lists every kernel of the step, each
+also against `hbm_read_floor_us`: what a plain streaming read of the same number of
+bytes takes on this machine (cold buffers, same kind of timing).
 """
 import argparse
 import json
@@ -51,16 +54,19 @@ def parse():
 
 
 def read_traffic():
-    """HBM bytes per launch of the first attention kernel, measured offline with rocprofv3 --pmc
-    (FETCH_SIZE and WRITE_SIZE scaled by a copy of known size; see the file for the commands)."""
+    """HBM bytes per launch of the attention kernel, measured offline with rocprofv3 --pmc (FETCH_SIZE and
+    WRITE_SIZE scaled by a copy of known size; the file gives the commands and the commit it was taken at)."""
     path = os.path.join(ROOT, "profiles", "tree_attention_c2_traffic.txt")
+    out = {}
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch"):
-                return float(line.split("=")[1])
+                out["traffic_bytes_per_launch"] = float(line.split("=")[1])
+            if line.startswith("taken_at_commit"):
+                out["source"] = "profiles/tree_attention_c2_traffic.txt at " + line.split("=")[1].strip()
     except OSError:
         pass
-    return None
+    return out
 
 
 def main():
@@ -245,42 +251,86 @@ def main():
     torch.cuda.synchronize()
     copy_gbps = 5 * 2.0 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9
     del csrc, cdst
-    for m in null_marks:                       # cost of an empty pair of marks, taken off each phase
+    for m in null_marks:                       # cost of an empty pair of marks (reported, never subtracted)
         m[0].record(); m[1].record()
     torch.cuda.synchronize()
     null_us = float(np.mean([m[0].elapsed_time(m[1]) for m in null_marks]) * 1e3)
 
+    # What a plain streaming read of n bytes takes here: the library's read probe (16-byte loads, nothing
+    # kept) on cold data -- consecutive launches walk through a 1.5 GiB buffer, so no launch finds its bytes
+    # in L2 or in the memory-side cache -- timed like the kernels above (dispatch begin to end).
+    ea_bytes = expand_bytes * steps_per_cycle + accept_bytes
+    floor_sizes = {"expand": expand_bytes, "attention": attn_bytes, "accept": accept_bytes,
+                   "expand_accept_cycle": ea_bytes, "kv_269MB": 269 << 20}
+    floor_us = {}
+    if not args.no_kernel_events:
+        big = torch.empty(1536 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        for name, nbytes in floor_sizes.items():
+            nb = (nbytes + 255) // 256 * 256
+            slots = big.numel() // nb
+            reps = 10 if nb > (100 << 20) else 40
+            calls = [b.radar_probe_hbm_read(big, nb, (j % slots) * nb, prepared=True) for j in range(reps + 4)]
+            for c in calls[:4]:
+                c()
+            torch.cuda.synchronize()
+            b.radar_profile_begin(reps)
+            for c in calls[4:]:
+                c()
+            torch.cuda.synchronize()
+            floor_us[name] = b.radar_profile_end()["hbm_read_probe"]["mean_us"]
+        del big
+
     if args.no_marks:
-        attn_us = exp_us = acc_us = np.zeros(K) + null_us
+        attn_us = exp_us = acc_us = np.zeros(K)
     else:
         attn_us = np.array([m[0].elapsed_time(m[1]) for m in marks]) * 1e3
         exp_us = np.array([m[1].elapsed_time(m[2]) for m in marks]) * 1e3
         acc_us = np.array([m[2].elapsed_time(m[3]) for m in marks]) * 1e3
-    a_us, e_us, c_us = (max(0.0, float(x.mean()) - null_us) for x in (attn_us, exp_us, acc_us))
-    attn_gbps = attn_bytes / (a_us * 1e-6) / 1e9 if a_us > 0 else 0.0
-    ea_bytes = expand_bytes * steps_per_cycle + accept_bytes
-    ea_us = e_us + c_us
-    ea_gbps = ea_bytes / (ea_us * 1e-6) / 1e9 if ea_us > 0 else 0.0
+    a_win, e_win, c_win = (float(x.mean()) for x in (attn_us, exp_us, acc_us))
 
-    # roofline entries: algorithmic bytes of one launch / that kernel's mean device duration
-    alg_bytes = {"tree_attn_group_share": attn_bytes,
-                 "expand": expand_bytes, "accept": accept_bytes}
+    # per-kernel entries: algorithmic bytes of one launch / that kernel's mean device duration
+    alg_bytes = {"tree_attn": attn_bytes, "tree_attn_group_share": attn_bytes, "expand": expand_bytes, "accept": accept_bytes}
+    floor_of = {"tree_attn": "attention", "tree_attn_group_share": "attention", "expand": "expand", "accept": "accept"}
     kernels = []
     for name, t in sorted(kern.items(), key=lambda kv: -kv[1]["total_us"]):
         ent = {"kernel": name, "calls_per_step": round(t["calls"] / K, 2), "mean_us": round(t["mean_us"], 2),
-               "min_us": round(t["min_us"], 2), "max_us": round(t["max_us"], 2)}
+               "min_us": round(t["min_us"], 2), "max_us": round(t["max_us"], 2),
+               "us_per_step": round(t["total_us"] / K, 2)}
         if name in alg_bytes:
             g = alg_bytes[name] / (t["mean_us"] * 1e-6) / 1e9
             ent.update(bound="hbm", algorithmic_bytes=alg_bytes[name], achieved=round(g, 1), unit="GB/s",
                        frac=round(g / PEAK_HBM_GBPS, 4))
+            if floor_of[name] in floor_us:
+                ent.update(read_floor_us=round(floor_us[floor_of[name]], 2),
+                           frac_of_read_floor=round(floor_us[floor_of[name]] / t["mean_us"], 4))
         kernels.append(ent)
-    attn_kernel = next((e for e in kernels if e["kernel"].startswith("tree_attn_") and "achieved" in e), None)
-    roof = {"kernel": None, "bound": "hbm", "achieved": 0.0, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": 0.0,
-            "traffic": None,
-            "measured": "second pass over the same steps with events attached to each launch (kernel-trace time)"}
+
+    def per_step(prefixes):
+        return sum(t["total_us"] for n, t in kern.items() if n.startswith(prefixes)) / K if kern else 0.0
+    # time of the calls from the kernels' own durations (what the launches occupy the device for)
+    a_us = per_step(("tree_attn",))
+    e_us = per_step(("expand", "rerank", "policy"))
+    c_us = per_step(("accept",))
+    if not kern:                                # no per-kernel events: the windows are all there is
+        a_us, e_us, c_us = a_win, e_win, c_win
+    attn_gbps = attn_bytes / (a_us * 1e-6) / 1e9 if a_us > 0 else 0.0
+    ea_us = e_us + c_us
+    ea_gbps = ea_bytes / (ea_us * 1e-6) / 1e9 if ea_us > 0 else 0.0
+
+    def roofline_of(ent, **extra):
+        r = {"kernel": ent["kernel"], "bound": "hbm", "achieved": ent["achieved"], "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+             "frac": ent["frac"], "traffic": None, "kernel_us": ent["mean_us"], "algorithmic_bytes": ent["algorithmic_bytes"],
+             "measured": "second pass over the same steps with events attached to each launch (kernel-trace time)"}
+        r.update(extra)
+        return r
+    attn_kernel = next((e for e in kernels if e["kernel"].startswith("tree_attn") and "achieved" in e), None)
+    roof = {"kernel": None, "bound": "hbm", "achieved": 0.0, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": 0.0, "traffic": None}
     if attn_kernel:
-        roof.update(kernel=attn_kernel["kernel"], achieved=attn_kernel["achieved"], frac=attn_kernel["frac"],
-                    kernel_us=attn_kernel["mean_us"], algorithmic_bytes=attn_bytes, traffic=read_traffic())
+        tr = read_traffic()
+        roof = roofline_of(attn_kernel, traffic=tr.get("traffic_bytes_per_launch"), traffic_source=tr.get("source"),
+                           call_us=round(a_us, 2), call_frac=round(attn_gbps / PEAK_HBM_GBPS, 4))
+    with_bytes = [e for e in kernels if "achieved" in e]
+    dominant = max(with_bytes, key=lambda e: e["us_per_step"]) if with_bytes else None
 
     result = {
         "metric": METRIC,
@@ -303,21 +353,28 @@ def main():
                    "cache": "%s: inputs rotate through %d MB (attention) / %d MB (logits)" % (
                        "cold" if min(attn_bytes * len(attn_sets), ea_bytes * len(cycle_sets)) > 512 * 2**20 else "warm",
                        attn_bytes * len(attn_sets) // 2**20, ea_bytes * len(cycle_sets) // 2**20)},
+        "value_is": "attention algorithmic bytes / summed device durations of the attention call's kernels",
         "attention_us": round(a_us, 2),
         "attention_pct_peak_hbm": round(100 * attn_gbps / PEAK_HBM_GBPS, 2),
         "hbm_copy_gbps_measured": round(copy_gbps, 1),
         "attention_pct_of_measured_copy": round(100 * attn_gbps / copy_gbps, 2),
         "attention_tflops": round(4.0 * A.Hq * A.T * kv_rows * A.D / (a_us * 1e-6) / 1e12, 1) if a_us > 0 else 0.0,
         "expand_chain_us": round(e_us, 2),
-        "expand_us_per_call": round(e_us / steps_per_cycle, 2),
+        "expand_us_per_call": round(per_step(("expand",)) / steps_per_cycle, 2),
         "accept_us": round(c_us, 2),
         "expand_accept_us_per_step": round(ea_us, 2),
         "expand_accept_gbps": round(ea_gbps, 1),
         "expand_accept_pct_peak_hbm": round(100 * ea_gbps / PEAK_HBM_GBPS, 2),
-        "phase_us_p10_p50_p90": {name: [round(float(np.percentile(x, q)) - null_us, 2) for q in (10, 50, 90)]
-                                 for name, x in (("attention", attn_us), ("expand_chain", exp_us), ("accept", acc_us))},
+        # the same phases between stream events in the timed pass, as measured (event cost included)
+        "attention_window_us": round(a_win, 2), "expand_chain_window_us": round(e_win, 2), "accept_window_us": round(c_win, 2),
+        "attention_window_gbps": round(attn_bytes / (a_win * 1e-6) / 1e9, 1) if a_win > 0 else 0.0,
+        "phase_window_us_p10_p50_p90": {name: [round(float(np.percentile(x, q)), 2) for q in (10, 50, 90)]
+                                        for name, x in (("attention", attn_us), ("expand_chain", exp_us), ("accept", acc_us))},
         "event_pair_overhead_us": round(null_us, 2),
+        "hbm_read_floor_us": {n: round(v, 2) for n, v in floor_us.items()},
+        "hbm_read_floor_bytes": floor_sizes,
         "roofline": roof,
+        "roofline_dominant": roofline_of(dominant, us_per_step=dominant["us_per_step"]) if dominant else None,
         "kernels": kernels,
     }
 

@@ -517,7 +517,10 @@ radar_status radar_debug_validate_tree(const int32_t *parents, const int32_t *n_
  * the recorded kernels, writes one entry per kernel name into out[0..capacity)
  * (HOST memory; names beyond capacity are dropped), stores the number of
  * entries in *n_out and destroys the events.  These two calls are the only
- * ones that create or destroy anything and that synchronise. */
+ * ones that create or destroy anything and that synchronise.  Neither may
+ * run while another thread is inside a call of this library: a launch that
+ * has taken its event pair must have been issued before radar_profile_end
+ * destroys the events. */
 typedef struct radar_kernel_time {
     char name[48];      /* "expand", "expand_stream", "expand_finish", "rerank", "accept",
                            "accept_length_distribution", "tree_attn_group_share",
@@ -530,6 +533,14 @@ typedef struct radar_kernel_time {
 
 radar_status radar_profile_begin(int32_t max_launches);
 radar_status radar_profile_end(radar_kernel_time *out, int32_t capacity, int32_t *n_out);
+
+/* Measurement support: reads `bytes` (a multiple of 16 is read; src 16-byte aligned, DEVICE
+ * memory) once with 16-byte loads from every CU and keeps nothing -- the time a pure streaming
+ * read of that size takes on this chip, against which the streaming kernels above (logits
+ * passes, KV passes) are priced besides the nominal peak.  sink: DEVICE u32 or NULL, written
+ * practically never (it only keeps the loads alive).  One kernel ("hbm_read_probe" in the
+ * timing table); enqueues and returns. */
+radar_status radar_probe_hbm_read(const void *src, size_t bytes, uint32_t *sink, void *stream);
 
 #ifdef __cplusplus
 }

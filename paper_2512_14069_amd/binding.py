@@ -79,7 +79,7 @@ EXPORTS = [
     "radar_verify_accept_workspace_bytes", "radar_verify_accept",
     "radar_accept_length_distribution", "radar_policy_step",
     "radar_verify_accept_q_workspace_bytes", "radar_verify_accept_q",
-    "radar_debug_validate_tree", "radar_profile_begin", "radar_profile_end",
+    "radar_debug_validate_tree", "radar_profile_begin", "radar_profile_end", "radar_probe_hbm_read",
 ]
 
 
@@ -143,6 +143,8 @@ def load():
     lib.radar_policy_step.argtypes = [vp] * 3 + [ctypes.POINTER(PolicyParams)] + [vp] * 6 + [i32, vp]
     lib.radar_debug_validate_tree.restype = i32
     lib.radar_debug_validate_tree.argtypes = [vp, vp, i32, i32, vp, vp]
+    lib.radar_probe_hbm_read.restype = i32
+    lib.radar_probe_hbm_read.argtypes = [vp, sz, vp, vp]
     lib.radar_profile_begin.restype = i32
     lib.radar_profile_begin.argtypes = [i32]
     lib.radar_profile_end.restype = i32
@@ -752,6 +754,15 @@ def radar_debug_validate_tree(parents, n_nodes=None):
         _ptr(_dense(parents, "parents"), torch.int32), _ptr(n_nodes, torch.int32), B, T, _ptr(bad), _stream())
     _check(rc, "radar_debug_validate_tree")
     return bad
+
+
+def radar_probe_hbm_read(buf, nbytes=None, offset=0, prepared=False):
+    """One streaming read of nbytes of the uint8 device tensor `buf`, starting at byte `offset`."""
+    nbytes = buf.numel() * buf.element_size() - offset if nbytes is None else int(nbytes)
+    if offset % 16 or offset + nbytes > buf.numel() * buf.element_size():
+        raise ValueError("offset / size outside the buffer or not 16-byte aligned")
+    args = (ctypes.c_void_p(buf.data_ptr() + offset), ctypes.c_size_t(nbytes), None, _stream())
+    return _finish("radar_probe_hbm_read", load().radar_probe_hbm_read, args, (buf,), None, prepared)
 
 
 def radar_profile_begin(max_launches):

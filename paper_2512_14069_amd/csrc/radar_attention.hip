@@ -587,13 +587,11 @@ constexpr int gs_smem_bytes() { return 2 * (2 * kKT * D * 2) + RADAR_T_MAX * 4; 
 
 template <int D, bool DEEP>
 static hipError_t launch_gs(const AttnArgs &a, dim3 grid, hipStream_t s) {
-    static bool configured = false;                        // raise the dynamic LDS limit once per instantiation
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_gs_kernel<D, DEEP>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, gs_smem_bytes<D>());
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    // the dynamic LDS limit is raised once per instantiation (a function-local static is initialised
+    // exactly once, also when several threads launch at the same time)
+    static const hipError_t configured = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_gs_kernel<D, DEEP>),
+                                                             hipFuncAttributeMaxDynamicSharedMemorySize, gs_smem_bytes<D>());
+    if (configured != hipSuccess) return configured;
     return launch("tree_attn_group_share", tree_attn_gs_kernel<D, DEEP>, grid, dim3(kGsThreads), gs_smem_bytes<D>(), s, a);
 }
 

@@ -15,6 +15,23 @@ __global__ void zero_fill_kernel(uint4 *p, size_t n16) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) p[i] = z;
 }
 
+// Reads n16 x 16 bytes once, four independent loads per lane in flight, and keeps nothing: what a
+// pure streaming read costs on this chip, the floor every streaming kernel here is compared with.
+__global__ __launch_bounds__(256) void hbm_read_probe_kernel(const uint4 *p, size_t n16, uint32_t *sink) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint32_t acc = 0;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
+        acc ^= (a.x ^ a.y ^ a.z ^ a.w) ^ (b.x ^ b.y ^ b.z ^ b.w) ^ (c.x ^ c.y ^ c.z ^ c.w) ^ (d.x ^ d.y ^ d.z ^ d.w);
+    }
+    for (; i < n16; i += stride) {
+        const uint4 a = p[i];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w;
+    }
+    if (acc == 0x9e3779b9u && sink) *sink = acc;          // keeps the loads alive; practically never taken
+}
+
 namespace {
 struct ProfRecord { const char *name; hipEvent_t start, stop; };
 std::mutex g_prof_mutex;
@@ -54,6 +71,17 @@ extern "C" radar_status radar_workspace_init(void *workspace, size_t bytes, void
     const unsigned blocks = (unsigned)((n16 + 255) / 256 > 1024 ? 1024 : (n16 + 255) / 256);
     const hipError_t e = launch("zero_fill", zero_fill_kernel, dim3(blocks), dim3(256), 0,
                                 static_cast<hipStream_t>(stream), static_cast<uint4 *>(workspace), n16);
+    return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
+}
+
+extern "C" radar_status radar_probe_hbm_read(const void *src, size_t bytes, uint32_t *sink, void *stream) {
+    if (!src || bytes < 16 || ((uintptr_t)src & 15) != 0) return RADAR_INVALID_ARG;
+    const size_t n16 = bytes / 16;
+    // one 16-byte load per lane and pass; at most eight workgroups of 256 lanes per CU's worth of grid
+    const size_t want = (n16 + 4 * 256 - 1) / (4 * 256);
+    const unsigned blocks = (unsigned)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
+    const hipError_t e = launch("hbm_read_probe", hbm_read_probe_kernel, dim3(blocks), dim3(256), 0,
+                                static_cast<hipStream_t>(stream), static_cast<const uint4 *>(src), n16, sink);
     return e == hipSuccess ? RADAR_OK : RADAR_HIP_ERROR;
 }
 
