@@ -31,6 +31,8 @@ constexpr int kCounterStride = 32;                    // arrival counters sit 12
                                                       // cache line serialise at roughly 10 ns each
 constexpr size_t kCounterBytes = 16384;               // leading counter block of the workspace
 constexpr float kLog2eF = 1.4426950408889634f;
+constexpr int kDumpCap = 64;                          // hot lanes (largest logit reaches the threshold) whose logits go through LDS
+constexpr int kFastCap = 512;                         // chunk candidates ranked by the short path; more (runs of equal values) rank per wavefront
 constexpr int64_t kStreamMinLogits = 4 << 20;         // batched calls of at least 16 MB of logits take the streaming path
 
 struct ExpandArgs {
@@ -61,30 +63,19 @@ struct ExpandArgs {
 
 struct alignas(16) ExpandSmem {
     WaveTopkSmem wtk[kExpWaves];                  // one scratch per wavefront
-    uint64_t wlist[kExpWaves * kWaveListSlots];   // the wavefronts' candidates of a chunk (0 = none)
-    float wave_m[kExpWaves];
-    double wave_l[kExpWaves];
+    uint64_t wlist[kExpWaves * kWaveListSlots];   // the wavefronts' candidates of a chunk (0 = none; many ties only)
+    uint64_t ctop[16];                            // the chunk's top-k, best first
+    float gmax[16];                               // maxima of the sixteen 16-lane rows of the streaming wavefronts
+    float wave_l[4];                              // sum of exp(x - chunk maximum) over each streaming wavefront
+    unsigned int nsurv;                           // candidates of the chunk that reached the threshold
+    unsigned int ndump;                           // lanes whose largest logit reached it
+    float tau;                                    // the threshold
+    unsigned short dump_lane[kDumpCap];           // which lane left each block of logits
     // last workgroup only: candidate (row f, rank r) at f * 16 + r
     float cand_sc[RADAR_F_MAX * 16];
     int cand_tok[RADAR_F_MAX * 16];
     unsigned int ticket, ticket2;
 };
-
-// sum over the wavefront entries of l_i * exp(m_i - m): lanes 0..15 of a wavefront take one term
-// each (weights by the fp32 exponential, as the terms themselves were), added in a fixed order.
-// Every lane gets the result.
-__device__ __forceinline__ double combine_waves(const float *wm, const double *wl, float m) {
-    const int lane = lane_id();
-    double t = 0.0;
-    if (lane < kExpWaves && wm[lane] > -INFINITY) t = wl[lane] * (double)__builtin_amdgcn_exp2f((wm[lane] - m) * kLog2eF);
-    // a 16-lane row sum by DPP, fixed association order
-    auto step = [](double x, uint64_t moved) { return x + __longlong_as_double((long long)moved); };
-    t = step(t, dpp_u64<0xB1>((uint64_t)__double_as_longlong(t)));
-    t = step(t, dpp_u64<0x4E>((uint64_t)__double_as_longlong(t)));
-    t = step(t, dpp_u64<0x141>((uint64_t)__double_as_longlong(t)));
-    t = step(t, dpp_u64<0x140>((uint64_t)__double_as_longlong(t)));
-    return __longlong_as_double((long long)readlane_u64((uint64_t)__double_as_longlong(t), 0));
-}
 
 // 512 slots, starting at c0, of one row's chunk lists in the workspace (device-scope loads)
 __device__ __forceinline__ void load_key_block(const uint64_t *pk, int nslot, int c0, int K, uint64_t (&kk)[9]) {
@@ -280,6 +271,7 @@ template <bool VEC4, int EPT, bool EXT>
 __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
     const bool has_policy = EXT && a.has_policy != 0;
     static_assert(EPT == 4 || EPT == 8 || EPT == 16, "EPT");
+    static_assert(kFastCap + 8 <= kWave * kWaveTopkMaxEPL + 8 && kExpWaves == 16, "candidate list inside the selection scratch");
     constexpr int kChunk = kExpThreads * EPT;
     __shared__ ExpandSmem s;
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
@@ -302,19 +294,44 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
     const int base = chunk * kChunk;
     const int K = a.k;
 
-    // ---- stream the chunk: EPT/4 x (1024 lanes x 16 B), coalesced; all loads are issued before
-    // anything is computed from them (out-of-range lanes read a valid address and are masked)
-    float4 raw[EPT / 4];
+    // ---- stream the chunk.  Only the first four wavefronts (one per SIMD) stream and select: a
+    // 64-wide vector instruction occupies its SIMD for four cycles whichever wavefront issues it, so
+    // four wavefronts with 4 * EPT logits per lane do the per-logit work in the same time as sixteen
+    // with EPT each, and what a wavefront does once (reductions, threshold, list bookkeeping) is
+    // done four times per workgroup instead of sixteen.  The other wavefronts only serve the end of
+    // the call (one row each, the prediction model).  NE/4 x (256 lanes x 16 B) coalesced loads, all
+    // issued before anything is computed from them (out-of-range lanes read a valid address and are
+    // masked).
+    constexpr int kStreamers = 4;                                  // wavefronts that stream
+    constexpr int kSLanes = kStreamers * kWave;
+    constexpr int NE = EPT * (kExpThreads / kSLanes);              // logits per streaming lane
+    const bool streamer = w < kStreamers;
+    const bool tail = base + kChunk > a.V;                         // the row ends inside this chunk
+    float x[NE];
+    if (streamer) {
+        float4 raw[NE / 4];
 #pragma unroll
-    for (int g = 0; g < EPT / 4; ++g) {
-        const int idx0 = base + g * (kExpThreads * 4) + tid * 4;
-        if (VEC4) {
-            raw[g] = *reinterpret_cast<const float4 *>(row + (idx0 < a.V ? idx0 : 0));
-        } else {
-            raw[g].x = row[min(idx0 + 0, a.V - 1)];
-            raw[g].y = row[min(idx0 + 1, a.V - 1)];
-            raw[g].z = row[min(idx0 + 2, a.V - 1)];
-            raw[g].w = row[min(idx0 + 3, a.V - 1)];
+        for (int g = 0; g < NE / 4; ++g) {
+            const int idx0 = base + g * (kSLanes * 4) + tid * 4;
+            if (VEC4) {
+                raw[g] = *reinterpret_cast<const float4 *>(row + (idx0 < a.V ? idx0 : 0));
+            } else {
+                raw[g].x = row[min(idx0 + 0, a.V - 1)];
+                raw[g].y = row[min(idx0 + 1, a.V - 1)];
+                raw[g].z = row[min(idx0 + 2, a.V - 1)];
+                raw[g].w = row[min(idx0 + 3, a.V - 1)];
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < NE / 4; ++g) {
+            x[4 * g + 0] = raw[g].x; x[4 * g + 1] = raw[g].y; x[4 * g + 2] = raw[g].z; x[4 * g + 3] = raw[g].w;
+        }
+        if (tail) {
+#pragma unroll
+            for (int e = 0; e < NE; ++e) {
+                const int idx = base + (e >> 2) * (kSLanes * 4) + tid * 4 + (e & 3);
+                x[e] = idx < a.V ? x[e] : -INFINITY;
+            }
         }
     }
     // The prediction model's input-free part (w_hh h) is shared out over the workgroups of the
@@ -323,77 +340,169 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
     if (has_policy && a.pol_has_state)
         policy_hidden_rows<4>(a.pol, bz, blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y,
                               [&](int r, float v) { store_shared_result(&a.gate_pre[r], v); });
-    float x[EPT];
-#pragma unroll
-    for (int g = 0; g < EPT / 4; ++g) {
-        const int idx0 = base + g * (kExpThreads * 4) + tid * 4;
-        const float v[4] = {raw[g].x, raw[g].y, raw[g].z, raw[g].w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) x[4 * g + j] = (idx0 + j < a.V) ? v[j] : -INFINITY;
-    }
 
-    // ---- log-sum-exp partial per wavefront (exp2 of fp32 differences; a lane's few terms are added in
-    // fp32, everything after that in fp64)
-    float tm = x[0];
+    // ---- the chunk's maximum, and the threshold of its top-k: the k-th largest of the maxima of the
+    // sixteen 16-lane rows of the streaming wavefronts.  At least k logits of the chunk reach it (one
+    // per row whose maximum does), and on untied data only about 1.6 k do.  Everything here is a
+    // chain of latencies (a ballot whose count a scalar instruction needs costs ~30 cycles, a lane
+    // read with a compare ~40, an LDS round trip ~120), so the steps are laid out to run side by
+    // side: a wavefront that does not stream ranks the sixteen maxima while the streaming ones take
+    // their exponentials, and logits are compared with the threshold only where they can reach it.
+    float lmax = -INFINITY;                                        // the lane's largest logit
+    if (streamer) {
+        lmax = x[0];
 #pragma unroll
-    for (int e = 1; e < EPT; ++e) tm = fmaxf(tm, x[e]);
-    const float wm = wave_max_f32(tm);
-    float tl = 0.f;
-    if (wm > -INFINITY) {
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) tl += __builtin_amdgcn_exp2f((x[e] - wm) * kLog2eF);
+        for (int e = 1; e < NE; ++e) lmax = fmaxf(lmax, x[e]);
+        float rm = lmax;
+        rm = fmaxf(rm, dpp_f32<0xB1>(rm));
+        rm = fmaxf(rm, dpp_f32<0x4E>(rm));
+        rm = fmaxf(rm, dpp_f32<0x141>(rm));
+        rm = fmaxf(rm, dpp_f32<0x140>(rm));                        // every lane: the maximum of its 16-lane row
+        if ((lane & 15) == 0) s.gmax[w * 4 + (lane >> 4)] = rm;
     }
-    const double wl = wave_sum_f64((double)tl);
-    if (lane == 0) { s.wave_m[w] = wm; s.wave_l[w] = wl; }
-
-    // ---- candidates of each wavefront (everything that reaches the K-th largest quad maximum; no
-    // ranking yet), then the top-k of the 16 candidate lists
-    {
-        uint64_t *list = &s.wlist[w * kWaveListSlots];
-        bool listed = false;
-        if constexpr (EPT <= 8)
-            listed = wave_candidates<EPT>(x, tm, uint32_t(base + tid * 4), uint32_t(kExpThreads * 4), uint32_t(a.V), K, s.wtk[w], list);
-        else
-            listed = wave_candidates_counted<EPT>(x, tm, uint32_t(base + tid * 4), uint32_t(kExpThreads * 4), uint32_t(a.V), K, list);
-        if (!listed) {                                             // more than 32 candidates: rank
-            uint64_t keys[EPT];
+    if (tid == 0) { s.nsurv = 0; s.ndump = 0; }
+    if (tid < 16) s.ctop[tid] = 0;
+    __syncthreads();
+    float cm = 0.f;                                                // chunk maximum (streamers, and wavefront 1 below)
+    if (w == kStreamers) {
+        // threshold: the k-th largest of the sixteen maxima (ties: lower row first), by one wavefront
+        const uint32_t ov = ord_of(s.gmax[lane & 15]);             // every 16-lane row holds the 16 maxima
+        int larger = 0;
 #pragma unroll
-            for (int e = 0; e < EPT; ++e) {
-                const int idx = base + (e >> 2) * (kExpThreads * 4) + tid * 4 + (e & 3);
-                keys[e] = idx < a.V ? make_key(x[e], uint32_t(idx)) : 0;
+        for (int j = 0; j < 16; ++j) {
+            const uint32_t oj = readlane_u32(ov, j);
+            larger += (oj > ov || (oj == ov && j < (lane & 15))) ? 1 : 0;
+        }
+        const uint64_t sel = __ballot(larger == K - 1) & 0xffffull; // ranks are a permutation of 0..15: exactly one lane
+        if (lane == 0) s.tau = float_of_ord(readlane_u32(ov, __ffsll((long long)sel) - 1));
+    } else if (streamer) {
+        cm = s.gmax[lane & 15];
+        cm = fmaxf(cm, dpp_f32<0xB1>(cm));
+        cm = fmaxf(cm, dpp_f32<0x4E>(cm));
+        cm = fmaxf(cm, dpp_f32<0x141>(cm));
+        cm = fmaxf(cm, dpp_f32<0x140>(cm));
+        // ---- sum of exp(x - chunk maximum): fp32 exponentials; a lane adds its terms in four fp32 chains,
+        // the wavefront's 64 lanes as a fixed fp32 tree (relative error below 1e-6), the rest is fp64.
+        // (x - cm) first: folding the scale into one fused multiply-add would round cm * log2(e), an
+        // absolute error in the exponent that grows with |cm|.
+        float tl[4] = {0.f, 0.f, 0.f, 0.f};
+        if (cm > -INFINITY) {
+#pragma unroll
+            for (int e = 0; e < NE; ++e) tl[e & 3] += __builtin_amdgcn_exp2f((x[e] - cm) * kLog2eF);
+        }
+        const float wl = wave_sum_f32((tl[0] + tl[1]) + (tl[2] + tl[3]));
+        if (lane == 0) s.wave_l[w] = wl;
+    }
+    __syncthreads();
+    // Lanes whose largest logit reaches the threshold (about 1.6 k of the 256) leave all their logits
+    // in LDS; only those are compared one by one afterwards.
+    float *const dump = reinterpret_cast<float *>(&s.wtk[1]);      // [kDumpCap][NE], inside the selection scratch
+    uint64_t *const surv = s.wtk[0].surv;                          // kFastCap + 8 slots
+    static_assert(kDumpCap * NE * sizeof(float) <= (kExpWaves - 1) * sizeof(WaveTopkSmem), "dump inside the scratch");
+    const float tau_f = s.tau;
+    if (streamer) {
+        const bool hot = lmax >= tau_f && base + tid * 4 < a.V;    // (a lane wholly past the row holds -inf only)
+        const uint64_t hm = __ballot(hot);
+        if (hm != 0) {
+            int at = 0;
+            if (lane == 0) at = (int)atomicAdd(&s.ndump, (unsigned int)__popcll(hm));
+            at = (int)readlane_u32((uint32_t)at, 0) + lanes_below(hm);
+            if (hot && at < kDumpCap) {
+                float4 *d4 = reinterpret_cast<float4 *>(dump + (size_t)at * NE);
+#pragma unroll
+                for (int g = 0; g < NE / 4; ++g) d4[g] = make_float4(x[4 * g], x[4 * g + 1], x[4 * g + 2], x[4 * g + 3]);
+                s.dump_lane[at] = (unsigned short)tid;
             }
-            constexpr int E1 = EPT < 8 ? EPT : 8;
-            uint64_t kk[E1];
-#pragma unroll
-            for (int e = 0; e < E1; ++e) kk[e] = keys[e];
-            uint64_t wt = wave_topk<E1>(kk, K, s.wtk[w]);
-            if (EPT > 8) {                                         // the rest, with the selection so far
-                uint64_t k2[EPT - E1 + 1];
-#pragma unroll
-                for (int e = E1; e < EPT; ++e) k2[e - E1] = keys[e];
-                k2[EPT - E1] = wt;
-                wt = wave_topk<EPT - E1 + 1>(k2, K, s.wtk[w]);
-            }
-            if (lane < kWaveListSlots) list[lane] = wt;            // lanes 16.. hold 0
         }
     }
     __syncthreads();
-
+    const int ndump = (int)s.ndump;
+    if (ndump <= kDumpCap) {
+        // The logits of the hot lanes against the threshold, all sixteen wavefronts side by side: a lane
+        // takes one logit of one block; what passes goes to the workgroup's candidate list (its order is
+        // immaterial, the ranking below is by key).
+        constexpr int kPerWave = NE <= kWave ? kWave / NE : 1;     // blocks a wavefront takes at a time
+        for (int d0 = w * kPerWave; d0 < ndump; d0 += kExpWaves * kPerWave) {
+#pragma unroll
+            for (int e1 = 0; e1 < NE; e1 += kWave) {               // (one round unless a lane streams more than 64 logits)
+                const int d = d0 + (NE <= kWave ? lane / NE : 0);
+                const int e = NE <= kWave ? lane % NE : e1 + lane;
+                const bool live = d < ndump;
+                const float v = dump[(size_t)min(d, ndump - 1) * NE + e];
+                const int src = (int)s.dump_lane[min(d, ndump - 1)];
+                const int idx = base + (e >> 2) * (kSLanes * 4) + src * 4 + (e & 3);
+                const uint64_t m = __ballot(live && v >= tau_f && idx < a.V);
+                if (m != 0) {
+                    int at = 0;
+                    if (lane == 0) at = (int)atomicAdd(&s.nsurv, (unsigned int)__popcll(m));
+                    at = (int)readlane_u32((uint32_t)at, 0) + lanes_below(m);
+                    if (((m >> lane) & 1) && at < kFastCap) surv[at] = make_key(v, uint32_t(idx));
+                }
+            }
+        }
+    }
+    // more hot lanes or candidates than the lists hold means long runs of equal values (every
+    // wavefront reads the same counts after the barrier and takes the same path)
+    if (ndump > kDumpCap && tid == 0) s.nsurv = kFastCap + 1;
+    __syncthreads();
     const size_t pslot = (size_t)f * a.nchunks + chunk;
-    if (w == 0) {
-        constexpr int NS = kExpWaves * kWaveListSlots / kWave;    // 16 lists of 32 slots, eight slots per lane
-        uint64_t kk[NS];
+    const int nsurv = (int)s.nsurv;
+    if (nsurv > kFastCap) {
+        // Long runs of equal values (more candidates than the list holds): every streaming wavefront
+        // ranks its own logits exactly, eight per lane at a time with the selection so far riding
+        // along, then one wavefront ranks the four lists.  The logits are read again (a rolled loop
+        // over registers would index them dynamically); this path only runs on heavily tied rows.
+        if (streamer) {
+            uint64_t wt = 0;
+#pragma unroll 1
+            for (int g0 = 0; g0 < NE / 4; g0 += 2) {
+                uint64_t kk[9];
 #pragma unroll
-        for (int e = 0; e < NS; ++e) kk[e] = s.wlist[topk_slot_of(e)];   // rotated: the used slots lead each list
-        const uint64_t top = wave_topk<NS>(kk, K, s.wtk[0]);
-        if (lane < K) store_shared_result(a.part_keys + pslot * RADAR_K_MAX + lane, top);
-    } else if (w == 1) {
-        float m = s.wave_m[0];
+                for (int u = 0; u < 8; ++u) {
+                    const int idx = base + (g0 + (u >> 2)) * (kSLanes * 4) + tid * 4 + (u & 3);
+                    const float v = row[min(idx, a.V - 1)];
+                    kk[u] = idx < a.V ? make_key(v, uint32_t(idx)) : 0;
+                }
+                kk[8] = wt;
+                wt = wave_topk<9>(kk, K, s.wtk[w]);
+            }
+            if (lane < kWaveListSlots) s.wlist[w * kWaveListSlots + lane] = wt;   // lanes 16.. hold 0
+        }
+        __syncthreads();
+        if (w == 0) {
+            constexpr int NS = kStreamers * kWaveListSlots / kWave;   // four lists of 32 slots, two slots per lane
+            uint64_t k2[NS];
 #pragma unroll
-        for (int i = 1; i < kExpWaves; ++i) m = fmaxf(m, s.wave_m[i]);
-        const double l = combine_waves(s.wave_m, s.wave_l, m);
+            for (int e = 0; e < NS; ++e) k2[e] = s.wlist[e * kWave + lane];
+            const uint64_t top = wave_topk<NS>(k2, K, s.wtk[0]);
+            if (lane < K) store_shared_result(a.part_keys + pslot * RADAR_K_MAX + lane, top);
+        }
+    } else if (w == 0) {
+        // exact ranks among the chunk's candidates: every lane counts the larger keys with broadcast reads
+        if (lane < 8) surv[nsurv + lane] = 0;                      // padding for the grouped reads
+        wave_lds_sync();
+        for (int i0 = 0; i0 < nsurv; i0 += kWave) {                // one pass unless there are many ties
+            const int i = i0 + lane;
+            const uint64_t key = surv[min(i, nsurv - 1)];
+            int rank = 0;
+            for (int j = 0; j < nsurv; j += 8) {
+                uint64_t kj[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) kj[u] = surv[j + u];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) rank += (kj[u] > key) ? 1 : 0;
+            }
+            if (i < nsurv && rank < K) s.ctop[rank] = key;
+        }
+        wave_lds_sync();
+        if (lane < K) store_shared_result(a.part_keys + pslot * RADAR_K_MAX + lane, s.ctop[lane]);
+    }
+    if (w == 1) {
+        double l = 0.0;                                            // fixed order of addition
+#pragma unroll
+        for (int i = 0; i < kStreamers; ++i) l += (double)s.wave_l[i];
         if (lane == 0) {
-            store_shared_result(&a.part_m[pslot], m);
+            store_shared_result(&a.part_m[pslot], cm);
             store_shared_result(&a.part_l[pslot], l);
         }
     }
