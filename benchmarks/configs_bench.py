@@ -5,7 +5,7 @@ memory than the caches hold, per-kernel device durations recorded by the library
 (radar_profile_begin / radar_profile_end), algorithmic bytes and flops, and the fraction of the
 roof that binds (HBM 8 TB/s; dense bf16 MFMA 2.5 PFLOP/s for attention at configuration 5).
 
-    python -m paper_2512_14069_amd.configs_bench [--reps 30] [--configs 2,4,5] [--modes greedy,sampling]
+    python -m benchmarks.configs_bench [--reps 30] [--configs 2,4,5] [--modes greedy,sampling]
 
 Inputs are synthetic: the trees come from the seeded generators, tensors are drawn on the device
 (timing does not depend on their values beyond the shape of the accepted path).
@@ -27,7 +27,7 @@ def main():
     args = ap.parse_args()
     import numpy as np
     import torch
-    from . import binding as b, synth
+    from paper_2512_14069_amd import binding as b, synth
 
     if not torch.cuda.is_available():
         print("configs_bench: no GPU visible", file=sys.stderr)

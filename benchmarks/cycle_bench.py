@@ -7,7 +7,7 @@ by call (argument marshalling done beforehand) or as one captured HIP graph, and
 scripted to stop after 2, 4 or all 8 draft calls.  Inputs rotate through several sets (one graph
 per set).  Prints one JSON line per (mode, stop) with the microseconds per cycle.
 
-    python -m paper_2512_14069_amd.cycle_bench [--cycles 300] [--sets 4] [--batch B]
+    python -m benchmarks.cycle_bench [--cycles 300] [--sets 4] [--batch B]
 
 --batch B > 1 runs the cycles of B sequences together: batched draft calls (radar_draft_expand_batch with
 every sequence's own state and decision), one batched rerank, attention and the verify walk over the B
@@ -27,7 +27,7 @@ def main():
     args = ap.parse_args()
     import numpy as np
     import torch
-    from . import binding as b, synth
+    from paper_2512_14069_amd import binding as b, synth
 
     if not torch.cuda.is_available():
         print("cycle_bench: no GPU visible", file=sys.stderr)

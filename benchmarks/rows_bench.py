@@ -3,7 +3,7 @@ acceptance-length distribution, prediction-model step (alone and fused into the 
 expansion of 4, 16 and 64 sequences in one launch, and verification with draft distributions.  One JSON line per entry point with the per-kernel device
 durations the library records (radar_profile_begin / radar_profile_end) and the algorithmic bytes.
 
-    python -m paper_2512_14069_amd.rows_bench [--reps 100]
+    python -m benchmarks.rows_bench [--reps 100]
 """
 import argparse
 import json
@@ -16,7 +16,7 @@ def main():
     args = ap.parse_args()
     import numpy as np
     import torch
-    from . import binding as b, synth
+    from paper_2512_14069_amd import binding as b, synth
 
     if not torch.cuda.is_available():
         print("rows_bench: no GPU visible", file=sys.stderr)

@@ -307,16 +307,20 @@ radar_status radar_accept_length_distribution(const float *target_logits, const 
  * [B,T_max+1].  Nodes whose token or draft row is out of range are skipped.
  * Limits: T_max <= RADAR_T_MAX; V <= 1048576; B * (T_max + Tq) <= 65535;
  *         both temperatures > 0.  Two or three kernels are enqueued.  The shared walk needs its
- *         B * G <= 256 workgroups resident together (an otherwise idle GPU); if they are not,
- *         the bounded wait turns into the fall-back described at walk_spin_limit. */
+ *         B * G workgroups resident together; the library sizes G from the occupancy the runtime
+ *         reports for the device (CUs x workgroups per CU) and bounds every wait (about 100 us by
+ *         default): where other work keeps some of them from running, the wait ends and the
+ *         fall-back described at walk_spin_limit redoes the sequence.  On a GPU that is shared as a
+ *         rule, pass walk_spin_limit < 0 (single-workgroup walk, no waiting at all). */
 typedef struct radar_accept_q_desc {
     int32_t B, T_max, Tq, V, D_max;
     float   temperature, draft_temperature;
     int32_t walk_spin_limit;    /* 0: the library's choice.  The walk of one sequence is shared by several
                                    workgroups that meet at a counter after every rejection; the wait there is
                                    bounded, and a sequence whose workgroups gave up is redone by a single one
-                                   (same results).  > 0: polls before giving up (tests pass 1 to force that
-                                   path); < 0: single-workgroup walk only */
+                                   (same results).  > 0: polls (about 0.4 us each) before giving up (tests
+                                   pass 1 to force that path; the default is 256); < 0: single-workgroup
+                                   walk only */
 } radar_accept_q_desc;
 
 size_t radar_verify_accept_q_workspace_bytes(const radar_accept_q_desc *desc);

@@ -7,6 +7,7 @@ package.
 """
 from .radar_oracle import (  # noqa: F401
     build,
+    sanitizer_runtime,
     num_threads,
     set_threads,
     round_bf16,

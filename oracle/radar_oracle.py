@@ -19,22 +19,36 @@ class OracleError(RuntimeError):
     pass
 
 
-def build(force=False):
-    """Compile radar_oracle.c with gcc into oracle/libradar_oracle.so."""
-    if (not force and os.path.exists(_LIB)
-            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
-        return _LIB
-    cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
-           "-o", _LIB, _SRC, "-lm"]
+_SAN_LIB = os.path.join(_HERE, "libradar_oracle_san.so")
+# RADAR_ORACLE_SANITIZE=1 in the environment makes this module load the sanitized build (the
+# process must then have gcc's libasan preloaded; tests/test_sanitizers.py does that in a child).
+_SANITIZE = os.environ.get("RADAR_ORACLE_SANITIZE", "0") == "1"
+
+
+def build(force=False, sanitize=None):
+    """Compile radar_oracle.c with gcc into oracle/libradar_oracle.so, or, with sanitize=True, into
+    oracle/libradar_oracle_san.so under AddressSanitizer and UndefinedBehaviorSanitizer."""
+    sanitize = _SANITIZE if sanitize is None else sanitize
+    lib = _SAN_LIB if sanitize else _LIB
+    if (not force and os.path.exists(lib)
+            and os.path.getmtime(lib) >= os.path.getmtime(_SRC)):
+        return lib
+    opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           "-fno-omit-frame-pointer"] if sanitize else ["-O2"]
+    cmd = ["gcc"] + opt + ["-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra", "-o", lib, _SRC, "-lm"]
     subprocess.run(cmd, check=True)
-    return _LIB
+    return lib
+
+
+def sanitizer_runtime():
+    """Path of gcc's address-sanitizer runtime, to preload into a process that loads the sanitized build."""
+    return subprocess.run(["gcc", "-print-file-name=libasan.so"], capture_output=True, text=True).stdout.strip()
 
 
 def _load():
     global _lib
     if _lib is None:
-        build()
-        _lib = ctypes.CDLL(_LIB)
+        _lib = ctypes.CDLL(build())
         _lib.radar_oracle_round_bf16.restype = ctypes.c_uint16
         _lib.radar_oracle_round_bf16.argtypes = [ctypes.c_double]
     return _lib

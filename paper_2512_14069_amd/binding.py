@@ -11,7 +11,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libradar.so")
+# RADAR_LIB_SANITIZE=1 selects the build whose host code runs under the sanitizers (CPU tests only)
+LIB_PATH = os.path.join(_HERE, "libradar_san.so" if os.environ.get("RADAR_LIB_SANITIZE", "0") == "1" else "libradar.so")
 _lib = None
 
 RADAR_OK = 0

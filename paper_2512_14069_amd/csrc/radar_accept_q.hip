@@ -718,13 +718,31 @@ using namespace radar;
 
 static int aq_chunks(int V) { return (V + kAqChunk - 1) / kAqChunk; }
 
+// How many 1024-lane workgroups of the shared walk the current device can hold at once: the
+// occupancy the runtime reports for the kernel times the number of CUs (queried once; 0 if the
+// queries fail, which selects the single-workgroup walk).
+static int aq_resident_capacity() {
+    static const int capacity = [] {
+        int dev = 0, per_cu = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(&accept_q_coop_kernel<true>),
+                                                         kAqThreads, 0) != hipSuccess)
+            return 0;
+        return per_cu * prop.multiProcessorCount;
+    }();
+    return capacity;
+}
+
 // Workgroups per sequence (G) and float4 per lane (R) of the walk; G = 1 means the single-workgroup
-// walk.  All G * B workgroups must be resident together for the arrival counters to make progress,
-// so their number stays within the 256 CUs (one 1024-lane workgroup each).
+// walk.  The G * B workgroups of the shared walk meet at arrival counters, which only makes progress
+// while all of them are resident, so their number stays within what the device holds at once (on a
+// GPU that other work shares, the bounded wait turns a missing workgroup into the fall-back).
 static void aq_coop_plan(const radar_accept_q_desc *d, int *G, int *R) {
     *G = 1; *R = 1;
-    if (d->walk_spin_limit < 0 || d->B > 128) return;
-    const int gcap = 256 / d->B < kCoG ? 256 / d->B : kCoG;
+    const int cap = aq_resident_capacity();
+    if (d->walk_spin_limit < 0 || cap < 2 || d->B > cap / 2) return;
+    const int gcap = cap / d->B < kCoG ? cap / d->B : kCoG;
     const int per_wg = kAqThreads * 4;
     int r = ((d->V + per_wg - 1) / per_wg + gcap - 1) / gcap;              // float4 per lane needed with gcap workgroups
     if (r > kCoR) return;
@@ -787,7 +805,9 @@ extern "C" radar_status radar_verify_accept_q(const float *target_logits, const 
     int G = 1, R = 1;
     aq_coop_plan(d, &G, &R);
     a.co_R = R;
-    a.co_spin_limit = d->walk_spin_limit > 0 ? (unsigned int)d->walk_spin_limit : 1000000u;   // roughly a second of polling
+    // default: 256 polls of about 0.4 us (an atomic load and a short sleep): the workgroups of a walk reach a
+    // meeting within microseconds of each other, so 100 us without progress means one of them is not running
+    a.co_spin_limit = d->walk_spin_limit > 0 ? (unsigned int)d->walk_spin_limit : 256u;
 
     const bool vec4 = (d->V % 4 == 0) && (((uintptr_t)target_logits & 15) == 0) && (((uintptr_t)draft_logits & 15) == 0);
     hipStream_t st = static_cast<hipStream_t>(stream);
