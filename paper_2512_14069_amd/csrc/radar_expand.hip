@@ -64,7 +64,6 @@ struct ExpandArgs {
 struct alignas(16) ExpandSmem {
     WaveTopkSmem wtk[kExpWaves];                  // one scratch per wavefront
     uint64_t wlist[kExpWaves * kWaveListSlots];   // the wavefronts' candidates of a chunk (0 = none; many ties only)
-    uint64_t ctop[16];                            // the chunk's top-k, best first
     float gmax[16];                               // maxima of the sixteen 16-lane rows of the streaming wavefronts
     float wave_l[4];                              // sum of exp(x - chunk maximum) over each streaming wavefront
     unsigned int nsurv;                           // candidates of the chunk that reached the threshold
@@ -192,11 +191,13 @@ __device__ __forceinline__ void expand_finish(const ExpandArgs &a, ExpandSmem &s
         }
         float ml;
         double ll;
+        const bool few_chunks = a.nchunks <= 16;                   // every 16-lane row of the wavefront takes all chunks
         {                                                          // chunk partials, one chunk per lane first
-            const int c = min(lane, a.nchunks - 1);
+            const int cl = few_chunks ? (lane & 15) : lane;
+            const int c = min(cl, a.nchunks - 1);
             ml = load_shared_result(&a.part_m[(size_t)fr * a.nchunks + c]);
             ll = load_shared_result(&a.part_l[(size_t)fr * a.nchunks + c]);
-            if (lane >= a.nchunks) { ml = -INFINITY; ll = 0.0; }
+            if (cl >= a.nchunks) { ml = -INFINITY; ll = 0.0; }
         }
         const float pscore = a.parent_scores[fr];
         const int ppool = a.parent_pool_idx[fr];
@@ -215,8 +216,26 @@ __device__ __forceinline__ void expand_finish(const ExpandArgs &a, ExpandSmem &s
                 ll = ll * (double)__builtin_amdgcn_exp2f((ml - mn) * kLog2eF) + l2 * (double)__builtin_amdgcn_exp2f((m2 - mn) * kLog2eF);
             ml = mn;
         }
-        const float M = wave_max_f32(ml);
-        const double L = wave_sum_f64(ml > -INFINITY ? ll * (double)__builtin_amdgcn_exp2f((ml - M) * kLog2eF) : 0.0);
+        float M;
+        double L;
+        if (few_chunks) {
+            // maximum and sum inside each 16-lane row by DPP steps alone (no lane reads: those cost a
+            // scalar round trip each); fixed order of addition, every lane ends up with the result
+            M = ml;
+            M = fmaxf(M, dpp_f32<0xB1>(M));
+            M = fmaxf(M, dpp_f32<0x4E>(M));
+            M = fmaxf(M, dpp_f32<0x141>(M));
+            M = fmaxf(M, dpp_f32<0x140>(M));
+            L = ml > -INFINITY ? ll * (double)__builtin_amdgcn_exp2f((ml - M) * kLog2eF) : 0.0;
+            auto add = [](double x, uint64_t moved) { return x + __longlong_as_double((long long)moved); };
+            L = add(L, dpp_u64<0xB1>((uint64_t)__double_as_longlong(L)));
+            L = add(L, dpp_u64<0x4E>((uint64_t)__double_as_longlong(L)));
+            L = add(L, dpp_u64<0x141>((uint64_t)__double_as_longlong(L)));
+            L = add(L, dpp_u64<0x140>((uint64_t)__double_as_longlong(L)));
+        } else {
+            M = wave_max_f32(ml);
+            L = wave_sum_f64(ml > -INFINITY ? ll * (double)__builtin_amdgcn_exp2f((ml - M) * kLog2eF) : 0.0);
+        }
         // log in fp32 (1 ulp of a value below 14: 1e-6, a tenth of the tolerance on log-probabilities); the
         // fp64 routine costs 0.3 us on this serial path
         const double lse = (double)M + (double)logf((float)L);
@@ -361,7 +380,6 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
         if ((lane & 15) == 0) s.gmax[w * 4 + (lane >> 4)] = rm;
     }
     if (tid == 0) { s.nsurv = 0; s.ndump = 0; }
-    if (tid < 16) s.ctop[tid] = 0;
     __syncthreads();
     float cm = 0.f;                                                // chunk maximum (streamers, and wavefront 1 below)
     if (w == kStreamers) {
@@ -492,10 +510,9 @@ __global__ __launch_bounds__(kExpThreads, 1) void expand_kernel(ExpandArgs a) {
 #pragma unroll
                 for (int u = 0; u < 8; ++u) rank += (kj[u] > key) ? 1 : 0;
             }
-            if (i < nsurv && rank < K) s.ctop[rank] = key;
+            if (i < nsurv && rank < K) store_shared_result(a.part_keys + pslot * RADAR_K_MAX + rank, key);   // ranks are distinct
         }
-        wave_lds_sync();
-        if (lane < K) store_shared_result(a.part_keys + pslot * RADAR_K_MAX + lane, s.ctop[lane]);
+        if (lane >= nsurv && lane < K) store_shared_result(a.part_keys + pslot * RADAR_K_MAX + lane, (uint64_t)0);   // fewer than K in the chunk
     }
     if (w == 1) {
         double l = 0.0;                                            // fixed order of addition
