@@ -76,6 +76,16 @@ __device__ __forceinline__ int key_slot(int kappa) {
     return (kappa & ~12) | ((kappa & 4) << 1) | ((kappa & 8) >> 1);
 }
 
+// byte offset of 16-byte chunk `chunk` of row `row` in a row-major V tile that is read by transposing
+// LDS reads: one pass of such a read (32 lanes) touches 64 consecutive bytes of four consecutive rows,
+// and with 256-byte rows these would meet in the same banks; the row's two low bits move its 64-byte
+// windows apart.  (8 rows + 8 keeps the swizzle: the second read of a pair differs by a constant.)
+template <int D>
+__device__ __forceinline__ int vs_off(int row, int chunk) {
+    static_assert(D == 128, "row-major V tiles are built for 256-byte rows");
+    return row * (D * 2) + ((chunk ^ ((row & 3) << 2)) << 4);
+}
+
 // v = keep ? v : 0 without a branch (a select after a load tempts the compiler into a
 // conditional load, and conditional loads into register arrays wreck register allocation)
 __device__ __forceinline__ void and_mask(u32x4 &v, bool keep) {
@@ -92,131 +102,134 @@ __device__ __forceinline__ uint64_t ancestor_word(const int *par, int i) {
     return m;
 }
 
-// One wavefront, one 64-row tile that sits in LDS (Ks row-major swizzled, Vt transposed):
-// scores, masked online softmax, and the update of the transposed output accumulators.
+// One wavefront, one 64-row tile that sits in LDS, in three phases: scores into
+// `sacc` (register r of sub-tile `sub` is row 32*sub + 8*(r/4) + 4*g2 + r%4), masked online softmax
+// from `sacc` into the bf16 operand `pk` (rescaling the output accumulators when the maximum moved),
+// and the update of the transposed output accumulators, from a transposed V tile (vt_off) or, with
+// VTR, from a row-major one (vs_off) through transposing LDS reads.
 // The lane's query operands are passed in registers (qop: row j32 of the block, d = 16*st + 8*g2
 // .. +8; 32 VGPRs at D = 128): every LDS byte not read matters here, the eight wavefronts of a
-// workgroup already read each K and V tile eight times over.
+// workgroup already read each K and V tile eight times over.  K operands are read from LDS four
+// MFMAs before they are needed and the two score sub-tiles (the four output blocks) take turns, so
+// that consecutive MFMAs are independent and none starts by waiting for LDS.
 //   t0        cache row of the tile's first key;  L = prefix length;  kend = end of this range
 //   first     true if the accumulators are still zero (no rescaling needed)
-template <int D, int NQB>
-__device__ __forceinline__ void wave_tile(const unsigned char *Ks, const unsigned char *Vt,
-                                          const bf16x8 (&qop)[D / 16], floatx16 (&oacc)[D / 32][NQB],
-                                          float (&m_run)[NQB], float (&l_run)[NQB], const uint64_t (&anc)[NQB],
-                                          int t0, int L, int kend, bool first, float scale_log2) {
-    constexpr int KSTEPS = D / 16, DB = D / 32;
+template <int D>
+__device__ __forceinline__ void tile_scores(const unsigned char *Ks, const bf16x8 (&qop)[D / 16], floatx16 (&sacc)[2]) {
+    constexpr int KSTEPS = D / 16, NS = 2 * KSTEPS, kAhead = 4;
     const int lane = lane_id();
     const int j32 = lane & 31, g2 = lane >> 5;
-    const bool need_mask = (t0 + kKT > L) || (t0 + kKT > kend);
-
-    // Order of work (NQB = 2): scores of block 0, scores of block 1, softmax of block 0, P.V of
-    // block 0, softmax of block 1, P.V of block 1.  Each softmax (vector ALU) is independent of the
-    // MFMAs issued just before it, so the matrix pipe keeps running underneath it; with one
-    // wavefront per SIMD nothing else would hide that time.  K and V operands are read from LDS
-    // once per 32-query block.
-    // Register r of sub-tile `sub` is key 32*sub + 8*(r/4) + 4*g2 + r%4.
-    floatx16 sacc[NQB][2];
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-        static_assert(NQB == 1, "the query operands of one 32-row block are passed in registers");
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[sub][r] = 0.f;
+    auto kread = [&](int k) {
+        return *reinterpret_cast<const u32x4 *>(Ks + ks_off<D>(32 * (k & 1) + j32, 2 * (k >> 1) + g2));
+    };
+    u32x4 kf[kAhead];
+#pragma unroll
+    for (int k = 0; k < kAhead; ++k) kf[k] = kread(k);
+#pragma unroll
+    for (int k = 0; k < NS; ++k) {
+        const u32x4 cur = kf[k % kAhead];
+        if (k + kAhead < NS) kf[k % kAhead] = kread(k + kAhead);
+        sacc[k & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, cur), qop[k >> 1], sacc[k & 1], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);          // the order written above, for the scheduler
+#pragma unroll
+    for (int k = 0; k < NS; ++k) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (k + kAhead < NS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void tile_softmax(floatx16 (&sacc)[2], floatx16 (&oacc)[D / 32][1], float &m_run, float &l_run,
+                                           uint64_t anc, int t0, int L, int kend, bool first, float scale_log2,
+                                           bf16x8 (&pk)[2][2]) {
+    constexpr int DB = D / 32;
+    const int g2 = lane_id() >> 5;
+    if ((t0 + kKT > L) || (t0 + kKT > kend)) {                       // wave-uniform; prefix tiles skip it
+        const int pre = L - t0;                                      // prefix keys in this tile (may be <= 0 or >= 64)
+        uint64_t allow = pre >= 64 ? ~0ull : (pre > 0 ? ((1ull << pre) - 1) : 0ull);
+        if (pre > -64 && pre < 64) allow |= pre >= 0 ? (anc << pre) : (anc >> (-pre));
+        const int len = kend - t0;
+        if (len < 64) allow &= len > 0 ? ((1ull << len) - 1) : 0ull;
+        allow >>= 4 * g2;
+        const uint32_t aw[2] = {(uint32_t)allow, (uint32_t)(allow >> 32)};
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[qb][sub][r] = 0.f;
-        // The two sub-tiles take turns (consecutive MFMAs are independent) and the K operands are read
-        // kAhead MFMAs before they are needed, so that an MFMA does not start by waiting for LDS.
-        constexpr int NS = 2 * KSTEPS, kAhead = 4;
-        auto kread = [&](int k) {
-            return *reinterpret_cast<const u32x4 *>(Ks + ks_off<D>(32 * (k & 1) + j32, 2 * (k >> 1) + g2));
-        };
-        u32x4 kf[kAhead];
+            for (int r = 0; r < 16; ++r)
+                sacc[sub][r] = ((aw[sub] >> (8 * (r >> 2) + (r & 3))) & 1u) ? sacc[sub][r] : -INFINITY;
+    }
+    float mx = -INFINITY;
 #pragma unroll
-        for (int k = 0; k < kAhead; ++k) kf[k] = kread(k);
+    for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-        for (int k = 0; k < NS; ++k) {
-            const u32x4 cur = kf[k % kAhead];
-            if (k + kAhead < NS) kf[k % kAhead] = kread(k + kAhead);
-            sacc[qb][k & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, cur), qop[k >> 1],
-                                                                      sacc[qb][k & 1], 0, 0, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);          // the order written above, for the scheduler
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[sub][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx * scale_log2);               // scale_log2 > 0; -inf stays -inf
+    if (!first) {
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        l_run *= alpha;
+        if (__any(alpha != 1.0f)) {                                  // wave-uniform: most tiles skip this
 #pragma unroll
-        for (int k = 0; k < NS; ++k) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (k + kAhead < NS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            for (int db = 0; db < DB; ++db) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[db][0][r] *= alpha;
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     }
+    m_run = m_new;
+    float rs = 0.f;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[sub][r], scale_log2, -m_new));
+            rs += p;
+            pk[sub][r >> 3][r & 7] = (__bf16)p;
+        }
+    l_run += rs;
+}
 
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-        if (need_mask) {                                             // wave-uniform; prefix tiles skip it
-            // bit kappa of `allow`: may this lane's query see key t0 + kappa?  prefix rows, then the
-            // ancestor word shifted to where the tree rows sit in this tile, cut at the range end
-            const int pre = L - t0;                                  // prefix keys in this tile (may be <= 0 or >= 64)
-            uint64_t allow = pre >= 64 ? ~0ull : (pre > 0 ? ((1ull << pre) - 1) : 0ull);
-            if (pre > -64 && pre < 64) allow |= pre >= 0 ? (anc[qb] << pre) : (anc[qb] >> (-pre));
-            const int len = kend - t0;
-            if (len < 64) allow &= len > 0 ? ((1ull << len) - 1) : 0ull;
-            allow >>= 4 * g2;
-            const uint32_t aw[2] = {(uint32_t)allow, (uint32_t)(allow >> 32)};
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    sacc[qb][sub][r] = ((aw[sub] >> (8 * (r >> 2) + (r & 3))) & 1u) ? sacc[qb][sub][r] : -INFINITY;
+template <int D, bool VTR>
+__device__ __forceinline__ void tile_pv(const unsigned char *Vs, const bf16x8 (&pk)[2][2], floatx16 (&oacc)[D / 32][1]) {
+    constexpr int DB = D / 32, NP = 4 * DB, kAhead = 4;
+    const int lane = lane_id();
+    const int j32 = lane & 31, g2 = lane >> 5;
+    // V^T operand straight from the row-major tile, by two transposing LDS reads.  In each block of 16
+    // lanes, lane 4j+q names an 8-byte piece (row kv0+j, elements 4q..4q+3 of the block's 16) and lane l
+    // receives element l%4 of the pieces named by lanes 4j + l/4, j = 0..3: its own d for four
+    // consecutive rows.  Rows 16ss + 4g2 .. +4 fill k-slots 8g2 .. 8g2+3 and the rows eight further on
+    // fill 8g2+4 .. 8g2+7, which is where the P operand has them.
+    typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+    typedef bf16x4_t __attribute__((address_space(3))) *lds_b64;
+    auto vread = [&](int k) {
+        const int db = k % DB, ss = k / DB;                          // ss = 2 * sub + s2
+        if constexpr (!VTR) {
+            return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(Vs + vt_off(32 * db + j32, 16 * ss + 8 * g2)));
+        } else {
+            const int d0 = 32 * db + (j32 & 16) + 4 * (lane & 3);
+            const int kv0 = 16 * ss + 4 * g2 + ((lane >> 2) & 3);
+            const unsigned char *va = Vs + vs_off<D>(kv0, d0 >> 3) + (d0 & 7) * 2;
+            const unsigned char *vb = Vs + vs_off<D>(kv0 + 8, d0 >> 3) + (d0 & 7) * 2;
+            const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64)va);
+            const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64)vb);
+            return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         }
-        float mx = -INFINITY;
+    };
+    bf16x8 vf[kAhead];
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
+    for (int k = 0; k < kAhead; ++k) vf[k] = vread(k);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[qb][sub][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run[qb], mx * scale_log2);     // scale_log2 > 0; -inf stays -inf
-        if (!first) {
-            const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
-            l_run[qb] *= alpha;
-            if (__any(alpha != 1.0f)) {                              // wave-uniform: most tiles skip this
-#pragma unroll
-                for (int db = 0; db < DB; ++db) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
-                    __builtin_amdgcn_sched_barrier(0);        // one 16-register block at a time: keeps the
-                }                                             // accumulator shuffling from exhausting VGPRs
-            }
-        }
-        m_run[qb] = m_new;
-        float rs = 0.f;
-        bf16x8 pk[2][2];
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[qb][sub][r], scale_log2, -m_new));
-                rs += p;
-                pk[sub][r >> 3][r & 7] = (__bf16)p;
-            }
-        l_run[qb] += rs;
-
-        // ---- O^T += V^T P^T for this query block
-        // the output blocks take turns, operands are read kAhead MFMAs ahead as above
-        {
-            constexpr int NP = 4 * DB, kAhead = 4;
-            auto vread = [&](int k) {
-                const int db = k % DB, ss = k / DB;                          // ss = 2 * sub + s2
-                return *reinterpret_cast<const u32x4 *>(Vt + vt_off(32 * db + j32, 16 * ss + 8 * g2));
-            };
-            u32x4 vf[kAhead];
-#pragma unroll
-            for (int k = 0; k < kAhead; ++k) vf[k] = vread(k);
-#pragma unroll
-            for (int k = 0; k < NP; ++k) {
-                const u32x4 cur = vf[k % kAhead];
-                if (k + kAhead < NP) vf[k % kAhead] = vread(k + kAhead);
-                const int db = k % DB, ss = k / DB;
-                oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, cur), pk[ss >> 1][ss & 1],
-                                                                       oacc[db][qb], 0, 0, 0);
-            }
-        }
+    for (int k = 0; k < NP; ++k) {
+        const bf16x8 cur = vf[k % kAhead];
+        if (k + kAhead < NP) vf[k % kAhead] = vread(k + kAhead);
+        const int db = k % DB, ss = k / DB;
+        oacc[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, pk[ss >> 1][ss & 1], oacc[db][0], 0, 0, 0);
     }
 }
 
@@ -423,7 +436,13 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
     // t+1 and tells that nobody reads tile t any more.
     auto step = [&](int t, GsTileRegs<D> &next_regs, int ahead) {
         unsigned char *cur = smem + (t & 1) * TILE, *nxt = smem + ((t + 1) & 1) * TILE;
-        if (active) wave_tile<D, 1>(cur, cur + TILE / 2, qop, oacc, m_run, l_run, anc, kbeg + t * kKT, L, kend, t == 0, a.scale_log2);
+        if (active) {
+            floatx16 sacc[2];
+            bf16x8 pk[2][2];
+            tile_scores<D>(cur, qop, sacc);
+            tile_softmax<D>(sacc, oacc, m_run[0], l_run[0], anc[0], kbeg + t * kKT, L, kend, t == 0, a.scale_log2, pk);
+            tile_pv<D, false>(cur + TILE / 2, pk, oacc);
+        }
         if (t + 1 < ntiles) {
             gs_store_tile<D>(next_regs, nxt, nxt + TILE / 2, kbeg + (t + 1) * kKT, kend, tid);
             __syncthreads();
@@ -443,6 +462,135 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
     } else {
         for (int t = 0; t < ntiles; ++t) step(t, regs0, 2);
     }
+    if (!active) return;
+    gs_finish<D>(a, [&](int db, int r) { return oacc[db][0][r]; }, m_run[0], l_run[0], b, h, i, nn, sp, nsplit);
+}
+
+// ===================================================================== group-share kernel, long ranges
+// The same decomposition with tiles that reach LDS without passing through registers: every wavefront
+// issues four loads per tile that write LDS directly (1 KB each: four rows of K or V; a lane's 16 bytes
+// land at the instruction's LDS base + 16 * lane, so the swizzle is applied by choosing which chunk of
+// the row the lane fetches), a pair of tiles ahead of the pair being consumed, four tile buffers.  V
+// stays row-major and is transposed by the LDS reads that fetch the operands.  No staging registers,
+// no vector instructions for the transposition, one barrier per pair of tiles.  Rows past the end
+// of a range re-read its last row: their scores are masked, and the row they repeat is a cache row
+// whose values the result depends on anyway (0 * finite = 0).
+constexpr int kLdBufs = 4;
+
+template <int D>
+__device__ __forceinline__ void ld_issue_tile(unsigned char *buf, const __bf16 *kbase, const __bf16 *vbase, int kv_ss, int t0,
+                                              int kend, int w, int lane) {
+    static_assert(D == 128, "1 KB per instruction = four 256-byte rows");
+    // Issued as assembly: told about loads that write LDS, the compiler waits for all of them before
+    // the next LDS read it cannot tell apart from their targets, which would undo the run-ahead.  The
+    // waits for these loads are the explicit ones in the kernel's loop.
+    // (m0 is a reserved register: the compiler sets it right before each of its own uses and warns about the clobber)
+    auto lds_load16 = [](const __bf16 *g, unsigned char *dst) {
+        const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)dst);
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(base), "v"(g) : "memory", "m0");
+    };
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int rg = 2 * w + i;                                   // wave-uniform group of four rows
+        const int row = 4 * rg + (lane >> 4), slot = lane & 15;
+        const uint32_t rowoff = (uint32_t)(min(t0 + row, kend - 1) * kv_ss);
+        const __bf16 *gk = kbase + rowoff + ((slot ^ (row & 15)) << 3);           // inverse of ks_off's swizzle
+        const __bf16 *gv = vbase + rowoff + ((slot ^ ((row & 3) << 2)) << 3);     // inverse of vs_off's
+        lds_load16(gk, buf + rg * 1024);
+        lds_load16(gv, buf + kKT * D * 2 + rg * 1024);
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(kGsThreads) void tree_attn_ld_kernel(AttnArgs a) {
+    constexpr int DB = D / 32;
+    constexpr int TILE = 2 * kKT * D * 2;   // one K tile ([64][D] bf16, swizzled) + one V tile (row-major, swizzled)
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    int *s_par = reinterpret_cast<int *>(smem + kLdBufs * TILE);
+
+    const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
+    const int sp = blockIdx.x;
+    const int hk = blockIdx.y / a.n_ublk, ublk = blockIdx.y % a.n_ublk;
+    const int b = blockIdx.z;
+    const int L = a.ctx_lens[b];
+    int nn = a.n_nodes ? a.n_nodes[b] : a.T;
+    nn = max(1, min(nn, a.T));
+    const int total = min(L + nn, a.S);                  // never read past the cache the caller described
+    const int kbeg = sp * a.kps;
+    if (L < 0 || kbeg >= total) return;
+    const int kend = min(total, kbeg + a.kps);
+    const int nsplit = (total + a.kps - 1) / a.kps;
+
+    const int u = ublk * kGsWaves + w;                    // (head within the group, block of 32 rows)
+    const int g = u / a.nqb, qb = u % a.nqb;
+    const bool active = g < a.G;
+    const int h = hk * a.G + (active ? g : 0);
+    const int j32 = lane & 31, g2 = lane >> 5;
+    const int i = 32 * qb + j32;                          // this lane's tree row
+
+    const __bf16 *kbase = a.k + (size_t)b * a.kv_sb + (size_t)hk * a.kv_sh;
+    const __bf16 *vbase = a.v + (size_t)b * a.kv_sb + (size_t)hk * a.kv_sh;
+    const int kv_ss = (int)a.kv_ss;          // 32-bit offsets inside one head's cache (checked on the host)
+    const int ntiles = (kend - kbeg + kKT - 1) / kKT;
+
+    if (tid < RADAR_T_MAX) s_par[tid] = a.parents[(size_t)b * a.T + min(tid, nn - 1)];
+    bf16x8 qop[D / 16];                                  // row i, d = 16*st + 8*g2 .. +8, for the whole kernel
+    {
+        const __bf16 *qrow = a.q + (size_t)b * a.q_sb + (size_t)h * a.q_sh + (uint32_t)(min(i, a.T - 1) * (int)a.q_st);
+#pragma unroll
+        for (int st = 0; st < D / 16; ++st) {
+            u32x4 raw = *reinterpret_cast<const u32x4 *>(qrow + 16 * st + 8 * g2);
+            and_mask(raw, active && i < a.T);
+            qop[st] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+    ld_issue_tile<D>(smem, kbase, vbase, kv_ss, kbeg, kend, w, lane);
+    ld_issue_tile<D>(smem + TILE, kbase, vbase, kv_ss, kbeg + kKT, kend, w, lane);
+    __syncthreads();                                     // the parents are in LDS
+    uint64_t anc[1];
+    anc[0] = (kend > L && i < nn) ? ancestor_word(s_par, i) : 0ull;
+
+    floatx16 oacc[DB][1];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[db][0][r] = 0.f;
+    float m_run[1] = {kNegBig}, l_run[1] = {0.f};
+
+    // Tiles are taken in pairs, four buffers: while the pair (t, t+1) is consumed from two of them the
+    // loads of the next pair arrive in the other two.  One barrier per pair: it publishes the pair
+    // (every wavefront has waited for its own loads) and tells that nobody reads the previous pair
+    // any more, whose buffers the loads issued right after it overwrite -- issued whether or not the
+    // range still has such tiles (see above).  (Not __syncthreads(): nothing here needs its fence.)
+    // The two wavefronts of a SIMD (w and w + 4) are favoured in turn, one in the first tile of a pair
+    // and the other in the second.  Left alone, the older wavefront wins the arbitration in every
+    // tile and finishes it a third ahead of the other; taking turns measured 3-4 % faster at 16 K
+    // cached rows.  (A barrier per pair without the priorities is slower than one per tile, and
+    // priorities with a barrier per tile change nothing.)
+    floatx16 sacc[2];
+    bf16x8 pk[2][2];
+    const int fav = w < kGsWaves / 2 ? 1 : 0;
+    for (int t = 0; t < ntiles; t += 2) {
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        const int half = (t >> 1) & 1;                                     // this pair sits in buffers 2*half, 2*half + 1
+        ld_issue_tile<D>(smem + (2 - 2 * half) * TILE, kbase, vbase, kv_ss, kbeg + (t + 2) * kKT, kend, w, lane);
+        ld_issue_tile<D>(smem + (3 - 2 * half) * TILE, kbase, vbase, kv_ss, kbeg + (t + 3) * kKT, kend, w, lane);
+        if (active) {
+            const unsigned char *tile = smem + 2 * half * TILE;
+            if (fav) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
+            tile_scores<D>(tile, qop, sacc);
+            tile_softmax<D>(sacc, oacc, m_run[0], l_run[0], anc[0], kbeg + t * kKT, L, kend, t == 0, a.scale_log2, pk);
+            tile_pv<D, true>(tile + TILE / 2, pk, oacc);
+            if (fav) __builtin_amdgcn_s_setprio(0); else __builtin_amdgcn_s_setprio(1);
+            if (t + 1 < ntiles) {
+                tile_scores<D>(tile + TILE, qop, sacc);
+                tile_softmax<D>(sacc, oacc, m_run[0], l_run[0], anc[0], kbeg + (t + 1) * kKT, L, kend, false, a.scale_log2, pk);
+                tile_pv<D, true>(tile + TILE + TILE / 2, pk, oacc);
+            }
+        }
+    }
+    __builtin_amdgcn_s_setprio(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // nothing may still be on its way into LDS at the end
     if (!active) return;
     gs_finish<D>(a, [&](int db, int r) { return oacc[db][0][r]; }, m_run[0], l_run[0], b, h, i, nn, sp, nsplit);
 }
@@ -585,6 +733,15 @@ extern "C" size_t radar_tree_attention_workspace_bytes(const radar_attn_desc *d)
 template <int D>
 constexpr int gs_smem_bytes() { return 2 * (2 * kKT * D * 2) + RADAR_T_MAX * 4; }
 
+template <int D>
+static hipError_t launch_ld(const AttnArgs &a, dim3 grid, hipStream_t s) {
+    constexpr int bytes = kLdBufs * (2 * kKT * D * 2) + RADAR_T_MAX * 4;
+    static const hipError_t configured = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_ld_kernel<D>),
+                                                             hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (configured != hipSuccess) return configured;
+    return launch("tree_attn_group_share", tree_attn_ld_kernel<D>, grid, dim3(kGsThreads), bytes, s, a);
+}
+
 template <int D, bool DEEP>
 static hipError_t launch_gs(const AttnArgs &a, dim3 grid, hipStream_t s) {
     // the dynamic LDS limit is raised once per instantiation (a function-local static is initialised
@@ -643,7 +800,7 @@ extern "C" radar_status radar_tree_attention(const void *q, const void *k_cache,
     const dim3 grid((unsigned)a.max_splits, (unsigned)(a.Hkv * a.n_ublk), (unsigned)a.B);
     {
         hipError_t e;
-        if (p.kps >= 8 * kKT) e = d->D == 128 ? launch_gs<128, true>(a, grid, s) : launch_gs<64, true>(a, grid, s);
+        if (p.kps >= 8 * kKT) e = d->D == 128 ? launch_ld<128>(a, grid, s) : launch_gs<64, true>(a, grid, s);
         else                  e = d->D == 128 ? launch_gs<128, false>(a, grid, s) : launch_gs<64, false>(a, grid, s);
         if (e != hipSuccess) return RADAR_HIP_ERROR;
     }
