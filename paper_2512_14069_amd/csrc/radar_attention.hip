@@ -376,8 +376,11 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
 
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int sp = blockIdx.x;
-    const int hk = blockIdx.y / a.n_ublk, ublk = blockIdx.y % a.n_ublk;
-    const int b = blockIdx.z;
+    // The blocks of units that share a range of cache rows are ranges x KV heads apart in workgroup number:
+    // a multiple of eight with eight KV heads, and consecutive numbers go to consecutive XCDs, so the
+    // blocks meet in one XCD's L2 and their rows come from HBM once.
+    const int hk = blockIdx.y, ublk = blockIdx.z % a.n_ublk;
+    const int b = blockIdx.z / a.n_ublk;
     const int L = a.ctx_lens[b];
     int nn = a.n_nodes ? a.n_nodes[b] : a.T;
     nn = max(1, min(nn, a.T));
@@ -510,8 +513,11 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_ld_kernel(AttnArgs a) {
 
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int sp = blockIdx.x;
-    const int hk = blockIdx.y / a.n_ublk, ublk = blockIdx.y % a.n_ublk;
-    const int b = blockIdx.z;
+    // The blocks of units that share a range of cache rows are ranges x KV heads apart in workgroup number:
+    // a multiple of eight with eight KV heads, and consecutive numbers go to consecutive XCDs, so the
+    // blocks meet in one XCD's L2 and their rows come from HBM once.
+    const int hk = blockIdx.y, ublk = blockIdx.z % a.n_ublk;
+    const int b = blockIdx.z / a.n_ublk;
     const int L = a.ctx_lens[b];
     int nn = a.n_nodes ? a.n_nodes[b] : a.T;
     nn = max(1, min(nn, a.T));
@@ -796,8 +802,8 @@ extern "C" radar_status radar_tree_attention(const void *q, const void *k_cache,
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 block(kAttnThreads);
-    if ((long)a.Hkv * a.n_ublk > 65535) return RADAR_UNSUPPORTED_SHAPE;
-    const dim3 grid((unsigned)a.max_splits, (unsigned)(a.Hkv * a.n_ublk), (unsigned)a.B);
+    if ((long)a.B * a.n_ublk > 65535) return RADAR_UNSUPPORTED_SHAPE;
+    const dim3 grid((unsigned)a.max_splits, (unsigned)a.Hkv, (unsigned)(a.B * a.n_ublk));
     {
         hipError_t e;
         if (p.kps >= 8 * kKT) e = d->D == 128 ? launch_ld<128>(a, grid, s) : launch_gs<64, true>(a, grid, s);
