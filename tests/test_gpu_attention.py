@@ -89,14 +89,20 @@ LONG_CASES = {
     "d64_two_query_blocks": shape(1, 8, 2, 64, 64, [700], [64], [8], k=10),
     "one_tile_and_root_only": shape(2, 4, 2, 128, 30, [0, 600], [30, 1], [4, 1]),
     "group_of_3_tail_of_33": shape(1, 6, 2, 128, 20, [1037], [20], [4]),
+    # two blocks of units per range of cache rows (16 units), which sit a multiple of 8 apart in the grid
+    "group_of_8_two_unit_blocks": shape(2, 16, 2, 128, 64, [1500, 700], [64, 50], [8, 8], k=10),
+    # a cache that ends exactly at a tile (and range) boundary, and one row over it
+    "aligned_end_and_one_row_over": shape(2, 4, 1, 128, 40, [984, 985], [40, 40], [5, 5]),
 }
 
 
 @pytest.mark.parametrize("kps", [512, 1024, 2048])
 @pytest.mark.parametrize("name", list(LONG_CASES))
 def test_long_ranges_match_oracle(oracle, name, kps):
-    """Ranges of eight tiles or more run the software-pipelined kernel: ranges that end after one, two
-    or several tiles, tree rows that straddle a tile or a range boundary, a single range (no merge)."""
+    """Ranges of eight tiles or more run the long-range kernels (tiles loaded straight into LDS and taken
+    in pairs at D = 128, two-ahead register staging at D = 64): ranges that end after one, two or several
+    tiles, an odd and an even number of tiles, tree rows that straddle a tile or a range boundary, a
+    single range (no merge), wavefronts without a unit."""
     from paper_2512_14069_amd import binding as b
     a = LONG_CASES[name]
     x = synth.attention_inputs(a, seed=synth.seed_for(1, 7 * len(name) + kps // 512), shuffle=True)
@@ -161,6 +167,30 @@ def test_strided_views_and_scale(oracle):
                                  dev(x["n_nodes"]), softmax_scale=0.05)
     torch.cuda.synchronize()
     check_close(bf16_bits(out), ref, "strided")
+
+
+def test_long_range_strided_cache(oracle):
+    """Long ranges over caches with a padded row pitch and a padded head pitch (the row-to-LDS loads
+    compute their own addresses from the strides)."""
+    from paper_2512_14069_amd import binding as b
+    a = shape(2, 8, 2, 128, 33, [1200, 640], [33, 9], [6, 3])
+    x = synth.attention_inputs(a, seed=11, shuffle=True)
+    ref, ref_lse = oracle.tree_attention(x["q"], x["k_cache"], x["v_cache"], x["parents"], x["ctx_lens"], x["n_nodes"],
+                                         want_lse=True)
+    S = x["k_cache"].shape[2]
+    kbuf = torch.full((2, 2, S + 5, 136), 9.0, dtype=torch.bfloat16, device="cuda")
+    vbuf = torch.full((2, 2, S + 5, 136), -9.0, dtype=torch.bfloat16, device="cuda")
+    kbuf[:, :, :S, :128] = bf16_dev(x["k_cache"]); vbuf[:, :, :S, :128] = bf16_dev(x["v_cache"])
+    for kps in (512, 1024):
+        lse = torch.zeros((2, 33, 8), dtype=torch.float32, device="cuda")
+        out = b.radar_tree_attention(bf16_dev(x["q"]), kbuf[:, :, :S, :128], vbuf[:, :, :S, :128], dev(x["parents"]),
+                                     dev(x["ctx_lens"]), dev(x["n_nodes"]), lse_out=lse, keys_per_split=kps)
+        torch.cuda.synchronize()
+        got = bf16_bits(out)
+        for bb in range(a.B):
+            n = a.n_nodes[bb]
+            check_close(got[bb, :n], ref[bb, :n], f"strided long b={bb} kps={kps}")
+            assert np.max(np.abs(host(lse)[bb, :n] - ref_lse[bb, :n])) < LSE_TOL
 
 
 def whole_config_check(oracle, b, a, seed):
