@@ -480,27 +480,58 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
 // whose values the result depends on anyway (0 * finite = 0).
 constexpr int kLdBufs = 4;
 
+// A lane's share of a tile: two chunks of K and two of V.  Wavefront w loads the row groups 2w and
+// 2w + 1 (four rows, 1 KB each); the lane's 16 bytes land at the group's LDS base + 16 * lane, i.e. in
+// slot lane % 16 of row 4 * group + lane / 16, so it fetches the chunk that the swizzle puts there.
+// The byte offsets inside a tile are fixed for the kernel's lifetime.
+struct LdLane {
+    uint32_t offk[2], offv[2];        // from the tile's first row, rows kv_ss elements apart
+};
+
 template <int D>
-__device__ __forceinline__ void ld_issue_tile(unsigned char *buf, const __bf16 *kbase, const __bf16 *vbase, int kv_ss, int t0,
-                                              int kend, int w, int lane) {
+__device__ __forceinline__ LdLane ld_lane_offsets(int kv_ss, int w, int lane) {
     static_assert(D == 128, "1 KB per instruction = four 256-byte rows");
-    // Issued as assembly: told about loads that write LDS, the compiler waits for all of them before
-    // the next LDS read it cannot tell apart from their targets, which would undo the run-ahead.  The
-    // waits for these loads are the explicit ones in the kernel's loop.
-    // (m0 is a reserved register: the compiler sets it right before each of its own uses and warns about the clobber)
-    auto lds_load16 = [](const __bf16 *g, unsigned char *dst) {
-        const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)dst);
-        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(base), "v"(g) : "memory", "m0");
-    };
+    LdLane o;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-        const int rg = 2 * w + i;                                   // wave-uniform group of four rows
-        const int row = 4 * rg + (lane >> 4), slot = lane & 15;
-        const uint32_t rowoff = (uint32_t)(min(t0 + row, kend - 1) * kv_ss);
-        const __bf16 *gk = kbase + rowoff + ((slot ^ (row & 15)) << 3);           // inverse of ks_off's swizzle
-        const __bf16 *gv = vbase + rowoff + ((slot ^ ((row & 3) << 2)) << 3);     // inverse of vs_off's
-        lds_load16(gk, buf + rg * 1024);
-        lds_load16(gv, buf + kKT * D * 2 + rg * 1024);
+        const int row = 4 * (2 * w + i) + (lane >> 4), slot = lane & 15;
+        o.offk[i] = (uint32_t)(row * kv_ss) * 2 + (uint32_t)((slot ^ (row & 15)) << 4);          // inverse of ks_off's swizzle
+        o.offv[i] = (uint32_t)(row * kv_ss) * 2 + (uint32_t)((slot ^ ((row & 3) << 2)) << 4);    // inverse of vs_off's
+    }
+    return o;
+}
+
+// Issues this wavefront's four loads of the tile whose first cache row is t0 into the buffer `buf`.
+// Issued as assembly: told about loads that write LDS, the compiler waits for all of them before the
+// next LDS read it cannot tell apart from their targets, which would undo the run-ahead; the waits for
+// these loads are the explicit ones in the kernel's loop.  (m0 is a reserved register: the compiler
+// sets it right before each of its own uses and warns about the clobber.)  A tile inside the range
+// takes a scalar base and the lane's fixed offsets, no vector arithmetic; a tile that reaches past the
+// end of the range clamps every row to the range's last one.
+template <int D>
+__device__ __forceinline__ void ld_issue_tile(unsigned char *buf, const __bf16 *kbase, const __bf16 *vbase, int kv_ss, int t0,
+                                              int kend, int w, int lane, const LdLane &o) {
+    // (the wavefront's number is the same in every lane, which the compiler cannot see: the LDS bases below have to be scalars)
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)buf + (uint32_t)w * 2048);
+    if (t0 + kKT <= kend) {                                          // wave-uniform
+        const __bf16 *kt = kbase + (uint32_t)(t0 * kv_ss), *vt = vbase + (uint32_t)(t0 * kv_ss);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint32_t ldsk = lds0 + i * 1024, ldsv = ldsk + kKT * D * 2;
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(ldsk), "v"(o.offk[i]), "s"(kt) : "memory", "m0");
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(ldsv), "v"(o.offv[i]), "s"(vt) : "memory", "m0");
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int row = 4 * (2 * w + i) + (lane >> 4), slot = lane & 15;
+            const uint32_t rowoff = (uint32_t)(min(t0 + row, kend - 1) * kv_ss);
+            const __bf16 *gk = kbase + rowoff + ((slot ^ (row & 15)) << 3);
+            const __bf16 *gv = vbase + rowoff + ((slot ^ ((row & 3) << 2)) << 3);
+            const uint32_t ldsk = lds0 + i * 1024, ldsv = ldsk + kKT * D * 2;
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(ldsk), "v"(gk) : "memory", "m0");
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(ldsv), "v"(gv) : "memory", "m0");
+        }
     }
 }
 
@@ -550,8 +581,9 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_ld_kernel(AttnArgs a) {
             qop[st] = __builtin_bit_cast(bf16x8, raw);
         }
     }
-    ld_issue_tile<D>(smem, kbase, vbase, kv_ss, kbeg, kend, w, lane);
-    ld_issue_tile<D>(smem + TILE, kbase, vbase, kv_ss, kbeg + kKT, kend, w, lane);
+    const LdLane ldo = ld_lane_offsets<D>(kv_ss, w, lane);
+    ld_issue_tile<D>(smem, kbase, vbase, kv_ss, kbeg, kend, w, lane, ldo);
+    ld_issue_tile<D>(smem + TILE, kbase, vbase, kv_ss, kbeg + kKT, kend, w, lane, ldo);
     __syncthreads();                                     // the parents are in LDS
     uint64_t anc[1];
     anc[0] = (kend > L && i < nn) ? ancestor_word(s_par, i) : 0ull;
@@ -579,8 +611,8 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_ld_kernel(AttnArgs a) {
     for (int t = 0; t < ntiles; t += 2) {
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
         const int half = (t >> 1) & 1;                                     // this pair sits in buffers 2*half, 2*half + 1
-        ld_issue_tile<D>(smem + (2 - 2 * half) * TILE, kbase, vbase, kv_ss, kbeg + (t + 2) * kKT, kend, w, lane);
-        ld_issue_tile<D>(smem + (3 - 2 * half) * TILE, kbase, vbase, kv_ss, kbeg + (t + 3) * kKT, kend, w, lane);
+        ld_issue_tile<D>(smem + (2 - 2 * half) * TILE, kbase, vbase, kv_ss, kbeg + (t + 2) * kKT, kend, w, lane, ldo);
+        ld_issue_tile<D>(smem + (3 - 2 * half) * TILE, kbase, vbase, kv_ss, kbeg + (t + 3) * kKT, kend, w, lane, ldo);
         if (active) {
             const unsigned char *tile = smem + 2 * half * TILE;
             if (fav) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
