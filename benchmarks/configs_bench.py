@@ -24,6 +24,7 @@ def main():
     ap.add_argument("--reps", type=int, default=30)
     ap.add_argument("--configs", default="2,4,5")
     ap.add_argument("--modes", default="greedy,sampling", help="verify-accept modes to time (none: attention only)")
+    ap.add_argument("--attn-kps", type=int, default=0, help="cache rows per range of the attention call (0: the library's plan)")
     args = ap.parse_args()
     import numpy as np
     import torch
@@ -87,7 +88,7 @@ def main():
             kc = torch.randn((B, A.Hkv, A.S, A.D), generator=gen, device=dev).to(torch.bfloat16)
             vc = torch.randn((B, A.Hkv, A.S, A.D), generator=gen, device=dev).to(torch.bfloat16)
             sets.append((q, kc, vc))
-        desc = b.attn_desc(sets[0][0], sets[0][1])
+        desc = b.attn_desc(sets[0][0], sets[0][1], keys_per_split=args.attn_kps)
         ws = b.new_workspace(b.radar_tree_attention_workspace_bytes(desc))
         calls = [b.radar_tree_attention(q, kc, vc, parents, ctx, n_nodes, out=out, desc=desc, workspace=ws, prepared=True)
                  for q, kc, vc in sets]
@@ -102,7 +103,7 @@ def main():
                           "GBps": round((kv_bytes + qo_bytes) / k_us / 1e3, 1), "TFLOPps": round(flops / k_us / 1e6, 1),
                           "roofline": {"bound": bound, "achieved": round(ach, 1), "peak": peak,
                                        "unit": "TFLOP/s" if bound == "mfma" else "GB/s", "frac": round(ach / peak, 4)},
-                          "sets": nsets}), flush=True)
+                          "keys_per_split": args.attn_kps, "sets": nsets}), flush=True)
         del sets, calls, out, ws
         torch.cuda.empty_cache()
 
