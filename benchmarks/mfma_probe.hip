@@ -11,6 +11,10 @@
 //   mfma+valu   each MFMA followed by 7 independent v_fma_f32 in the same wavefront
 //   mfma+exp    each MFMA followed by 2 x (v_fma_f32, v_exp_f32, v_add_f32) and one more v_fma_f32
 //   split       wavefronts 0-3 run `mfma`, wavefronts 4-7 (the other wavefront of each SIMD) run `valu`
+//   mfma+ld/2   `mfma`, and every second repetition each wavefront loads 1 KB from global memory straight
+//               into LDS (global_load_lds_dwordx4), streaming through a 512 MB buffer: ~2 TB/s on the whole chip
+//   mfma+ld     the same with a load in every repetition: ~4 TB/s
+//   exp+ld      `mfma+exp` with a load in every repetition
 // Every pattern is one asm statement, so the order is the one written.  Output per pattern: core
 // cycles per repetition (median wavefront), wall time per repetition, the clock they imply, and the
 // MFMA rate of the whole launch in TFLOP/s.
@@ -38,9 +42,10 @@ struct Res { unsigned long long cyc, wall; float sink; int role; };
 #define EXP7 E1("%[x0]", "%[x1]", "%[x2]") E1("%[x3]", "%[x4]", "%[x5]") F1("%[x6]")
 #define MF(acc) "v_mfma_f32_32x32x16_bf16 " acc ", %[a], %[b], " acc "\n\t"
 
-// PAT: 0 mfma, 1 valu, 2 mfma+valu, 3 mfma+exp, 4 split by wavefront
-template <int PAT>
-__global__ __launch_bounds__(512) void probe(Res *out, int N, float seed) {
+// PAT: 0 mfma, 1 valu, 2 mfma+valu, 3 mfma+exp, 4 split by wavefront; LD: a load every LD-th repetition (0: none)
+template <int PAT, int LD>
+__global__ __launch_bounds__(512) void probe(Res *out, int N, float seed, const unsigned char *stream, size_t stream_bytes) {
+    __shared__ __attribute__((aligned(16))) unsigned char landing[8 * 4 * 1024];      // four 1 KB slots per wavefront
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     floatx16 acc0, acc1, acc2, acc3;
     for (int r = 0; r < 16; ++r) { acc0[r] = seed; acc1[r] = seed * 2; acc2[r] = seed * 3; acc3[r] = seed * 4; }
@@ -49,9 +54,20 @@ __global__ __launch_bounds__(512) void probe(Res *out, int N, float seed) {
     float x0 = seed, x1 = seed * 0.5f, x2 = 0.f, x3 = seed * 0.25f, x4 = seed * 0.125f, x5 = 0.f, x6 = seed * 0.3f;
     const float c = 0.999f;
     const int role = PAT == 4 ? (w < 4 ? 0 : 1) : PAT;
+    // each wavefront streams through its own slice of the buffer and wraps around
+    const size_t nwaves = (size_t)gridDim.x * 8, slice = (stream_bytes / nwaves) & ~size_t(1023);
+    const unsigned char *mine = stream + ((size_t)blockIdx.x * 8 + w) * slice + lane * 16;
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)landing + (uint32_t)w * 4096);
+    size_t pos = 0;
     __syncthreads();
     const unsigned long long t0 = clock64(), w0 = wall_clock64();
     for (int i = 0; i < N; ++i) {
+        if (LD > 0 && i % LD == 0) {
+            const uint32_t dst = lds0 + ((uint32_t)(i / LD) & 3u) * 1024;
+            asm volatile("s_waitcnt vmcnt(3)\n\ts_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(mine + pos) : "memory", "m0");
+            pos += 1024;
+            if (pos >= slice) pos = 0;
+        }
         if (role == 0) {
             asm volatile(MF("%[a0]") MF("%[a1]") MF("%[a2]") MF("%[a3]") MF("%[a0]") MF("%[a1]") MF("%[a2]") MF("%[a3]")
                          MF("%[a0]") MF("%[a1]") MF("%[a2]") MF("%[a3]") MF("%[a0]") MF("%[a1]") MF("%[a2]") MF("%[a3]")
@@ -80,7 +96,8 @@ __global__ __launch_bounds__(512) void probe(Res *out, int N, float seed) {
         }
     }
     // the accumulators are read here: the last MFMAs have finished before the clock is
-    float sink = acc0[0] + acc1[1] + acc2[2] + acc3[3] + x0 + x1 + x2 + x3 + x4 + x5 + x6;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    float sink = acc0[0] + acc1[1] + acc2[2] + acc3[3] + x0 + x1 + x2 + x3 + x4 + x5 + x6 + (float)landing[threadIdx.x];
     asm volatile("" : "+v"(sink));
     const unsigned long long t1 = clock64(), w1 = wall_clock64();
     if (lane == 0) {
@@ -89,15 +106,15 @@ __global__ __launch_bounds__(512) void probe(Res *out, int N, float seed) {
     }
 }
 
-template <int PAT>
-static int run(const char *name, int nwg, Res *d, int N) {
+template <int PAT, int LD = 0>
+static int run(const char *name, int nwg, Res *d, int N, const unsigned char *stream = nullptr, size_t stream_bytes = 0) {
     std::vector<Res> h(nwg * 8);
     hipEvent_t e0, e1;
     CHECK(hipEventCreate(&e0)); CHECK(hipEventCreate(&e1));
-    probe<PAT><<<nwg, 512>>>(d, N / 10, 1.0f);                    // warm-up
+    probe<PAT, LD><<<nwg, 512>>>(d, N / 10, 1.0f, stream, stream_bytes);      // warm-up
     CHECK(hipDeviceSynchronize());
     CHECK(hipEventRecord(e0));
-    probe<PAT><<<nwg, 512>>>(d, N, 1.0f);
+    probe<PAT, LD><<<nwg, 512>>>(d, N, 1.0f, stream, stream_bytes);
     CHECK(hipEventRecord(e1));
     CHECK(hipDeviceSynchronize());
     float ms = 0.f;
@@ -112,8 +129,9 @@ static int run(const char *name, int nwg, Res *d, int N) {
         const bool has_mfma = role != 1;
         const int waves = (int)cyc.size();
         const double tflops = has_mfma ? (double)waves * N * 16 * 32768.0 / (ms * 1e-3) * 1e-12 : 0.0;
-        printf("%-10s %3d WGs  role %d  %4d wavefronts  %7.1f cycles/rep  %7.1f ns/rep  clock %.2f GHz  kernel %.1f us  %s%.0f TFLOP/s\n",
-               name, nwg, role, waves, c, wns, c / wns, ms * 1e3, has_mfma ? "" : "(no MFMA) ", tflops);
+        const double tbs = LD > 0 ? (double)nwg * 8 * (N / LD) * 1024.0 / (ms * 1e-3) * 1e-12 : 0.0;
+        printf("%-10s %3d WGs  role %d  %4d wavefronts  %7.1f cycles/rep  %7.1f ns/rep  clock %.2f GHz  kernel %.1f us  %s%.0f TFLOP/s  %.2f TB/s loaded\n",
+               name, nwg, role, waves, c, wns, c / wns, ms * 1e3, has_mfma ? "" : "(no MFMA) ", tflops, tbs);
     }
     return 0;
 }
@@ -122,13 +140,21 @@ int main() {
     Res *d;
     CHECK(hipMalloc(&d, sizeof(Res) * 256 * 8));
     const int N = 4000;                                           // 64000 MFMAs per wavefront: ~1 ms
+    const size_t stream_bytes = size_t(512) << 20;
+    unsigned char *stream;
+    CHECK(hipMalloc(&stream, stream_bytes));
+    CHECK(hipMemset(stream, 1, stream_bytes));
     for (int nwg : {64, 256}) {
         if (run<0>("mfma", nwg, d, N)) return 1;
         if (run<1>("valu", nwg, d, N)) return 1;
         if (run<2>("mfma+valu", nwg, d, N)) return 1;
         if (run<3>("mfma+exp", nwg, d, N)) return 1;
         if (run<4>("split", nwg, d, N)) return 1;
+        if (run<0, 2>("mfma+ld/2", nwg, d, N, stream, stream_bytes)) return 1;
+        if (run<0, 1>("mfma+ld", nwg, d, N, stream, stream_bytes)) return 1;
+        if (run<3, 1>("exp+ld", nwg, d, N, stream, stream_bytes)) return 1;
     }
+    CHECK(hipFree(stream));
     CHECK(hipFree(d));
     return 0;
 }
