@@ -26,6 +26,7 @@
 // from a cost model that counts whole rounds of resident workgroups and the
 // partial traffic.
 #include "radar_device.h"
+#include <type_traits>
 #include "radar_host.h"
 
 namespace radar {
@@ -114,18 +115,18 @@ __device__ __forceinline__ uint64_t ancestor_word(const int *par, int i) {
 // that consecutive MFMAs are independent and none starts by waiting for LDS.
 //   t0        cache row of the tile's first key;  L = prefix length;  kend = end of this range
 //   first     true if the accumulators are still zero (no rescaling needed)
-template <int D>
-__device__ __forceinline__ void tile_scores(const unsigned char *Ks, const bf16x8 (&qop)[D / 16], floatx16 (&sacc)[2]) {
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+typedef const __attribute__((address_space(3))) u32x4 *lds_u32x4;
+
+// kaddr(k): where step k's K operand sits in LDS (sub-tile k % 2, 16-byte chunk 2 * (k / 2) + g2 of row j32)
+template <int D, typename KAddr>
+__device__ __forceinline__ void tile_scores(KAddr kaddr, const bf16x8 (&qop)[D / 16], floatx16 (&sacc)[2]) {
     constexpr int KSTEPS = D / 16, NS = 2 * KSTEPS, kAhead = 4;
-    const int lane = lane_id();
-    const int j32 = lane & 31, g2 = lane >> 5;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
         for (int r = 0; r < 16; ++r) sacc[sub][r] = 0.f;
-    auto kread = [&](int k) {
-        return *reinterpret_cast<const u32x4 *>(Ks + ks_off<D>(32 * (k & 1) + j32, 2 * (k >> 1) + g2));
-    };
+    auto kread = [&](int k) { return *kaddr(k); };
     u32x4 kf[kAhead];
 #pragma unroll
     for (int k = 0; k < kAhead; ++k) kf[k] = kread(k);
@@ -195,11 +196,11 @@ __device__ __forceinline__ void tile_softmax(floatx16 (&sacc)[2], floatx16 (&oac
     l_run += rs;
 }
 
-template <int D, bool VTR>
-__device__ __forceinline__ void tile_pv(const unsigned char *Vs, const bf16x8 (&pk)[2][2], floatx16 (&oacc)[D / 32][1]) {
+// vaddr(k, hi): VTR = false: where step k's V^T operand sits (16 bytes; hi unused); VTR = true: the 8-byte
+// piece this lane names for the first (hi = 0) or second (hi = 1) transposing read of step k
+template <int D, bool VTR, typename VAddr>
+__device__ __forceinline__ void tile_pv(VAddr vaddr, const bf16x8 (&pk)[2][2], floatx16 (&oacc)[D / 32][1]) {
     constexpr int DB = D / 32, NP = 4 * DB, kAhead = 4;
-    const int lane = lane_id();
-    const int j32 = lane & 31, g2 = lane >> 5;
     // V^T operand straight from the row-major tile, by two transposing LDS reads.  In each block of 16
     // lanes, lane 4j+q names an 8-byte piece (row kv0+j, elements 4q..4q+3 of the block's 16) and lane l
     // receives element l%4 of the pieces named by lanes 4j + l/4, j = 0..3: its own d for four
@@ -208,16 +209,11 @@ __device__ __forceinline__ void tile_pv(const unsigned char *Vs, const bf16x8 (&
     typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
     typedef bf16x4_t __attribute__((address_space(3))) *lds_b64;
     auto vread = [&](int k) {
-        const int db = k % DB, ss = k / DB;                          // ss = 2 * sub + s2
         if constexpr (!VTR) {
-            return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(Vs + vt_off(32 * db + j32, 16 * ss + 8 * g2)));
+            return __builtin_bit_cast(bf16x8, *(lds_u32x4)vaddr(k, 0));
         } else {
-            const int d0 = 32 * db + (j32 & 16) + 4 * (lane & 3);
-            const int kv0 = 16 * ss + 4 * g2 + ((lane >> 2) & 3);
-            const unsigned char *va = Vs + vs_off<D>(kv0, d0 >> 3) + (d0 & 7) * 2;
-            const unsigned char *vb = Vs + vs_off<D>(kv0 + 8, d0 >> 3) + (d0 & 7) * 2;
-            const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64)va);
-            const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64)vb);
+            const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64)vaddr(k, 0));
+            const bf16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64)vaddr(k, 1));
             return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         }
     };
@@ -442,9 +438,11 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
         if (active) {
             floatx16 sacc[2];
             bf16x8 pk[2][2];
-            tile_scores<D>(cur, qop, sacc);
+            const unsigned char *Vt = cur + TILE / 2;
+            tile_scores<D>([&](int k) { return (lds_u32x4)(cur + ks_off<D>(32 * (k & 1) + j32, 2 * (k >> 1) + g2)); }, qop, sacc);
             tile_softmax<D>(sacc, oacc, m_run[0], l_run[0], anc[0], kbeg + t * kKT, L, kend, t == 0, a.scale_log2, pk);
-            tile_pv<D, false>(cur + TILE / 2, pk, oacc);
+            tile_pv<D, false>([&](int k, int) { return (const lds_byte *)(Vt + vt_off(32 * (k % DB) + j32, 16 * (k / DB) + 8 * g2)); },
+                              pk, oacc);
         }
         if (t + 1 < ntiles) {
             gs_store_tile<D>(next_regs, nxt, nxt + TILE / 2, kbeg + (t + 1) * kKT, kend, tid);
@@ -605,8 +603,32 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_ld_kernel(AttnArgs a) {
     // tile and finishes it a third ahead of the other; taking turns measured 3-4 % faster at 16 K
     // cached rows.  (A barrier per pair without the priorities is slower than one per tile, and
     // priorities with a barrier per tile change nothing.)
+    // Operand addresses: a lane's are the same in every tile up to the tile's place in LDS, so they are
+    // kept in registers (eight for K: the XOR swizzle is not additive in the chunk; four for V) and the
+    // sub-tile, the step inside the tile and the second tile of a pair are instruction offsets; only the
+    // pair's own 64 KB step is added, once per pair.  (Recomputed per tile, as the compiler does when
+    // handed a tile pointer, they were a quarter of the loop's vector instructions.)
+    const lds_byte *ka[D / 16], *va[DB];
+    {
+        const lds_byte *base = (const lds_byte *)smem;
+#pragma unroll
+        for (int st = 0; st < D / 16; ++st) ka[st] = base + ks_off<D>(j32, 2 * st + g2);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const int d0 = 32 * db + (j32 & 16) + 4 * (lane & 3), kv0 = 4 * g2 + ((lane >> 2) & 3);
+            va[db] = base + TILE / 2 + vs_off<D>(kv0, d0 >> 3) + (d0 & 7) * 2;
+        }
+    }
     floatx16 sacc[2];
     bf16x8 pk[2][2];
+    auto run_tile = [&](auto second, int t0, bool first) {
+        constexpr int TOFF = decltype(second)::value ? TILE : 0;
+        // sub-tile k % 2: 32 rows on, the same swizzle (32 is a multiple of 16)
+        tile_scores<D>([&](int k) { return (lds_u32x4)(ka[k >> 1] + TOFF + (k & 1) * (32 * D * 2)); }, qop, sacc);
+        tile_softmax<D>(sacc, oacc, m_run[0], l_run[0], anc[0], t0, L, kend, first, a.scale_log2, pk);
+        // step k: output block k % DB, rows 16 * (k / DB) on (a multiple of 4: the same swizzle), hi: 8 rows on
+        tile_pv<D, true>([&](int k, int hi) { return va[k % DB] + TOFF + (k / DB) * (16 * D * 2) + hi * (8 * D * 2); }, pk, oacc);
+    };
     const int fav = w < kGsWaves / 2 ? 1 : 0;
     for (int t = 0; t < ntiles; t += 2) {
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -614,18 +636,16 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_ld_kernel(AttnArgs a) {
         ld_issue_tile<D>(smem + (2 - 2 * half) * TILE, kbase, vbase, kv_ss, kbeg + (t + 2) * kKT, kend, w, lane, ldo);
         ld_issue_tile<D>(smem + (3 - 2 * half) * TILE, kbase, vbase, kv_ss, kbeg + (t + 3) * kKT, kend, w, lane, ldo);
         if (active) {
-            const unsigned char *tile = smem + 2 * half * TILE;
             if (fav) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
-            tile_scores<D>(tile, qop, sacc);
-            tile_softmax<D>(sacc, oacc, m_run[0], l_run[0], anc[0], kbeg + t * kKT, L, kend, t == 0, a.scale_log2, pk);
-            tile_pv<D, true>(tile + TILE / 2, pk, oacc);
+            run_tile(std::false_type{}, kbeg + t * kKT, t == 0);
             if (fav) __builtin_amdgcn_s_setprio(0); else __builtin_amdgcn_s_setprio(1);
-            if (t + 1 < ntiles) {
-                tile_scores<D>(tile + TILE, qop, sacc);
-                tile_softmax<D>(sacc, oacc, m_run[0], l_run[0], anc[0], kbeg + (t + 1) * kKT, L, kend, false, a.scale_log2, pk);
-                tile_pv<D, true>(tile + TILE + TILE / 2, pk, oacc);
-            }
+            if (t + 1 < ntiles) run_tile(std::true_type{}, kbeg + (t + 1) * kKT, false);
         }
+        const int step = half ? -2 * TILE : 2 * TILE;                     // the next pair sits in the other two buffers
+#pragma unroll
+        for (int st = 0; st < D / 16; ++st) ka[st] += step;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) va[db] += step;
     }
     __builtin_amdgcn_s_setprio(0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // nothing may still be on its way into LDS at the end
