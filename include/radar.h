@@ -25,7 +25,11 @@
  *   - A call validates what the host can see, enqueues its kernels on `stream`
  *     (a hipStream_t passed as void*; NULL = the default stream) and returns
  *     without synchronising.  Outputs are valid once the stream has reached
- *     the end of the enqueued work.
+ *     the end of the enqueued work.  A call consists of kernel launches
+ *     only, so it may be made on a stream that is being captured into a HIP
+ *     graph (radar_workspace_init stays outside the capture; make each entry
+ *     point's first call on a device outside a capture as well: it sets the
+ *     kernels' launch attributes).
  *   - No call allocates or frees memory.  Scratch memory is a caller-owned
  *     device workspace whose size the matching *_workspace_bytes query gives.
  *     A workspace must be passed once through radar_workspace_init before its
