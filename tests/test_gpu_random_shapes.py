@@ -59,6 +59,40 @@ def test_attention_random_shapes(oracle, seed):
         assert np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30) <= 1e-2
 
 
+@pytest.mark.parametrize("seed", range(8 + EXTRA))
+def test_attention_random_long_ranges(oracle, seed):
+    """Ranges of eight tiles or more (the long-range kernels): random group sizes, tree sizes, context
+    lengths that end anywhere inside a tile, an odd or even number of tiles per range, one or two ranges."""
+    from paper_2512_14069_amd import binding as b
+    rng = np.random.default_rng(synth.seed_for(57, seed))
+    B = int(rng.integers(1, 3))
+    Hkv = int(rng.integers(1, 3))
+    G = int(rng.choice([1, 2, 3, 4, 5, 8]))
+    D = int(rng.choice([128, 128, 128, 64]))
+    T = int(rng.integers(1, 65))
+    ctx = [int(rng.integers(450, 2300)) for _ in range(B)]
+    nn = [int(rng.integers(1, T + 1)) for _ in range(B)]
+    nn[0] = T
+    S = max(c + n for c, n in zip(ctx, nn)) + int(rng.integers(0, 70))
+    q = synth.normal_bf16(rng, (B, T, Hkv * G, D))
+    kc = synth.normal_bf16(rng, (B, Hkv, S, D))
+    vc = synth.normal_bf16(rng, (B, Hkv, S, D))
+    parents = np.full((B, T), -1, np.int32)
+    for i in range(B):
+        parents[i, :nn[i]] = rand_tree(rng, nn[i], 4, 1000)[0]
+    ctx_a, nn_a = np.array(ctx, np.int32), np.array(nn, np.int32)
+    ref = synth.bf16_bits_to_f32(oracle.tree_attention(q, kc, vc, parents, ctx_a, nn_a)).astype(np.float64)
+    for kps in (512, 1024):
+        out = b.radar_tree_attention(bf16_dev(q), bf16_dev(kc), bf16_dev(vc), dev(parents), dev(ctx_a), dev(nn_a),
+                                     keys_per_split=kps)
+        torch.cuda.synchronize()
+        got = synth.bf16_bits_to_f32(bf16_bits(out)).astype(np.float64)
+        assert np.all(np.isfinite(got)), (seed, kps)
+        assert np.abs(got - ref).max() <= 2e-2, (seed, kps, B, Hkv, G, D, T)
+        assert np.all(np.abs(got - ref) <= 6e-3 + 8e-3 * np.abs(ref)), (seed, kps)
+        assert np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30) <= 1e-2
+
+
 @pytest.mark.parametrize("seed", range(16 + EXTRA))
 def test_expand_random_shapes(oracle, seed):
     from paper_2512_14069_amd import binding as b
