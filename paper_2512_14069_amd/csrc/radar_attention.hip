@@ -512,7 +512,14 @@ __device__ __forceinline__ void ld_issue_tile(unsigned char *buf, const __bf16 *
     // (the wavefront's number is the same in every lane, which the compiler cannot see: the LDS bases below have to be scalars)
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)buf + (uint32_t)w * 2048);
     if (t0 + kKT <= kend) {                                          // wave-uniform
-        const __bf16 *kt = kbase + (uint32_t)(t0 * kv_ss), *vt = vbase + (uint32_t)(t0 * kv_ss);
+        // (the tile bases are the same in every lane; passed through readfirstlane so that they are scalars
+        // for the assembly below whatever the compiler knows about their uniformity)
+        auto scalar_ptr = [](const __bf16 *p) {
+            const uint64_t v = (uint64_t)(uintptr_t)p;
+            const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+            return (const __bf16 *)(uintptr_t)(((uint64_t)hi << 32) | lo);
+        };
+        const __bf16 *kt = scalar_ptr(kbase + (uint32_t)(t0 * kv_ss)), *vt = scalar_ptr(vbase + (uint32_t)(t0 * kv_ss));
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const uint32_t ldsk = lds0 + i * 1024, ldsv = ldsk + kKT * D * 2;
@@ -568,6 +575,11 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_ld_kernel(AttnArgs a) {
     const int kv_ss = (int)a.kv_ss;          // 32-bit offsets inside one head's cache (checked on the host)
     const int ntiles = (kend - kbeg + kKT - 1) / kKT;
 
+    // the first two tiles are requested before anything else: the query rows below are consumed as soon as
+    // they arrive, and loads issued behind that wait would start a memory round trip late
+    const LdLane ldo = ld_lane_offsets<D>(kv_ss, w, lane);
+    ld_issue_tile<D>(smem, kbase, vbase, kv_ss, kbeg, kend, w, lane, ldo);
+    ld_issue_tile<D>(smem + TILE, kbase, vbase, kv_ss, kbeg + kKT, kend, w, lane, ldo);
     if (tid < RADAR_T_MAX) s_par[tid] = a.parents[(size_t)b * a.T + min(tid, nn - 1)];
     bf16x8 qop[D / 16];                                  // row i, d = 16*st + 8*g2 .. +8, for the whole kernel
     {
@@ -579,9 +591,6 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_ld_kernel(AttnArgs a) {
             qop[st] = __builtin_bit_cast(bf16x8, raw);
         }
     }
-    const LdLane ldo = ld_lane_offsets<D>(kv_ss, w, lane);
-    ld_issue_tile<D>(smem, kbase, vbase, kv_ss, kbeg, kend, w, lane, ldo);
-    ld_issue_tile<D>(smem + TILE, kbase, vbase, kv_ss, kbeg + kKT, kend, w, lane, ldo);
     __syncthreads();                                     // the parents are in LDS
     uint64_t anc[1];
     anc[0] = (kend > L && i < nn) ? ancestor_word(s_par, i) : 0ull;
