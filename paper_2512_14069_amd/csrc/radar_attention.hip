@@ -377,14 +377,7 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
     // blocks meet in one XCD's L2 and their rows come from HBM once.
     const int hk = blockIdx.y, ublk = blockIdx.z % a.n_ublk;
     const int b = blockIdx.z / a.n_ublk;
-    const int L = a.ctx_lens[b];
-    int nn = a.n_nodes ? a.n_nodes[b] : a.T;
-    nn = max(1, min(nn, a.T));
-    const int total = min(L + nn, a.S);                  // never read past the cache the caller described
-    const int kbeg = sp * a.kps;
-    if (L < 0 || kbeg >= total) return;
-    const int kend = min(total, kbeg + a.kps);
-    const int nsplit = (total + a.kps - 1) / a.kps;
+    const int kbeg = sp * a.kps;                          // < S: the grid has ceil(S / kps) ranges
 
     const int u = ublk * kGsWaves + w;                    // (head within the group, block of 32 rows)
     const int g = u / a.nqb, qb = u % a.nqb;
@@ -397,13 +390,16 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
     const __bf16 *vbase = a.v + (size_t)b * a.kv_sb + (size_t)hk * a.kv_sh;
     const int kv_ss = (int)a.kv_ss;          // 32-bit offsets inside one head's cache (checked on the host)
 
-    const int ntiles = (kend - kbeg + kKT - 1) / kKT;
+    // The first tile and the query rows are requested before the sequence's context length and tree size
+    // are known (two dependent scalar loads, most of a microsecond in a cold start): rows are clamped to
+    // the cache the caller described instead of to the end of the range.  Whatever rows past that end
+    // hold is never used: their scores are masked by selection and their V rows zeroed on the way into
+    // LDS, both from the range's real end below.
     // DEEP (ranges of many tiles): staging runs two tiles ahead through two register sets, which hides
     // HBM latency better but doubles the loop's code; short ranges keep the compact one-ahead loop
     // (their time goes into a cold start, where code size counts).
     GsTileRegs<D> regs0, regs1;
-    gs_load_tile<D>(regs0, kbase, vbase, kv_ss, kbeg, kend, tid);
-    if (DEEP) gs_load_tile<D>(regs1, kbase, vbase, kv_ss, kbeg + kKT, kend, tid);
+    gs_load_tile<D>(regs0, kbase, vbase, kv_ss, kbeg, a.S, tid);
     // this lane's query operands, kept in registers for the whole kernel: row i, d = 16*st + 8*g2 .. +8
     bf16x8 qop[D / 16];
     {
@@ -415,6 +411,15 @@ __global__ __launch_bounds__(kGsThreads) void tree_attn_gs_kernel(AttnArgs a) {
             qop[st] = __builtin_bit_cast(bf16x8, raw);
         }
     }
+    const int L = a.ctx_lens[b];
+    int nn = a.n_nodes ? a.n_nodes[b] : a.T;
+    nn = max(1, min(nn, a.T));
+    const int total = min(L + nn, a.S);                  // never read past the cache the caller described
+    if (L < 0 || kbeg >= total) return;
+    const int kend = min(total, kbeg + a.kps);
+    const int nsplit = (total + a.kps - 1) / a.kps;
+    const int ntiles = (kend - kbeg + kKT - 1) / kKT;
+    if (DEEP) gs_load_tile<D>(regs1, kbase, vbase, kv_ss, kbeg + kKT, kend, tid);
     if (tid < RADAR_T_MAX) s_par[tid] = a.parents[(size_t)b * a.T + min(tid, nn - 1)];
     gs_store_tile<D>(regs0, smem, smem + TILE / 2, kbeg, kend, tid);
     __syncthreads();
